@@ -1,0 +1,101 @@
+"""Pins for the packed layout and the matrix-level dequant: brute force on tiny
+inputs, walking-one patterns, an independent numpy packer, index-sensitive
+matrices."""
+import numpy as np
+import pytest
+
+import oracle
+import np_reference as ref
+import workloads
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_pack_unpack_roundtrip_and_numpy_packer(bits):
+    rng = np.random.default_rng(bits)
+    N, K = 5, 256
+    codes = rng.integers(0, 2 ** bits, size=(N, K), dtype=np.uint8)
+    p = oracle.pack_codes(codes, bits)
+    assert p.shape == (N, K * bits // 8)
+    assert np.array_equal(p, ref.pack(codes, bits))
+    assert np.array_equal(oracle.unpack_codes(p, K, bits), codes)
+    assert np.array_equal(ref.unpack(p, K, bits), codes)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_walking_one_bit_positions(bits):
+    # a single code with value v at position k sets exactly stream bits [b*k, b*k+b) (little-endian)
+    K = 64
+    for k in range(K):
+        for v in (1, 2 ** (bits - 1), 2 ** bits - 1):
+            codes = np.zeros((1, K), dtype=np.uint8)
+            codes[0, k] = v
+            p = oracle.pack_codes(codes, bits)[0]
+            stream = int.from_bytes(p.tobytes(), "little")
+            assert stream == v << (bits * k)
+
+
+def test_three_bit_codes_straddle_words():
+    # codes 10 and 21 of each 32-code block cross a 32-bit word boundary
+    codes = np.zeros((1, 32), dtype=np.uint8)
+    codes[0, 10] = 0b111
+    words = oracle.pack_codes(codes, 3).view("<u4")[0]
+    assert words[0] == 0b11 << 30 and words[1] == 0b1 and words[2] == 0
+
+
+@pytest.mark.parametrize("bits,group", [(2, 128), (3, 128), (3, 64), (4, 128)])
+def test_dequant_index_sensitive_matrix(bits, group):
+    # code(n,k) = (n + k) mod 2^b, scale(n,g) = 2^((n+g) mod 8 - 8): any index mix-up changes the result
+    N, K = 24, 512
+    n = np.arange(N)[:, None]
+    k = np.arange(K)[None, :]
+    codes = ((n + k) % 2 ** bits).astype(np.uint8)
+    g = np.arange(K // group)[None, :]
+    scales = (2.0 ** (((n + g) % 8) - 8)).astype(np.float16)
+    p = oracle.pack_codes(codes, bits)
+    out = oracle.pot_dequant(p, scales, K, bits, group).view(np.float16).astype(np.float64)
+    sign = codes >> (bits - 1)
+    E = codes & (2 ** (bits - 1) - 1)
+    want = np.where(sign == 1, -1.0, 1.0) * 2.0 ** E * np.repeat(scales.astype(np.float64), group, axis=1)
+    assert np.array_equal(out, want)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_dequant_vs_numpy_reference_on_workload_inputs(bits):
+    N, K, G = 48, 1024, 128
+    packed, scales = workloads.pot_matrix(0, 0, N, K, bits, G)
+    a = oracle.pot_dequant(packed, scales, K, bits, G)
+    b = oracle.pot_dequant(packed, scales, K, bits, G, use_bit_recipe=True)
+    c = ref.pot_dequant(packed, scales, K, bits, G).view(np.uint16)
+    assert np.array_equal(a, c) and np.array_equal(a, b)
+    assert oracle.check_scales(scales, bits) == 0
+    # invariants that hold for any in-domain input
+    s = np.repeat(scales.view(np.uint16), G, axis=1)
+    assert np.array_equal(a & 0x3FF, s & 0x3FF)
+    codes = ref.unpack(packed, K, bits)
+    assert np.array_equal(a >> 15, codes >> (bits - 1))
+    assert np.array_equal(((a >> 10) & 31).astype(int) - ((s >> 10) & 31), codes & (2 ** (bits - 1) - 1))
+    # threads do not change the result
+    assert np.array_equal(a, oracle.pot_dequant(packed, scales, K, bits, G, nthreads=4))
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_int_dequant_vs_numpy_reference(bits):
+    N, K, G = 40, 768, 128
+    packed, S, Z = workloads.int_matrix(1, 0, N, K, bits, G)
+    assert np.all(Z.astype(np.float64) == np.rint(Z.astype(np.float64)))
+    assert Z.min() >= -(2 ** bits - 1) and Z.max() <= 0
+    a = oracle.int_dequant(packed, S, Z, K, bits, G)
+    c = ref.int_dequant(packed, S, Z, K, bits, G).view(np.uint16)
+    assert np.array_equal(a, c)
+
+
+def test_workload_scale_distribution():
+    # max of 128 draws of |N(0, 0.02)|: median = 0.02 * Phi^-1((1 + 0.5^(1/128)) / 2) ~ 0.0558
+    s = workloads.pot_scales(123, 256, 128 * 64).astype(np.float64)
+    assert 0.054 < np.median(s) < 0.058
+    assert s.min() > 0.03 and s.max() < 0.13
+    # direct simulation of the same quantity agrees in distribution
+    rng = np.random.default_rng(5)
+    sim = np.abs(rng.normal(0, 0.02, size=(16384, 128))).max(axis=1)
+    assert abs(np.mean(sim) - np.mean(s)) < 4e-4
+    assert abs(np.std(sim) - np.std(s)) < 4e-4
