@@ -1,0 +1,160 @@
+/*
+ * potq.h -- C ABI of the MI355X (gfx950) power-of-two weight de-quantisation library.
+ *
+ * The library implements the inference hot path of PoT-PTQ (arXiv 2507.11959):
+ * low-bit power-of-two weight codes (one sign bit + exponent bits, one fp16
+ * scale per group of input features) are turned into fp16 weights by integer
+ * addition into the scale's exponent field, either as a stand-alone pass or
+ * fused into the GEMV / GEMM that consumes the weights.  A uniform-integer
+ * (scale + zero-point) path built to the same standard serves as baseline.
+ *
+ * Conventions for every entry point
+ * ---------------------------------
+ *  - All data pointers are DEVICE pointers (HIP global memory) unless a
+ *    parameter name ends in `_host`.  The caller owns every buffer; the library
+ *    never allocates, frees or keeps device memory and has no mutable global
+ *    state, so calls are re-entrant.
+ *  - `hip_stream` is a `hipStream_t` passed as `void*` (NULL = the null stream).
+ *    Every call only enqueues work on that stream and returns; nothing
+ *    synchronises.
+ *  - Matrices: W is N x K (N output features, K input features, nn.Linear
+ *    order).  `scales` (and `zeros`) are N x (K/group) fp16, row-major.  fp16
+ *    values are IEEE binary16 stored as 16-bit words.
+ *  - Requirements: bits in {2,3}; group in {64,128} (fused GEMV/GEMM: 128);
+ *    K a multiple of 128; every pointer 16-byte aligned; the tiled layout also
+ *    needs N to be a multiple of 16.  Sizes of zero are valid and do nothing.
+ *  - Return value: POTQ_OK or an error code; arguments are validated on the
+ *    host before anything is launched, and no entry point aborts or throws.
+ *
+ * Packed code layouts
+ * -------------------
+ *  POTQ_LAYOUT_CANONICAL  The format at the boundary.  Each row is a dense
+ *      little-endian bit stream along K: code k occupies stream bits
+ *      [bits*k, bits*k + bits); stream bit i is bit (i mod 8) of byte (i div 8);
+ *      inside a code the exponent is in the low bits-1 bits and the sign is the
+ *      top bit (Sec. 4.2, step 1(a): a 3-bit code reads S0 E1 E2).  Row stride
+ *      is K*bits/8 bytes, rows are contiguous.  Exactly `bits` bits per weight
+ *      (Table 2, "Avg Bits" = bits + 16/group).
+ *  POTQ_LAYOUT_TILE16     A kernel-native permutation of the same bits (still
+ *      exactly `bits` bits per weight, same total size) produced by
+ *      potq_repack(): 16-row x 128-column tiles stored contiguously, tile index
+ *      (n/16)*(K/128) + k/128, laid out so that one wavefront fetches a tile
+ *      with 16-byte loads per lane and so that four codes can be turned into
+ *      byte-permute selectors with one shift and one mask.  The exact bit map
+ *      is private to the library; potq_repack() converts in both directions.
+ */
+#ifndef POTQ_H
+#define POTQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    POTQ_OK = 0,
+    POTQ_ERR_NULL = 1,       /* a required pointer is NULL */
+    POTQ_ERR_BITS = 2,       /* bits not in {2,3} */
+    POTQ_ERR_GROUP = 3,      /* group size not supported by this entry point */
+    POTQ_ERR_SHAPE = 4,      /* negative size, K not a multiple of 128, N not a multiple of 16 (tiled) */
+    POTQ_ERR_ALIGN = 5,      /* a pointer is not 16-byte aligned */
+    POTQ_ERR_LAYOUT = 6,     /* layout id unknown or not supported by this entry point */
+    POTQ_ERR_LAUNCH = 7      /* the HIP runtime refused the launch */
+} potq_status;
+
+typedef enum {
+    POTQ_LAYOUT_CANONICAL = 0,
+    POTQ_LAYOUT_TILE16 = 1
+} potq_layout;
+
+/* Library version, major*100 + minor. */
+int potq_version(void);
+
+/* Static, human-readable text for a status code. */
+const char *potq_strerror(int status);
+
+/* Bytes of one canonical row: K*bits/8 (K must be a multiple of 8). */
+size_t potq_packed_row_bytes(int64_t K, int bits);
+
+/* Bytes of a whole packed N x K code matrix; identical for both layouts. */
+size_t potq_packed_bytes(int64_t N, int64_t K, int bits);
+
+/*
+ * pot_dequant -- stand-alone PoT de-quantisation (Sec. 4.2; value defined by
+ * Sec. 3.1 Eq. (1) and Sec. 4.1 Eq. (11)).
+ *   out[n,k] = bits16(scales[n, k/group]) + ((sign << 15) | (E << 10))   (16-bit integer add)
+ * which equals (-1)^sign * 2^E * scale exactly whenever the scale is a positive
+ * normal fp16 with biased exponent in [1, 30 - q_max], q_max = 2^(bits-1) - 1.
+ * Outside that domain the result is, by definition of this library, the
+ * wrap-around of that 16-bit add (pot_check_scales() finds such scales).
+ *   codes   in   canonical layout, N rows of K*bits/8 bytes
+ *   scales  in   N x (K/group) fp16
+ *   out_f16 out  N x K fp16, row-major, fully overwritten
+ */
+int pot_dequant(const void *codes, const void *scales, void *out_f16,
+                int64_t N, int64_t K, int bits, int group, void *hip_stream);
+
+/*
+ * int_dequant -- the uniform baseline (Sec. 4.1 Eq. (9)):
+ *   out[n,k] = fp16_rne( (q[n,k] + zeros[n,k/group]) * scales[n,k/group] )
+ * q is the unsigned `bits`-bit code (same canonical stream).  `zeros` holds
+ * integer-valued fp16 numbers in [-(2^bits - 1), 0]; for those the result is
+ * the exact product rounded once.  (For other zero-points q + Z is itself
+ * rounded to fp16 first.)
+ */
+int int_dequant(const void *codes, const void *scales, const void *zeros, void *out_f16,
+                int64_t N, int64_t K, int bits, int group, void *hip_stream);
+
+/*
+ * potq_repack -- permute packed codes between the two layouts (device to
+ * device, src and dst must not overlap).  to_layout = POTQ_LAYOUT_TILE16
+ * converts canonical -> tiled, POTQ_LAYOUT_CANONICAL converts tiled ->
+ * canonical.  Bijective; the code values are untouched, so it serves PoT and
+ * uniform codes alike.  N must be a multiple of 16.
+ */
+int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits,
+                int to_layout, void *hip_stream);
+
+/*
+ * pot_gemv -- fused de-quantise + matrix-vector product, batch-1 decode
+ * (the consumer of Sec. 4.2's weights: "dequantizing back to FP16 for GEMM", Sec. 1):
+ *   y[n] = fp16( sum_k W~[n,k] * x[k] ),  W~ as defined by pot_dequant,
+ * products exact, accumulation in fp32, one rounding to fp16 at the end.
+ *   x_f16 in  K fp16;   y_f16 out  N fp16
+ * `layout` names the layout `codes` is in.
+ */
+int pot_gemv(const void *codes, const void *scales, const void *x_f16, void *y_f16,
+             int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
+
+/* int_gemv -- the same with W~ as defined by int_dequant. */
+int int_gemv(const void *codes, const void *scales, const void *zeros, const void *x_f16, void *y_f16,
+             int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
+
+/*
+ * pot_gemm -- fused de-quantise + GEMM on the matrix cores:
+ *   Y[m,n] = fp16( sum_k X[m,k] * W~[n,k] ),   X: M x K fp16 row-major,
+ *   Y: M x N fp16 row-major (Y = X . W~^T, the nn.Linear convention).
+ * fp16 MFMA with fp32 accumulation.  `codes` must be in POTQ_LAYOUT_TILE16.
+ */
+int pot_gemm(const void *codes, const void *scales, const void *X_f16, void *Y_f16,
+             int64_t M, int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
+
+/* int_gemm -- the same with W~ as defined by int_dequant. */
+int int_gemm(const void *codes, const void *scales, const void *zeros, const void *X_f16, void *Y_f16,
+             int64_t M, int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
+
+/*
+ * pot_check_scales -- count the scales outside the domain on which the
+ * integer-add recipe equals the definition (not positive, subnormal or zero,
+ * exponent field above 30 - q_max, infinity, NaN).  The count is written, as
+ * one int64, to `bad_count_dev` (device memory, 8-byte aligned) on the stream;
+ * the caller copies it back.  Meant to be run once when weights are loaded.
+ */
+int pot_check_scales(const void *scales, int64_t count, int bits, void *bad_count_dev, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POTQ_H */

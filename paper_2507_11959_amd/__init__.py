@@ -1,0 +1,9 @@
+"""potq: MI355X-native power-of-two weight de-quantisation (PoT-PTQ, arXiv 2507.11959).
+
+`csrc/` holds the gfx950 HIP kernels and the C ABI (declared in include/potq.h);
+`binding` is the ctypes marshalling layer with the same entry-point names.
+"""
+from .binding import (  # noqa: F401
+    LAYOUT_CANONICAL, LAYOUT_TILE16, PotqError, int_dequant, int_gemm, int_gemv, packed_bytes, packed_row_bytes,
+    pot_check_scales, pot_dequant, pot_gemm, pot_gemv, potq_repack, strerror, version,
+)

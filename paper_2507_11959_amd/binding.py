@@ -1,0 +1,187 @@
+"""Thin ctypes binding of the potq C ABI (include/potq.h).
+
+Argument marshalling only: every function takes torch CUDA(HIP) tensors, checks
+dtype / shape / device / contiguity, and passes raw device pointers plus the
+current HIP stream to the shared library.  All computation happens in the
+library's kernels.  There is no CPU fallback: if the library has not been
+built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # loads the process's HIP runtime before libpotq.so is opened
+
+from .build import LIB_PATH
+
+LAYOUT_CANONICAL = 0
+LAYOUT_TILE16 = 1
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+        "or python paper_2507_11959_amd/build.py). There is no fallback path."
+    )
+
+_lib = ctypes.CDLL(LIB_PATH)
+_vp, _i64, _int = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+
+EXPORTS = {
+    "potq_version": (_int, []),
+    "potq_strerror": (ctypes.c_char_p, [_int]),
+    "potq_packed_row_bytes": (ctypes.c_size_t, [_i64, _int]),
+    "potq_packed_bytes": (ctypes.c_size_t, [_i64, _i64, _int]),
+    "pot_dequant": (_int, [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]),
+    "int_dequant": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _vp]),
+    "potq_repack": (_int, [_vp, _vp, _i64, _i64, _int, _int, _vp]),
+    "pot_gemv": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
+    "int_gemv": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
+    "pot_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp]),
+    "int_gemm": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp]),
+    "pot_check_scales": (_int, [_vp, _i64, _int, _vp, _vp]),
+}
+for _name, (_res, _args) in EXPORTS.items():
+    _f = getattr(_lib, _name)
+    _f.restype = _res
+    _f.argtypes = _args
+
+
+class PotqError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"potq status {status}: {_lib.potq_strerror(status).decode()}")
+
+
+def _ok(status: int) -> None:
+    if status != 0:
+        raise PotqError(status)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def version() -> int:
+    return _lib.potq_version()
+
+
+def strerror(status: int) -> str:
+    return _lib.potq_strerror(status).decode()
+
+
+def packed_row_bytes(K: int, bits: int) -> int:
+    return _lib.potq_packed_row_bytes(K, bits)
+
+
+def packed_bytes(N: int, K: int, bits: int) -> int:
+    return _lib.potq_packed_bytes(N, K, bits)
+
+
+def _shape_codes(codes: torch.Tensor, K: int, bits: int) -> int:
+    n_bytes = codes.numel() * codes.element_size()
+    rb = packed_row_bytes(K, bits)
+    if rb == 0 or n_bytes % rb:
+        raise ValueError("codes size is not a whole number of packed rows")
+    return n_bytes // rb
+
+
+def pot_dequant(codes, scales, K: int, bits: int, group: int = 128, out=None):
+    """codes: uint8 (N, K*bits/8) canonical; scales: fp16 (N, K/group) -> fp16 (N, K)."""
+    N = _shape_codes(codes, K, bits)
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float16, device=codes.device)
+    _ok(_lib.pot_dequant(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
+                         _dev(out, torch.float16, "out"), N, K, bits, group, _stream()))
+    return out
+
+
+def int_dequant(codes, scales, zeros, K: int, bits: int, group: int = 128, out=None):
+    N = _shape_codes(codes, K, bits)
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float16, device=codes.device)
+    _ok(_lib.int_dequant(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
+                         _dev(zeros, torch.float16, "zeros"), _dev(out, torch.float16, "out"),
+                         N, K, bits, group, _stream()))
+    return out
+
+
+def potq_repack(src, K: int, bits: int, to_layout: int = LAYOUT_TILE16, out=None):
+    N = _shape_codes(src, K, bits)
+    if out is None:
+        out = torch.empty_like(src)
+    _ok(_lib.potq_repack(_dev(src, torch.uint8, "src"), _dev(out, torch.uint8, "dst"), N, K, bits, to_layout,
+                         _stream()))
+    return out
+
+
+def pot_gemv(codes, scales, x, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16, out=None):
+    N = _shape_codes(codes, K, bits)
+    if x.numel() != K:
+        raise ValueError("x must have K elements")
+    if out is None:
+        out = torch.empty((N,), dtype=torch.float16, device=codes.device)
+    _ok(_lib.pot_gemv(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
+                      _dev(x, torch.float16, "x"), _dev(out, torch.float16, "y"), N, K, bits, group, layout,
+                      _stream()))
+    return out
+
+
+def int_gemv(codes, scales, zeros, x, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16, out=None):
+    N = _shape_codes(codes, K, bits)
+    if x.numel() != K:
+        raise ValueError("x must have K elements")
+    if out is None:
+        out = torch.empty((N,), dtype=torch.float16, device=codes.device)
+    _ok(_lib.int_gemv(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
+                      _dev(zeros, torch.float16, "zeros"), _dev(x, torch.float16, "x"),
+                      _dev(out, torch.float16, "y"), N, K, bits, group, layout, _stream()))
+    return out
+
+
+def pot_gemm(codes, scales, X, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16, out=None):
+    N = _shape_codes(codes, K, bits)
+    if X.dim() != 2 or X.shape[1] != K:
+        raise ValueError("X must be (M, K)")
+    M = X.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=codes.device)
+    _ok(_lib.pot_gemm(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
+                      _dev(X, torch.float16, "X"), _dev(out, torch.float16, "Y"), M, N, K, bits, group, layout,
+                      _stream()))
+    return out
+
+
+def int_gemm(codes, scales, zeros, X, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16, out=None):
+    N = _shape_codes(codes, K, bits)
+    if X.dim() != 2 or X.shape[1] != K:
+        raise ValueError("X must be (M, K)")
+    M = X.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=codes.device)
+    _ok(_lib.int_gemm(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
+                      _dev(zeros, torch.float16, "zeros"), _dev(X, torch.float16, "X"),
+                      _dev(out, torch.float16, "Y"), M, N, K, bits, group, layout, _stream()))
+    return out
+
+
+def pot_check_scales(scales, bits: int) -> int:
+    """Number of scales outside the exact domain (copies one int64 back: synchronises)."""
+    bad = torch.empty((1,), dtype=torch.int64, device=scales.device)
+    _ok(_lib.pot_check_scales(_dev(scales, torch.float16, "scales"), scales.numel(), bits, bad.data_ptr(), _stream()))
+    return int(bad.item())
+
+
+def raw():
+    """The ctypes library object, for tests that call the ABI with hand-made arguments."""
+    return _lib

@@ -1,0 +1,176 @@
+// Host side of the C ABI declared in include/potq.h: argument validation and
+// dispatch.  Nothing here allocates device memory or synchronises.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "potq.h"
+
+namespace potq {
+hipError_t run_dequant(bool is_int, const void *codes, const void *scales, const void *zeros, void *out,
+                       int64_t N, int64_t K, int bits, int group, hipStream_t stream);
+hipError_t run_check_scales(const void *scales, int64_t count, int bits, void *bad_count_dev, hipStream_t stream);
+hipError_t run_repack(const void *src, void *dst, int64_t N, int64_t K, int bits, bool to_tiled, hipStream_t stream);
+hipError_t run_fill_zero(void *p, int64_t count, hipStream_t stream);
+size_t gemv_lds_bytes(int64_t K);
+hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
+                           void *y, int64_t N, int64_t K, int bits, hipStream_t stream);
+hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
+                           void *Y, int64_t M, int64_t N, int64_t K, int bits, hipStream_t stream);
+}  // namespace potq
+
+namespace {
+
+constexpr int64_t kMaxDim = (int64_t)1 << 30;
+
+bool misaligned(const void *p, uintptr_t a = 16) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+// Shared checks; returns POTQ_OK when the call should proceed.
+int check_common(int64_t N, int64_t K, int bits, int group, bool fused)
+{
+    if (bits != 2 && bits != 3) return POTQ_ERR_BITS;
+    if (fused ? (group != 128) : (group != 64 && group != 128)) return POTQ_ERR_GROUP;
+    if (N < 0 || K < 0 || N > kMaxDim || K > kMaxDim || (K % 128) != 0) return POTQ_ERR_SHAPE;
+    return POTQ_OK;
+}
+
+int finish(hipError_t e) { return e == hipSuccess ? POTQ_OK : POTQ_ERR_LAUNCH; }
+
+int dequant_entry(bool is_int, const void *codes, const void *scales, const void *zeros, void *out,
+                  int64_t N, int64_t K, int bits, int group, void *stream)
+{
+    const int st = check_common(N, K, bits, group, false);
+    if (st != POTQ_OK) return st;
+    if (N == 0 || K == 0) return POTQ_OK;
+    if (!codes || !scales || !out || (is_int && !zeros)) return POTQ_ERR_NULL;
+    if (misaligned(codes) || misaligned(scales) || misaligned(out) || (is_int && misaligned(zeros)))
+        return POTQ_ERR_ALIGN;
+    return finish(potq::run_dequant(is_int, codes, scales, zeros, out, N, K, bits, group, (hipStream_t)stream));
+}
+
+int gemv_entry(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x, void *y,
+               int64_t N, int64_t K, int bits, int group, int layout, void *stream)
+{
+    const int st = check_common(N, K, bits, group, true);
+    if (st != POTQ_OK) return st;
+    if (layout != POTQ_LAYOUT_TILE16) return POTQ_ERR_LAYOUT;
+    if (N % 16 != 0) return POTQ_ERR_SHAPE;
+    if (N == 0) return POTQ_OK;
+    if (!y) return POTQ_ERR_NULL;
+    if (misaligned(y)) return POTQ_ERR_ALIGN;
+    if (K == 0) return finish(potq::run_fill_zero(y, N, (hipStream_t)stream));
+    if (!codes || !scales || !x || (is_int && !zeros)) return POTQ_ERR_NULL;
+    if (misaligned(codes) || misaligned(scales) || misaligned(x) || (is_int && misaligned(zeros)))
+        return POTQ_ERR_ALIGN;
+    if (potq::gemv_lds_bytes(K) > 64 * 1024) return POTQ_ERR_SHAPE;
+    return finish(potq::run_gemv_tile16(is_int, codes, scales, zeros, x, y, N, K, bits, (hipStream_t)stream));
+}
+
+int gemm_entry(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
+               int64_t M, int64_t N, int64_t K, int bits, int group, int layout, void *stream)
+{
+    const int st = check_common(N, K, bits, group, true);
+    if (st != POTQ_OK) return st;
+    if (M < 0 || M > kMaxDim) return POTQ_ERR_SHAPE;
+    if (layout != POTQ_LAYOUT_TILE16) return POTQ_ERR_LAYOUT;
+    if (N % 16 != 0) return POTQ_ERR_SHAPE;
+    if (N == 0 || M == 0) return POTQ_OK;
+    if (!Y) return POTQ_ERR_NULL;
+    if (misaligned(Y)) return POTQ_ERR_ALIGN;
+    if (K == 0) return finish(potq::run_fill_zero(Y, M * N, (hipStream_t)stream));
+    if (!codes || !scales || !X || (is_int && !zeros)) return POTQ_ERR_NULL;
+    if (misaligned(codes) || misaligned(scales) || misaligned(X) || (is_int && misaligned(zeros)))
+        return POTQ_ERR_ALIGN;
+    return finish(potq::run_gemm_tile16(is_int, codes, scales, zeros, X, Y, M, N, K, bits, (hipStream_t)stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+int potq_version(void) { return 100; }
+
+const char *potq_strerror(int status)
+{
+    switch (status) {
+    case POTQ_OK: return "ok";
+    case POTQ_ERR_NULL: return "a required pointer is NULL";
+    case POTQ_ERR_BITS: return "bits must be 2 or 3";
+    case POTQ_ERR_GROUP: return "group size not supported (64 or 128; fused kernels: 128)";
+    case POTQ_ERR_SHAPE: return "bad shape (negative, K not a multiple of 128, N not a multiple of 16, or K too large)";
+    case POTQ_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+    case POTQ_ERR_LAYOUT: return "layout not supported by this entry point";
+    case POTQ_ERR_LAUNCH: return "the HIP runtime refused the launch";
+    default: return "unknown status";
+    }
+}
+
+size_t potq_packed_row_bytes(int64_t K, int bits)
+{
+    if (K < 0 || bits <= 0 || (K % 8) != 0) return 0;
+    return (size_t)(K / 8) * (size_t)bits;
+}
+
+size_t potq_packed_bytes(int64_t N, int64_t K, int bits)
+{
+    if (N < 0) return 0;
+    return (size_t)N * potq_packed_row_bytes(K, bits);
+}
+
+int pot_dequant(const void *codes, const void *scales, void *out_f16, int64_t N, int64_t K, int bits, int group,
+                void *hip_stream)
+{
+    return dequant_entry(false, codes, scales, nullptr, out_f16, N, K, bits, group, hip_stream);
+}
+
+int int_dequant(const void *codes, const void *scales, const void *zeros, void *out_f16, int64_t N, int64_t K,
+                int bits, int group, void *hip_stream)
+{
+    return dequant_entry(true, codes, scales, zeros, out_f16, N, K, bits, group, hip_stream);
+}
+
+int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits, int to_layout, void *hip_stream)
+{
+    const int st = check_common(N, K, bits, 128, false);
+    if (st != POTQ_OK) return st;
+    if (to_layout != POTQ_LAYOUT_TILE16 && to_layout != POTQ_LAYOUT_CANONICAL) return POTQ_ERR_LAYOUT;
+    if (N % 16 != 0) return POTQ_ERR_SHAPE;
+    if (N == 0 || K == 0) return POTQ_OK;
+    if (!src || !dst) return POTQ_ERR_NULL;
+    if (misaligned(src) || misaligned(dst)) return POTQ_ERR_ALIGN;
+    return finish(potq::run_repack(src, dst, N, K, bits, to_layout == POTQ_LAYOUT_TILE16, (hipStream_t)hip_stream));
+}
+
+int pot_gemv(const void *codes, const void *scales, const void *x_f16, void *y_f16, int64_t N, int64_t K, int bits,
+             int group, int layout, void *hip_stream)
+{
+    return gemv_entry(false, codes, scales, nullptr, x_f16, y_f16, N, K, bits, group, layout, hip_stream);
+}
+
+int int_gemv(const void *codes, const void *scales, const void *zeros, const void *x_f16, void *y_f16, int64_t N,
+             int64_t K, int bits, int group, int layout, void *hip_stream)
+{
+    return gemv_entry(true, codes, scales, zeros, x_f16, y_f16, N, K, bits, group, layout, hip_stream);
+}
+
+int pot_gemm(const void *codes, const void *scales, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,
+             int bits, int group, int layout, void *hip_stream)
+{
+    return gemm_entry(false, codes, scales, nullptr, X_f16, Y_f16, M, N, K, bits, group, layout, hip_stream);
+}
+
+int int_gemm(const void *codes, const void *scales, const void *zeros, const void *X_f16, void *Y_f16, int64_t M,
+             int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream)
+{
+    return gemm_entry(true, codes, scales, zeros, X_f16, Y_f16, M, N, K, bits, group, layout, hip_stream);
+}
+
+int pot_check_scales(const void *scales, int64_t count, int bits, void *bad_count_dev, void *hip_stream)
+{
+    if (bits != 2 && bits != 3) return POTQ_ERR_BITS;
+    if (count < 0) return POTQ_ERR_SHAPE;
+    if (!bad_count_dev || (count > 0 && !scales)) return POTQ_ERR_NULL;
+    if (misaligned(bad_count_dev, 8) || misaligned(scales, 2)) return POTQ_ERR_ALIGN;
+    return finish(potq::run_check_scales(scales, count, bits, bad_count_dev, (hipStream_t)hip_stream));
+}
+
+}  // extern "C"

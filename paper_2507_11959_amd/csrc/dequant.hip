@@ -1,0 +1,191 @@
+// Stand-alone de-quantisation kernels (canonical layout), gfx950.
+//
+// The whole matrix is one linear stream: because K is a multiple of 128, the
+// packed codes, the scales and the fp16 output are all contiguous and "octet"
+// o (eight consecutive weights) sits at code byte `bits*o`, output byte 16*o
+// and scale index (8*o)/group, whatever the row.  The pass is bound by HBM
+// writes (2 bytes out per weight against bits/8 + 2/group in), so the mapping
+// is chosen for the store side: every lane writes one 16-byte octet per store
+// instruction and 16 neighbouring lanes cover one 256-byte run, four such runs
+// per wavefront instruction, all full cache lines.
+#include "potq_device.hpp"
+
+namespace potq {
+
+constexpr int kOctetsPerLane = 4;                         // U: stores per lane
+constexpr int kDequantBlock = 256;                        // threads per workgroup
+constexpr int kOctetsPerWave = kWave * kOctetsPerLane;    // 256 octets = 2048 weights
+
+// 24 (bits=3) or 16 (bits=2) code bits of octet `o`, from aligned 32-bit words.
+template <int BITS>
+__device__ __forceinline__ uint32_t load_octet_bits(const uint32_t *__restrict__ words, int64_t o)
+{
+    if (BITS == 3) {
+        const int64_t byte = 3 * o;
+        const uint32_t a = words[byte >> 2];
+        const uint32_t b = words[(byte + 2) >> 2];        // word holding the octet's last byte
+        return __builtin_amdgcn_alignbyte(b, a, (uint32_t)(byte & 3)) & 0xFFFFFFu;
+    } else {
+        const uint32_t a = words[o >> 1];
+        return (a >> (16 * (uint32_t)(o & 1))) & 0xFFFFu;
+    }
+}
+
+// Sec. 4.2 for two codes at once, one per 16-bit half of a register: the field
+// (sign, 000, E) << 10 of each code is added, as a 16-bit integer, to the bit
+// pattern of the scale (v_pk_add_u16: the halves wrap independently, which is
+// the documented behaviour for scales outside the exact domain).
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t add_u16x2(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, a) + __builtin_bit_cast(u16x2, b));
+}
+
+// Two adjacent codes (2*BITS bits at bit `pos` of f) -> code A in bits [0,BITS), code B in [16,16+BITS).
+template <int BITS>
+__device__ __forceinline__ uint32_t spread_pair(uint32_t f, int pos)
+{
+    const uint32_t y = __builtin_amdgcn_ubfe(f, pos, 2 * BITS);
+    return __umul24(y, (1u << (16 - BITS)) | 1u) & (((1u << BITS) - 1u) * 0x00010001u);
+}
+
+template <int BITS>
+__device__ __forceinline__ u32x4 pot_octet(uint32_t f, uint32_t scale_bits)
+{
+    const uint32_t s2 = scale_bits | (scale_bits << 16);
+    u32x4 out;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const uint32_t pair = spread_pair<BITS>(f, 2 * BITS * m);
+        // c * (2^10 + 2^(16-BITS)) puts E on bits 10.. and the sign on bit 15; stray copies are masked off
+        const uint32_t t = (BITS == 3) ? (__umul24(pair, 0x2400u) & 0x8C008C00u)
+                                       : (__umul24(pair, 0x4400u) & 0x84008400u);
+        out[m] = add_u16x2(s2, t);
+    }
+    return out;
+}
+
+// Uniform baseline, Sec. 4.1 Eq. (9): q -> fp16 by or-ing it into the mantissa
+// of 1024.0 (0x6400), then (1024 + q) + (Z - 1024) = q + Z exactly and one
+// rounded multiply by S.
+template <int BITS>
+__device__ __forceinline__ u32x4 int_octet(uint32_t f, half2_t zm1024, half2_t s2)
+{
+    u32x4 out;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const uint32_t pair = spread_pair<BITS>(f, 2 * BITS * m) | 0x64006400u;
+        const half2_t w = (as_half2(pair) + zm1024) * s2;
+        out[m] = as_u32(w);
+    }
+    return out;
+}
+
+template <int BITS, bool IS_INT>
+__global__ __launch_bounds__(kDequantBlock) void dequant_kernel(
+    const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales,
+    const uint16_t *__restrict__ zeros, u32x4 *__restrict__ out, int64_t n_octets, int group_shift)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave = (int64_t)blockIdx.x * (kDequantBlock / kWave) + (threadIdx.x >> 6);
+    const int64_t base = wave * kOctetsPerWave;
+    if (base >= n_octets) return;
+    // lane = (quarter, l): quarter q owns octets base + q*64 .. +63, visited 16 lanes at a time
+    const int64_t o0 = base + (lane >> 4) * (16 * kOctetsPerLane) + (lane & 15);
+    const int octet_shift = group_shift - 3;   // octets per group = group / 8
+
+#pragma unroll
+    for (int j = 0; j < kOctetsPerLane; ++j) {
+        const int64_t o = o0 + 16 * j;
+        if (o < n_octets) {
+            const uint32_t f = load_octet_bits<BITS>(codes, o);
+            const int64_t g = o >> octet_shift;
+            const uint32_t s = scales[g];
+            u32x4 w;
+            if (IS_INT) {
+                const _Float16 S = __builtin_bit_cast(_Float16, (uint16_t)s);
+                const _Float16 Z = __builtin_bit_cast(_Float16, zeros[g]) - (_Float16)1024.0f;
+                w = int_octet<BITS>(f, half2_t{Z, Z}, half2_t{S, S});
+            } else {
+                w = pot_octet<BITS>(f, s);
+            }
+            __builtin_nontemporal_store(w, &out[o]);
+        }
+    }
+}
+
+template <int BITS, bool IS_INT>
+static hipError_t launch_dequant(const void *codes, const void *scales, const void *zeros, void *out,
+                                 int64_t N, int64_t K, int group, hipStream_t stream)
+{
+    const int64_t n_octets = N * K / 8;
+    const int64_t waves = (n_octets + kOctetsPerWave - 1) / kOctetsPerWave;
+    const int64_t blocks = (waves + (kDequantBlock / kWave) - 1) / (kDequantBlock / kWave);
+    const int group_shift = (group == 128) ? 7 : 6;
+    hipLaunchKernelGGL((dequant_kernel<BITS, IS_INT>), dim3((unsigned)blocks), dim3(kDequantBlock), 0, stream,
+                       (const uint32_t *)codes, (const uint16_t *)scales, (const uint16_t *)zeros,
+                       (u32x4 *)out, n_octets, group_shift);
+    return hipGetLastError();
+}
+
+hipError_t run_dequant(bool is_int, const void *codes, const void *scales, const void *zeros, void *out,
+                       int64_t N, int64_t K, int bits, int group, hipStream_t stream)
+{
+    if (is_int)
+        return bits == 3 ? launch_dequant<3, true>(codes, scales, zeros, out, N, K, group, stream)
+                         : launch_dequant<2, true>(codes, scales, zeros, out, N, K, group, stream);
+    return bits == 3 ? launch_dequant<3, false>(codes, scales, zeros, out, N, K, group, stream)
+                     : launch_dequant<2, false>(codes, scales, zeros, out, N, K, group, stream);
+}
+
+// ---------------------------------------------------------------------------
+// Scale-domain check: positive, normal, exponent field <= 30 - q_max.
+// ---------------------------------------------------------------------------
+__global__ void zero_count_kernel(unsigned long long *count) { *count = 0ull; }
+
+__global__ __launch_bounds__(256) void check_scales_kernel(const uint16_t *__restrict__ scales, int64_t count,
+                                                           int max_exp, unsigned long long *bad)
+{
+    unsigned long long local = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const uint32_t s = scales[i];
+        const uint32_t e = (s >> 10) & 31u;
+        local += ((s >> 15) != 0u) || e < 1u || e > (uint32_t)max_exp;
+    }
+    // wave-level sum, then one integer atomic per wave (integer adds commute: deterministic)
+    for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off, 64);
+    if ((threadIdx.x & 63) == 0 && local) atomicAdd(bad, local);
+}
+
+hipError_t run_check_scales(const void *scales, int64_t count, int bits, void *bad_count_dev, hipStream_t stream)
+{
+    const int qmax = (1 << (bits - 1)) - 1;
+    hipLaunchKernelGGL(zero_count_kernel, dim3(1), dim3(1), 0, stream, (unsigned long long *)bad_count_dev);
+    if (count > 0) {
+        int64_t blocks = (count + 255) / 256;
+        if (blocks > 2048) blocks = 2048;
+        hipLaunchKernelGGL(check_scales_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           (const uint16_t *)scales, count, 30 - qmax, (unsigned long long *)bad_count_dev);
+    }
+    return hipGetLastError();
+}
+
+// Zero-fill of `count` 16-bit words (results of products over an empty K).
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint16_t *p, int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = 0;
+}
+
+hipError_t run_fill_zero(void *p, int64_t count, hipStream_t stream)
+{
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (uint16_t *)p, count);
+    return hipGetLastError();
+}
+
+}  // namespace potq

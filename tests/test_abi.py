@@ -1,0 +1,88 @@
+"""CPU-only checks of the boundary: the built library loads, exports every
+function the public header declares, and rejects bad arguments on the host
+(before anything could be launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "potq.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2507_11959_amd import binding
+    return binding.raw()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
+    return sorted({n for n in names if n.startswith(("pot_", "int_", "potq_"))})
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"pot_dequant", "int_dequant", "pot_gemv", "int_gemv", "pot_gemm", "int_gemm", "potq_repack",
+            "pot_check_scales", "potq_version", "potq_strerror", "potq_packed_row_bytes",
+            "potq_packed_bytes"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2507_11959_amd import binding
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_sizes_and_strings(lib):
+    assert lib.potq_version() >= 100
+    assert lib.potq_packed_row_bytes(4096, 3) == 1536
+    assert lib.potq_packed_row_bytes(4096, 2) == 1024
+    assert lib.potq_packed_bytes(11008, 4096, 2) == 11008 * 1024
+    assert lib.potq_packed_row_bytes(100, 3) == 0
+    for s in range(8):
+        assert lib.potq_strerror(s)
+    assert lib.potq_strerror(0) == b"ok"
+
+
+def test_host_side_validation(lib):
+    A, MIS = 0x10000, 0x10004          # fake device addresses: never dereferenced on these paths
+    OK, NULL, BITS, GROUP, SHAPE, ALIGN, LAYOUT = 0, 1, 2, 3, 4, 5, 6
+    d = lib.pot_dequant
+    assert d(None, A, A, 16, 128, 3, 128, None) == NULL
+    assert d(A, None, A, 16, 128, 3, 128, None) == NULL
+    assert d(A, A, None, 16, 128, 3, 128, None) == NULL
+    assert d(A, A, A, 16, 128, 4, 128, None) == BITS
+    assert d(A, A, A, 16, 128, 1, 128, None) == BITS
+    assert d(A, A, A, 16, 128, 3, 32, None) == GROUP
+    assert d(A, A, A, 16, 192, 3, 64, None) == SHAPE
+    assert d(A, A, A, -1, 128, 3, 128, None) == SHAPE
+    assert d(MIS, A, A, 16, 128, 3, 128, None) == ALIGN
+    assert d(A, A, MIS, 16, 128, 3, 128, None) == ALIGN
+    assert d(None, None, None, 0, 128, 3, 128, None) == OK          # empty input: nothing to do
+    assert d(None, None, None, 16, 0, 2, 64, None) == OK
+    i = lib.int_dequant
+    assert i(A, A, None, A, 16, 128, 3, 128, None) == NULL
+    assert i(A, A, MIS, A, 16, 128, 2, 128, None) == ALIGN
+    g = lib.pot_gemv
+    assert g(A, A, A, A, 16, 128, 3, 64, 1, None) == GROUP            # fused kernels: group 128 only
+    assert g(A, A, A, A, 16, 128, 3, 128, 7, None) == LAYOUT
+    assert g(A, A, A, A, 8, 128, 3, 128, 1, None) == SHAPE            # tiled layout: N % 16
+    assert g(A, A, None, A, 16, 128, 3, 128, 1, None) == NULL
+    assert g(A, A, A, None, 16, 128, 3, 128, 1, None) == NULL
+    assert g(None, None, None, None, 0, 128, 3, 128, 1, None) == OK
+    m = lib.pot_gemm
+    assert m(A, A, A, A, -2, 16, 128, 3, 128, 1, None) == SHAPE
+    assert m(A, A, A, A, 4, 16, 128, 3, 128, 0, None) == LAYOUT
+    assert m(None, None, None, None, 0, 16, 128, 3, 128, 1, None) == OK
+    assert lib.int_gemm(A, A, None, A, A, 4, 16, 128, 3, 128, 1, None) == NULL
+    assert lib.int_gemv(A, A, A, MIS, A, 16, 128, 3, 128, 1, None) == ALIGN
+    r = lib.potq_repack
+    assert r(A, A, 24, 128, 3, 1, None) == SHAPE
+    assert r(A, A, 16, 128, 3, 5, None) == LAYOUT
+    assert r(A, None, 16, 128, 3, 1, None) == NULL
+    c = lib.pot_check_scales
+    assert c(A, 4, 3, None, None) == NULL
+    assert c(A, 4, 5, A, None) == BITS
+    assert c(A, -1, 3, A, None) == SHAPE

@@ -1,0 +1,204 @@
+"""GPU parity tests: the HIP library, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  Dequant is compared bit for bit; the fused
+GEMV / GEMM within the stated relative tolerance, and bit for bit wherever the
+result is a single term (one-hot activations)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_util import REL_TOL, dev, host_bits, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def potq():
+    import paper_2507_11959_amd as p
+    return p
+
+
+# shapes: several 2048-weight wavefront chunks plus a ragged tail; one-group and one-row cases
+DEQ_SHAPES = [(37, 640), (1, 128), (3, 128), (16, 2048), (5, 11008), (129, 4096)]
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("N,K", DEQ_SHAPES)
+def test_pot_dequant_bit_exact(potq, bits, group, N, K):
+    packed = workloads.packed_codes(11 * N + K + bits, N, K, bits)
+    scales = workloads.pot_scales(13 * N + K + group, N, K, group)
+    want = oracle.pot_dequant(packed, scales, K, bits, group, nthreads=4)
+    got = host_bits(potq.pot_dequant(dev(packed), dev(scales), K, bits, group))
+    assert got.shape == want.shape
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("N,K", DEQ_SHAPES)
+def test_int_dequant_bit_exact(potq, bits, group, N, K):
+    packed = workloads.packed_codes(17 * N + K + bits, N, K, bits)
+    S, Z = workloads.int_scales_zeros(19 * N + K + group, N, K, bits, group)
+    want = oracle.int_dequant(packed, S, Z, K, bits, group, nthreads=4)
+    got = host_bits(potq.int_dequant(dev(packed), dev(S), dev(Z), K, bits, group))
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_pot_dequant_structured_pattern(potq, bits):
+    # code(n,k) = (n + k) mod 2^b, scale(n,g) = 2^((n+g) mod 8 - 8): index mix-ups change the output
+    N, K, G = 40, 1024, 128
+    n = np.arange(N)[:, None]
+    codes = ((n + np.arange(K)[None, :]) % 2 ** bits).astype(np.uint8)
+    scales = (2.0 ** (((n + np.arange(K // G)[None, :]) % 8) - 8)).astype(np.float16)
+    packed = oracle.pack_codes(codes, bits)
+    want = oracle.pot_dequant(packed, scales, K, bits, G)
+    got = host_bits(potq.pot_dequant(dev(packed), dev(scales), K, bits, G))
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_pot_dequant_any_scale_pattern_is_the_bit_recipe(potq, bits):
+    # outside the exact domain the library's result is defined as the 16-bit wrap-around add
+    N, K, G = 64, 1024, 128
+    rng = np.random.default_rng(bits)
+    scales = rng.integers(0, 65536, size=(N, K // G), dtype=np.uint16)
+    packed = workloads.packed_codes(5, N, K, bits)
+    want = oracle.pot_dequant(packed, scales, K, bits, G, use_bit_recipe=True)
+    got = host_bits(potq.pot_dequant(dev(packed), dev(scales), K, bits, G))
+    assert np.array_equal(got, want)
+    bad = oracle.check_scales(scales, bits)
+    assert 0 < bad < scales.size
+    assert potq.pot_check_scales(dev(scales), bits) == bad
+    assert potq.pot_check_scales(dev(workloads.pot_scales(1, N, K)), bits) == 0
+
+
+def test_int_dequant_all_zero_points(potq):
+    # every (q, Z) pair with sampled scales, including S = 1 (exact small integers)
+    for bits in (2, 3):
+        L = 2 ** bits - 1
+        N, K, G = 16 * (L + 1), 128, 128
+        codes = np.tile(np.arange(K) % (L + 1), (N, 1)).astype(np.uint8)
+        packed = oracle.pack_codes(codes, bits)
+        Z = np.repeat(-np.arange(L + 1), 16).astype(np.float16)[:, None]
+        rng = np.random.default_rng(3)
+        S = rng.uniform(1e-3, 0.1, size=(N, 1)).astype(np.float16)
+        S[::16] = 1.0
+        want = oracle.int_dequant(packed, S, Z, K, bits, G)
+        got = host_bits(potq.int_dequant(dev(packed), dev(S), dev(Z), K, bits, G))
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("N,K", [(16, 128), (48, 640), (256, 4096)])
+def test_repack_round_trip_and_permutation(potq, bits, N, K):
+    packed = workloads.packed_codes(23 + N + bits, N, K, bits)
+    d = dev(packed)
+    tiled = potq.potq_repack(d, K, bits, potq.LAYOUT_TILE16)
+    back = potq.potq_repack(tiled, K, bits, potq.LAYOUT_CANONICAL)
+    assert torch.equal(back, d)
+    assert tiled.numel() == d.numel()
+    # a permutation of bits: same population count, and (for random input) not the identity
+    t = tiled.cpu().numpy()
+    assert np.unpackbits(t).sum() == np.unpackbits(packed).sum()
+    assert not np.array_equal(t.ravel(), packed.ravel())
+
+
+def _gemv_inputs(seed, N, K, bits, is_int):
+    packed = workloads.packed_codes(seed, N, K, bits)
+    if is_int:
+        S, Z = workloads.int_scales_zeros(seed + 3, N, K, bits)
+    else:
+        S, Z = workloads.pot_scales(seed + 1, N, K), None
+    return packed, S, Z
+
+
+def _run_gemm(potq, packed, S, Z, X, K, bits):
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    if X.shape[0] == 1:
+        if Z is None:
+            y = potq.pot_gemv(tiled, dev(S), dev(X[0]), K, bits)
+        else:
+            y = potq.int_gemv(tiled, dev(S), dev(Z), dev(X[0]), K, bits)
+        return host_bits(y)[None, :]
+    if Z is None:
+        return host_bits(potq.pot_gemm(tiled, dev(S), dev(X), K, bits))
+    return host_bits(potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits))
+
+
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("N,K", [(16, 128), (48, 640), (272, 4096), (64, 11008)])
+def test_gemv_one_hot_gives_exact_columns(potq, bits, N, K, is_int):
+    packed, S, Z = _gemv_inputs(100 + N + bits, N, K, bits, is_int)
+    W = oracle.int_dequant(packed, S, Z, K, bits, 128) if is_int else oracle.pot_dequant(packed, S, K, bits, 128)
+    rng = np.random.default_rng(N + K)
+    ks = sorted(set([0, 1, 2, 3, 31, 32, 127, K - 128, K - 1] + list(rng.integers(0, K, 24))))
+    for k in ks:
+        X = np.zeros((1, K), np.float16)
+        X[0, k] = 1.0
+        y = _run_gemm(potq, packed, S, Z, X, K, bits)[0]
+        assert np.array_equal(y, W[:, k]), k
+
+
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("N,K", [(16, 128), (48, 640), (272, 4096), (64, 11008), (1024, 8192)])
+def test_gemv_vs_oracle(potq, bits, N, K, is_int):
+    packed, S, Z = _gemv_inputs(200 + N + bits, N, K, bits, is_int)
+    X = workloads.activations(300 + K, 1, K)
+    want = oracle.gemm(packed, S, Z, X, K, bits, 128, nthreads=8)
+    got = _run_gemm(potq, packed, S, Z, X, K, bits)
+    e, nw, nfloor = rel_err(got, want)
+    assert e <= REL_TOL, (e, nw, nfloor)
+
+
+def test_gemv_all_ones_zero_codes(potq):
+    N, K = 32, 1024
+    scales = (2.0 ** -(np.arange(K // 128) % 4)[None, :] * np.ones((N, 1))).astype(np.float16)
+    packed = np.zeros((N, K * 3 // 8), np.uint8)
+    y = _run_gemm(potq, packed, scales, None, np.ones((1, K), np.float16), K, 3)[0]
+    assert np.all(y.view(np.float16).astype(np.float64) == 128 * scales.astype(np.float64).sum(axis=1))
+
+
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("M", [2, 16, 33, 70, 256])
+def test_gemm_vs_oracle(potq, bits, M, is_int):
+    N, K = 80, 1280
+    packed, S, Z = _gemv_inputs(400 + M + bits, N, K, bits, is_int)
+    X = workloads.activations(500 + M, M, K)
+    want = oracle.gemm(packed, S, Z, X, K, bits, 128, nthreads=8)
+    got = _run_gemm(potq, packed, S, Z, X, K, bits)
+    assert got.shape == (M, N)
+    e, nw, nfloor = rel_err(got, want)
+    assert e <= REL_TOL, (e, nw, nfloor)
+
+
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("bits", [2, 3])
+def test_gemm_one_hot_rows_give_exact_columns(potq, bits, is_int):
+    N, K, M = 48, 640, 40
+    packed, S, Z = _gemv_inputs(600 + bits, N, K, bits, is_int)
+    W = oracle.int_dequant(packed, S, Z, K, bits, 128) if is_int else oracle.pot_dequant(packed, S, K, bits, 128)
+    ks = np.random.default_rng(9).choice(K, size=M, replace=False)
+    X = np.zeros((M, K), np.float16)
+    X[np.arange(M), ks] = 1.0
+    got = _run_gemm(potq, packed, S, Z, X, K, bits)
+    assert np.array_equal(got, W[:, ks].T)
+
+
+def test_empty_inputs_are_accepted(potq):
+    e8 = torch.empty((0,), dtype=torch.uint8, device="cuda:0")
+    e16 = torch.empty((0,), dtype=torch.float16, device="cuda:0")
+    lib = __import__("paper_2507_11959_amd.binding", fromlist=["raw"]).raw()
+    assert lib.pot_dequant(None, None, None, 0, 4096, 3, 128, None) == 0
+    assert lib.pot_gemm(None, None, None, None, 0, 16, 128, 3, 128, 1, None) == 0
+    # K = 0: products over an empty K are zero
+    y = torch.full((16,), 7.0, dtype=torch.float16, device="cuda:0")
+    assert lib.pot_gemv(None, None, None, y.data_ptr(), 16, 0, 3, 128, 1, None) == 0
+    torch.cuda.synchronize()
+    assert torch.all(y == 0)
+    assert e8.numel() == 0 and e16.numel() == 0
