@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the potq hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras] [--no-cpu]
+
+Headline ("step"): one stand-alone PoT dequant pass over a Llama-2-7B-shaped
+decoder layer (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), 2-bit
+codes, group 128: seven pot_dequant launches, inputs resident in HBM.  `value`
+is algorithmic bytes (codes + scales in, fp16 out) per second.  The same JSON
+line carries the roofline of the dominant kernel, the CPU oracle timed on the
+host cores, and (unless --no-extras) the uniform-INT baseline, the fused GEMV on
+the 7B shapes (3-bit) and the fused MFMA GEMM on the 13B shapes (3-bit,
+M = 16/64/256), each with its speed-up over the INT path.
+
+All inputs are seeded synthetic tensors from workloads.py.  This run uses one
+GPU; --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16 MFMA, published
+CONFIG_INDEX = 1                # the Llama-2-7B layer workload
+
+
+def _events(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def _time_steps(torch, step, steps, warmup):
+    """Average milliseconds per call of `step` over `steps` calls, HIP events on the launch stream."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-extras", action="store_true", help="headline only (used for profiling runs)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (reference kernel for byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2507_11959_amd as potq     # raises if libpotq.so has not been built
+    from paper_2507_11959_amd import binding
+    import workloads
+
+    lib = binding.raw()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    G = workloads.GROUP
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    def check(status):
+        if status != 0:
+            raise RuntimeError(f"potq status {status}: {potq.strerror(status)}")
+
+    # ---------------------------------------------------------------- headline: 7B layer, 2-bit dequant
+    bits = 2
+    shapes = workloads.LLAMA2_7B_LAYER
+    mats = []
+    for i, (name, N, K) in enumerate(shapes):
+        codes, scales = workloads.pot_matrix(CONFIG_INDEX, i, N, K, bits, G)
+        S, Z = workloads.int_scales_zeros(workloads.seed_of(CONFIG_INDEX, i, 3), N, K, bits, G)
+        mats.append(dict(name=name, N=N, K=K, codes_h=codes, scales_h=scales,
+                         codes=to_dev(codes), scales=to_dev(scales), S=to_dev(S), Z=to_dev(Z),
+                         out=torch.empty((N, K), dtype=torch.float16, device=dev)))
+    pot_bytes = sum(workloads.algorithmic_bytes_dequant(m["N"], m["K"], bits, G) for m in mats)
+    int_bytes = sum(workloads.algorithmic_bytes_dequant(m["N"], m["K"], bits, G, True) for m in mats)
+    weights = sum(m["N"] * m["K"] for m in mats)
+
+    pot_calls = [(m["codes"].data_ptr(), m["scales"].data_ptr(), m["out"].data_ptr(), m["N"], m["K"], bits, G, stream)
+                 for m in mats]
+    int_calls = [(m["codes"].data_ptr(), m["S"].data_ptr(), m["Z"].data_ptr(), m["out"].data_ptr(), m["N"], m["K"],
+                  bits, G, stream) for m in mats]
+
+    def pot_step():
+        for c in pot_calls:
+            check(lib.pot_dequant(*c))
+
+    def int_step():
+        for c in int_calls:
+            check(lib.int_dequant(*c))
+
+    ms = _time_steps(torch, pot_step, args.steps, args.warmup)
+    value = pot_bytes / (ms * 1e-3) / 1e9
+    launches = len(mats)
+    result = {
+        "metric": "PoT dequant GB/s (algorithmic bytes: codes + scales in, fp16 out)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u16",
+        "data": "synthetic",
+        "config": {"workload": "Llama-2-7B decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008), "
+                               "2-bit PoT codes, group 128, stand-alone dequant of all seven matrices",
+                   "bits": bits, "group": G, "weights": weights, "launches_per_step": launches,
+                   "layout": "canonical"},
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "roofline": {
+            "kernel": "potq::dequant_kernel<2, false>",
+            "bound": "hbm",
+            "achieved": round(value, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(value / HBM_PEAK_GBPS, 4),
+            "bytes_per_launch": pot_bytes / launches,
+            "us_per_launch": round(ms * 1e3 / launches, 3),
+            "traffic": None,
+        },
+    }
+
+    if args.copy_calibration:
+        # a kernel whose HBM traffic is known exactly: 256 MiB read + 256 MiB written per launch
+        a = torch.empty(128 * 1024 * 1024, dtype=torch.float16, device=dev).normal_()
+        b = torch.empty_like(a)
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+    # ---------------------------------------------------------------- CPU oracle on the host cores
+    if not args.no_cpu:
+        import oracle
+        cores = len(os.sched_getaffinity(0))
+        threads = min(cores, oracle.max_threads())
+        passes = 0
+        t0 = time.perf_counter()
+        while passes < 64 and (passes == 0 or time.perf_counter() - t0 < 12.0):
+            for m in mats:
+                oracle.pot_dequant(m["codes_h"], m["scales_h"], m["K"], bits, G, nthreads=threads)
+            passes += 1
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(passes * pot_bytes / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{passes} full passes over the same seven matrices (202.4 M weights each), "
+                      "oracle/potq_oracle.c pot_dequant, OpenMP over rows",
+            "seconds": round(dt, 2),
+        }
+    for m in mats:
+        del m["codes_h"], m["scales_h"]
+
+    # ---------------------------------------------------------------- extras
+    if not args.no_extras:
+        extras = {}
+        ms_int = _time_steps(torch, int_step, args.steps, args.warmup)
+        extras["int_dequant_7b_layer_2bit"] = {
+            "GBps": round(int_bytes / (ms_int * 1e-3) / 1e9, 1), "ms_per_step": round(ms_int, 5),
+            "pot_speedup_vs_int": round(ms_int / ms, 4)}
+        del mats, pot_calls, int_calls
+        torch.cuda.empty_cache()
+
+        def rotate(nbytes_per_set):
+            return max(2, min(64, (1 << 30) // max(1, nbytes_per_set) + 1))
+
+        # fused GEMV, 3-bit, 7B shapes, rotating through distinct weight buffers (>= 1 GiB in total)
+        gemv = []
+        b3 = 3
+        for i, (name, N, K) in enumerate(workloads.GEMV_7B_SHAPES):
+            nbytes = workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
+            R = rotate(nbytes)
+            codes_h, scales_h = workloads.pot_matrix(2, i, N, K, b3, G)
+            S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(2, i, 3), N, K, b3, G)
+            x = to_dev(workloads.activations(workloads.seed_of(2, i, 2), 1, K)[0])
+            tiled = potq.potq_repack(to_dev(codes_h), K, b3)
+            sets = [tiled.clone() for _ in range(R)]
+            sc = [to_dev(scales_h) for _ in range(R)]
+            Ss = [to_dev(S_h) for _ in range(R)]
+            Zs = [to_dev(Z_h) for _ in range(R)]
+            y = torch.empty((N,), dtype=torch.float16, device=dev)
+            pc = [(sets[r].data_ptr(), sc[r].data_ptr(), x.data_ptr(), y.data_ptr(), N, K, b3, G, 1, stream)
+                  for r in range(R)]
+            ic = [(sets[r].data_ptr(), Ss[r].data_ptr(), Zs[r].data_ptr(), x.data_ptr(), y.data_ptr(), N, K, b3, G, 1,
+                   stream) for r in range(R)]
+
+            def pot_rot():
+                for c in pc:
+                    check(lib.pot_gemv(*c))
+
+            def int_rot():
+                for c in ic:
+                    check(lib.int_gemv(*c))
+
+            reps = max(2, 256 // R)
+            us_p = _time_steps(torch, pot_rot, reps, 2) * 1e3 / R
+            us_i = _time_steps(torch, int_rot, reps, 2) * 1e3 / R
+            gemv.append({"shape": f"{N}x{K}", "us": round(us_p, 2), "GBps": round(nbytes / us_p / 1e3, 1),
+                         "pct_hbm_peak": round(nbytes / us_p / 1e3 / HBM_PEAK_GBPS * 100, 1),
+                         "TFLOPs": round(2.0 * N * K / us_p / 1e6, 2), "int_us": round(us_i, 2),
+                         "pot_speedup_vs_int": round(us_i / us_p, 3), "buffers_rotated": R})
+            del sets, sc, Ss, Zs, pc, ic
+        extras["pot_gemv_3bit_7b_shapes"] = gemv
+        torch.cuda.empty_cache()
+
+        # fused MFMA GEMM, 3-bit, 13B shapes
+        gemm = []
+        for i, (name, N, K) in enumerate(workloads.GEMM_13B_SHAPES):
+            codes_h, scales_h = workloads.pot_matrix(4, i, N, K, b3, G)
+            S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(4, i, 3), N, K, b3, G)
+            tiled = potq.potq_repack(to_dev(codes_h), K, b3)
+            sc, Sd, Zd = to_dev(scales_h), to_dev(S_h), to_dev(Z_h)
+            for M in workloads.GEMM_TOKENS:
+                X = to_dev(workloads.activations(workloads.seed_of(4, i, 2) + M, M, K))
+                Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+                pa = (tiled.data_ptr(), sc.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1, stream)
+                ia = (tiled.data_ptr(), Sd.data_ptr(), Zd.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1,
+                      stream)
+                us_p = _time_steps(torch, lambda: check(lib.pot_gemm(*pa)), 30, 3) * 1e3
+                us_i = _time_steps(torch, lambda: check(lib.int_gemm(*ia)), 30, 3) * 1e3
+                tf = 2.0 * M * N * K / us_p / 1e6
+                gemm.append({"shape": f"{N}x{K}", "M": M, "us": round(us_p, 2), "TFLOPs": round(tf, 1),
+                             "pct_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 2),
+                             "GBps": round(workloads.algorithmic_bytes_gemm(M, N, K, b3, G) / us_p / 1e3, 1),
+                             "int_us": round(us_i, 2), "pot_speedup_vs_int": round(us_i / us_p, 3)})
+        extras["pot_gemm_3bit_13b_shapes"] = gemm
+        result["extras"] = extras
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
