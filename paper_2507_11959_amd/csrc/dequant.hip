@@ -12,8 +12,17 @@
 
 namespace potq {
 
-constexpr int kOctetsPerLane = 4;                         // U: stores per lane
-constexpr int kDequantBlock = 256;                        // threads per workgroup
+#ifndef POTQ_DQ_OCTETS
+#define POTQ_DQ_OCTETS 1
+#endif
+#ifndef POTQ_DQ_BLOCK
+#define POTQ_DQ_BLOCK 256
+#endif
+#ifndef POTQ_DQ_NT
+#define POTQ_DQ_NT 1
+#endif
+constexpr int kOctetsPerLane = POTQ_DQ_OCTETS;            // U: stores per lane
+constexpr int kDequantBlock = POTQ_DQ_BLOCK;              // threads per workgroup
 constexpr int kOctetsPerWave = kWave * kOctetsPerLane;    // 256 octets = 2048 weights
 
 // 24 (bits=3) or 16 (bits=2) code bits of octet `o`, from aligned 32-bit words.
@@ -110,7 +119,11 @@ __global__ __launch_bounds__(kDequantBlock) void dequant_kernel(
             } else {
                 w = pot_octet<BITS>(f, s);
             }
+#if POTQ_DQ_NT
             __builtin_nontemporal_store(w, &out[o]);
+#else
+            out[o] = w;
+#endif
         }
     }
 }
