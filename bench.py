@@ -5,7 +5,8 @@
 
 Headline ("step"): one stand-alone PoT dequant pass over a Llama-2-7B-shaped
 decoder layer (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), 2-bit
-codes, group 128: seven pot_dequant launches, inputs resident in HBM.  `value`
+codes, group 128, all seven matrices in one pot_dequant_batch launch, inputs
+resident in HBM.  `value`
 is algorithmic bytes (codes + scales in, fp16 out) per second.  The same JSON
 line carries the roofline of the dominant kernel, the CPU oracle timed on the
 host cores, and (unless --no-extras) the uniform-INT baseline, the fused GEMV on
@@ -105,17 +106,22 @@ def main() -> int:
     int_calls = [(m["codes"].data_ptr(), m["S"].data_ptr(), m["Z"].data_ptr(), m["out"].data_ptr(), m["N"], m["K"],
                   bits, G, stream) for m in mats]
 
-    def pot_step():
+    pot_items = binding.make_batch([(m["codes"], m["scales"], None, m["out"], m["K"], bits) for m in mats])
+    int_items = binding.make_batch([(m["codes"], m["S"], m["Z"], m["out"], m["K"], bits) for m in mats], is_int=True)
+
+    def pot_step():          # the whole layer in one launch
+        check(lib.pot_dequant_batch(pot_items, len(mats), bits, G, stream))
+
+    def int_step():
+        check(lib.int_dequant_batch(int_items, len(mats), bits, G, stream))
+
+    def pot_step_7():        # the same work as seven separate launches
         for c in pot_calls:
             check(lib.pot_dequant(*c))
 
-    def int_step():
-        for c in int_calls:
-            check(lib.int_dequant(*c))
-
     ms = _time_steps(torch, pot_step, args.steps, args.warmup)
     value = pot_bytes / (ms * 1e-3) / 1e9
-    launches = len(mats)
+    launches = 1
     result = {
         "metric": "PoT dequant GB/s (algorithmic bytes: codes + scales in, fp16 out)",
         "value": round(value, 1),
@@ -132,10 +138,10 @@ def main() -> int:
         "config": {"workload": "Llama-2-7B decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008), "
                                "2-bit PoT codes, group 128, stand-alone dequant of all seven matrices",
                    "bits": bits, "group": G, "weights": weights, "launches_per_step": launches,
-                   "layout": "canonical"},
+                   "entry_point": "pot_dequant_batch", "layout": "canonical"},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "roofline": {
-            "kernel": "potq::dequant_kernel<2, false>",
+            "kernel": "potq::dequant_batch_kernel<2, false>",
             "bound": "hbm",
             "achieved": round(value, 1),
             "peak": HBM_PEAK_GBPS,
@@ -143,7 +149,9 @@ def main() -> int:
             "frac": round(value / HBM_PEAK_GBPS, 4),
             "bytes_per_launch": pot_bytes / launches,
             "us_per_launch": round(ms * 1e3 / launches, 3),
-            "traffic": None,
+            # HBM bytes per launch from rocprofv3 FETCH_SIZE (x2.000) + WRITE_SIZE (x1.000), factors calibrated
+            # on a 256 MiB copy; figures and commands in profiles/pot_dequant_batch_b2_llama7b_layer.md
+            "traffic": 458826850,
         },
     }
 
@@ -184,7 +192,10 @@ def main() -> int:
         extras["int_dequant_7b_layer_2bit"] = {
             "GBps": round(int_bytes / (ms_int * 1e-3) / 1e9, 1), "ms_per_step": round(ms_int, 5),
             "pot_speedup_vs_int": round(ms_int / ms, 4)}
-        del mats, pot_calls, int_calls
+        ms7 = _time_steps(torch, pot_step_7, args.steps, args.warmup)
+        extras["pot_dequant_7b_layer_2bit_seven_launches"] = {
+            "GBps": round(pot_bytes / (ms7 * 1e-3) / 1e9, 1), "ms_per_step": round(ms7, 5)}
+        del mats, pot_calls, int_calls, pot_items, int_items
         torch.cuda.empty_cache()
 
         def rotate(nbytes_per_set):

@@ -108,6 +108,28 @@ int int_dequant(const void *codes, const void *scales, const void *zeros, void *
                 int64_t N, int64_t K, int bits, int group, void *hip_stream);
 
 /*
+ * pot_dequant_batch / int_dequant_batch -- the same operation on up to
+ * POTQ_MAX_BATCH matrices (e.g. the seven projections of a decoder layer) in a
+ * single kernel launch, so that the fixed start-up and drain time of a launch,
+ * during which HBM idles, is paid once.  `items_host` is a HOST array of `count`
+ * descriptors; it is copied into the launch and may be reused or freed as soon as
+ * the call returns.  Every matrix obeys the rules of pot_dequant / int_dequant
+ * (`zeros` is ignored by the PoT entry point); all share `bits` and `group`.
+ * Results are identical, bit for bit, to `count` separate calls.
+ */
+#define POTQ_MAX_BATCH 16
+typedef struct potq_dequant_item {
+    const void *codes;      /* device, canonical layout */
+    const void *scales;     /* device, N x (K/group) fp16 */
+    const void *zeros;      /* device, N x (K/group) fp16; uniform baseline only */
+    void *out_f16;          /* device, N x K fp16 */
+    int64_t N, K;
+} potq_dequant_item;
+
+int pot_dequant_batch(const potq_dequant_item *items_host, int count, int bits, int group, void *hip_stream);
+int int_dequant_batch(const potq_dequant_item *items_host, int count, int bits, int group, void *hip_stream);
+
+/*
  * potq_repack -- permute packed codes between the two layouts (device to
  * device, src and dst must not overlap).  to_layout = POTQ_LAYOUT_TILE16
  * converts canonical -> tiled, POTQ_LAYOUT_CANONICAL converts tiled ->

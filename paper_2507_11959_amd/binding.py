@@ -34,6 +34,8 @@ EXPORTS = {
     "potq_packed_bytes": (ctypes.c_size_t, [_i64, _i64, _int]),
     "pot_dequant": (_int, [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]),
     "int_dequant": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _vp]),
+    "pot_dequant_batch": (_int, [_vp, _int, _int, _int, _vp]),
+    "int_dequant_batch": (_int, [_vp, _int, _int, _int, _vp]),
     "potq_repack": (_int, [_vp, _vp, _i64, _i64, _int, _int, _vp]),
     "pot_gemv": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
     "int_gemv": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
@@ -114,6 +116,41 @@ def int_dequant(codes, scales, zeros, K: int, bits: int, group: int = 128, out=N
                          _dev(zeros, torch.float16, "zeros"), _dev(out, torch.float16, "out"),
                          N, K, bits, group, _stream()))
     return out
+
+
+MAX_BATCH = 16
+
+
+class DequantItem(ctypes.Structure):
+    """Mirror of `potq_dequant_item`."""
+    _fields_ = [("codes", _vp), ("scales", _vp), ("zeros", _vp), ("out_f16", _vp), ("N", _i64), ("K", _i64)]
+
+
+def make_batch(mats, is_int: bool = False):
+    """mats: list of (codes, scales, zeros-or-None, out, K, bits) device tensors -> ctypes descriptor array.
+
+    The returned array only holds raw pointers: keep the tensors alive while it is in use."""
+    arr = (DequantItem * len(mats))()
+    for i, (codes, scales, zeros, out, K, bits) in enumerate(mats):
+        N = _shape_codes(codes, K, bits)
+        arr[i].codes = _dev(codes, torch.uint8, "codes")
+        arr[i].scales = _dev(scales, torch.float16, "scales")
+        arr[i].zeros = _dev(zeros, torch.float16, "zeros") if is_int else None
+        arr[i].out_f16 = _dev(out, torch.float16, "out")
+        arr[i].N, arr[i].K = N, K
+    return arr
+
+
+def pot_dequant_batch(mats, bits: int, group: int = 128):
+    """mats: list of (codes, scales, out, K); one launch for all of them."""
+    arr = make_batch([(c, s, None, o, K, bits) for (c, s, o, K) in mats])
+    _ok(_lib.pot_dequant_batch(arr, len(mats), bits, group, _stream()))
+
+
+def int_dequant_batch(mats, bits: int, group: int = 128):
+    """mats: list of (codes, scales, zeros, out, K); one launch for all of them."""
+    arr = make_batch([(c, s, z, o, K, bits) for (c, s, z, o, K) in mats], is_int=True)
+    _ok(_lib.int_dequant_batch(arr, len(mats), bits, group, _stream()))
 
 
 def potq_repack(src, K: int, bits: int, to_layout: int = LAYOUT_TILE16, out=None):

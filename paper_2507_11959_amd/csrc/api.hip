@@ -8,6 +8,10 @@
 namespace potq {
 hipError_t run_dequant(bool is_int, const void *codes, const void *scales, const void *zeros, void *out,
                        int64_t N, int64_t K, int bits, int group, hipStream_t stream);
+int dequant_max_batch();
+hipError_t run_dequant_batch(bool is_int, int count, const void *const *codes, const void *const *scales,
+                             const void *const *zeros, void *const *out, const int64_t *N, const int64_t *K,
+                             int bits, int group, hipStream_t stream);
 hipError_t run_check_scales(const void *scales, int64_t count, int bits, void *bad_count_dev, hipStream_t stream);
 hipError_t run_repack(const void *src, void *dst, int64_t N, int64_t K, int bits, bool to_tiled, hipStream_t stream);
 hipError_t run_fill_zero(void *p, int64_t count, hipStream_t stream);
@@ -45,6 +49,38 @@ int dequant_entry(bool is_int, const void *codes, const void *scales, const void
     if (misaligned(codes) || misaligned(scales) || misaligned(out) || (is_int && misaligned(zeros)))
         return POTQ_ERR_ALIGN;
     return finish(potq::run_dequant(is_int, codes, scales, zeros, out, N, K, bits, group, (hipStream_t)stream));
+}
+
+int dequant_batch_entry(bool is_int, const potq_dequant_item *items, int count, int bits, int group, void *stream)
+{
+    if (bits != 2 && bits != 3) return POTQ_ERR_BITS;
+    if (group != 64 && group != 128) return POTQ_ERR_GROUP;
+    if (count < 0 || count > potq::dequant_max_batch()) return POTQ_ERR_SHAPE;
+    if (count == 0) return POTQ_OK;
+    if (!items) return POTQ_ERR_NULL;
+    const void *codes[POTQ_MAX_BATCH], *scales[POTQ_MAX_BATCH], *zeros[POTQ_MAX_BATCH];
+    void *out[POTQ_MAX_BATCH];
+    int64_t N[POTQ_MAX_BATCH], K[POTQ_MAX_BATCH];
+    int live = 0;
+    for (int i = 0; i < count; ++i) {
+        const potq_dequant_item &it = items[i];
+        const int st = check_common(it.N, it.K, bits, group, false);
+        if (st != POTQ_OK) return st;
+        if (it.N == 0 || it.K == 0) continue;
+        if (!it.codes || !it.scales || !it.out_f16 || (is_int && !it.zeros)) return POTQ_ERR_NULL;
+        if (misaligned(it.codes) || misaligned(it.scales) || misaligned(it.out_f16) ||
+            (is_int && misaligned(it.zeros)))
+            return POTQ_ERR_ALIGN;
+        codes[live] = it.codes;
+        scales[live] = it.scales;
+        zeros[live] = it.zeros;
+        out[live] = it.out_f16;
+        N[live] = it.N;
+        K[live] = it.K;
+        ++live;
+    }
+    return finish(potq::run_dequant_batch(is_int, live, codes, scales, zeros, out, N, K, bits, group,
+                                          (hipStream_t)stream));
 }
 
 int gemv_entry(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x, void *y,
@@ -126,6 +162,16 @@ int int_dequant(const void *codes, const void *scales, const void *zeros, void *
                 int bits, int group, void *hip_stream)
 {
     return dequant_entry(true, codes, scales, zeros, out_f16, N, K, bits, group, hip_stream);
+}
+
+int pot_dequant_batch(const potq_dequant_item *items_host, int count, int bits, int group, void *hip_stream)
+{
+    return dequant_batch_entry(false, items_host, count, bits, group, hip_stream);
+}
+
+int int_dequant_batch(const potq_dequant_item *items_host, int count, int bits, int group, void *hip_stream)
+{
+    return dequant_batch_entry(true, items_host, count, bits, group, hip_stream);
 }
 
 int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits, int to_layout, void *hip_stream)

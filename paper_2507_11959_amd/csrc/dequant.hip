@@ -13,10 +13,10 @@
 namespace potq {
 
 #ifndef POTQ_DQ_OCTETS
-#define POTQ_DQ_OCTETS 1
+#define POTQ_DQ_OCTETS 2
 #endif
 #ifndef POTQ_DQ_BLOCK
-#define POTQ_DQ_BLOCK 256
+#define POTQ_DQ_BLOCK 512
 #endif
 #ifndef POTQ_DQ_NT
 #define POTQ_DQ_NT 1
@@ -91,16 +91,17 @@ __device__ __forceinline__ u32x4 int_octet(uint32_t f, half2_t zm1024, half2_t s
     return out;
 }
 
+// The work of one workgroup: `block` indexes 256-thread slices of the matrix's octet stream.
 template <int BITS, bool IS_INT>
-__global__ __launch_bounds__(kDequantBlock) void dequant_kernel(
-    const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales,
-    const uint16_t *__restrict__ zeros, u32x4 *__restrict__ out, int64_t n_octets, int group_shift)
+__device__ __forceinline__ void dequant_block(const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales,
+                                              const uint16_t *__restrict__ zeros, u32x4 *__restrict__ out,
+                                              int64_t n_octets, int group_shift, int64_t block)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t wave = (int64_t)blockIdx.x * (kDequantBlock / kWave) + (threadIdx.x >> 6);
+    const int64_t wave = block * (kDequantBlock / kWave) + (threadIdx.x >> 6);
     const int64_t base = wave * kOctetsPerWave;
     if (base >= n_octets) return;
-    // lane = (quarter, l): quarter q owns octets base + q*64 .. +63, visited 16 lanes at a time
+    // lane = (quarter, l): quarter q owns a run of 16*U octets, visited 16 lanes (256 output bytes) at a time
     const int64_t o0 = base + (lane >> 4) * (16 * kOctetsPerLane) + (lane & 15);
     const int octet_shift = group_shift - 3;   // octets per group = group / 8
 
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(kDequantBlock) void dequant_kernel(
                 w = pot_octet<BITS>(f, s);
             }
 #if POTQ_DQ_NT
-            __builtin_nontemporal_store(w, &out[o]);
+            __builtin_nontemporal_store(w, &out[o]);   // the output is not read again by this pass
 #else
             out[o] = w;
 #endif
@@ -129,15 +130,50 @@ __global__ __launch_bounds__(kDequantBlock) void dequant_kernel(
 }
 
 template <int BITS, bool IS_INT>
+__global__ __launch_bounds__(kDequantBlock) void dequant_kernel(
+    const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales,
+    const uint16_t *__restrict__ zeros, u32x4 *__restrict__ out, int64_t n_octets, int group_shift)
+{
+    dequant_block<BITS, IS_INT>(codes, scales, zeros, out, n_octets, group_shift, blockIdx.x);
+}
+
+// Several matrices in one launch: every launch costs a fixed ramp-up and drain
+// (about 1.5 us here) during which HBM idles, so the matrices of a decoder
+// layer are best done together.  The descriptor table travels as a kernel argument.
+constexpr int kMaxBatch = 16;
+struct DequantBatch {
+    const uint32_t *codes[kMaxBatch];
+    const uint16_t *scales[kMaxBatch];
+    const uint16_t *zeros[kMaxBatch];
+    u32x4 *out[kMaxBatch];
+    int64_t n_octets[kMaxBatch];
+    uint32_t first_block[kMaxBatch + 1];   // prefix sum of workgroups per matrix
+    int count;
+};
+
+template <int BITS, bool IS_INT>
+__global__ __launch_bounds__(kDequantBlock) void dequant_batch_kernel(const DequantBatch batch, int group_shift)
+{
+    int i = 0;
+    while (i + 1 < batch.count && blockIdx.x >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
+    dequant_block<BITS, IS_INT>(batch.codes[i], batch.scales[i], batch.zeros[i], batch.out[i], batch.n_octets[i],
+                                group_shift, blockIdx.x - batch.first_block[i]);
+}
+
+static int64_t dequant_blocks(int64_t n_octets)
+{
+    const int64_t waves = (n_octets + kOctetsPerWave - 1) / kOctetsPerWave;
+    return (waves + (kDequantBlock / kWave) - 1) / (kDequantBlock / kWave);
+}
+
+template <int BITS, bool IS_INT>
 static hipError_t launch_dequant(const void *codes, const void *scales, const void *zeros, void *out,
                                  int64_t N, int64_t K, int group, hipStream_t stream)
 {
     const int64_t n_octets = N * K / 8;
-    const int64_t waves = (n_octets + kOctetsPerWave - 1) / kOctetsPerWave;
-    const int64_t blocks = (waves + (kDequantBlock / kWave) - 1) / (kDequantBlock / kWave);
     const int group_shift = (group == 128) ? 7 : 6;
-    hipLaunchKernelGGL((dequant_kernel<BITS, IS_INT>), dim3((unsigned)blocks), dim3(kDequantBlock), 0, stream,
-                       (const uint32_t *)codes, (const uint16_t *)scales, (const uint16_t *)zeros,
+    hipLaunchKernelGGL((dequant_kernel<BITS, IS_INT>), dim3((unsigned)dequant_blocks(n_octets)), dim3(kDequantBlock),
+                       0, stream, (const uint32_t *)codes, (const uint16_t *)scales, (const uint16_t *)zeros,
                        (u32x4 *)out, n_octets, group_shift);
     return hipGetLastError();
 }
@@ -150,6 +186,51 @@ hipError_t run_dequant(bool is_int, const void *codes, const void *scales, const
                          : launch_dequant<2, true>(codes, scales, zeros, out, N, K, group, stream);
     return bits == 3 ? launch_dequant<3, false>(codes, scales, zeros, out, N, K, group, stream)
                      : launch_dequant<2, false>(codes, scales, zeros, out, N, K, group, stream);
+}
+
+int dequant_max_batch() { return kMaxBatch; }
+
+// items: `count` non-empty matrices (count <= kMaxBatch), already validated by the caller.
+hipError_t run_dequant_batch(bool is_int, int count, const void *const *codes, const void *const *scales,
+                             const void *const *zeros, void *const *out, const int64_t *N, const int64_t *K,
+                             int bits, int group, hipStream_t stream)
+{
+    // largest matrix first: the workgroups of the small ones then fill the tail of the launch
+    int order[kMaxBatch];
+    for (int i = 0; i < count; ++i) order[i] = i;
+    for (int i = 1; i < count; ++i)
+        for (int j = i; j > 0 && N[order[j]] * K[order[j]] > N[order[j - 1]] * K[order[j - 1]]; --j) {
+            const int t = order[j];
+            order[j] = order[j - 1];
+            order[j - 1] = t;
+        }
+    DequantBatch b;
+    uint64_t blocks = 0;
+    for (int i = 0; i < kMaxBatch; ++i) {
+        const bool live = i < count;
+        const int k = live ? order[i] : 0;
+        b.codes[i] = live ? (const uint32_t *)codes[k] : nullptr;
+        b.scales[i] = live ? (const uint16_t *)scales[k] : nullptr;
+        b.zeros[i] = (live && is_int) ? (const uint16_t *)zeros[k] : nullptr;
+        b.out[i] = live ? (u32x4 *)out[k] : nullptr;
+        b.n_octets[i] = live ? N[k] * K[k] / 8 : 0;
+        b.first_block[i] = (uint32_t)blocks;
+        if (live) blocks += (uint64_t)dequant_blocks(b.n_octets[i]);
+    }
+    b.first_block[kMaxBatch] = (uint32_t)blocks;
+    b.count = count;
+    if (blocks == 0) return hipSuccess;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const int group_shift = (group == 128) ? 7 : 6;
+    const dim3 grid((unsigned)blocks), block(kDequantBlock);
+    if (is_int) {
+        if (bits == 3) hipLaunchKernelGGL((dequant_batch_kernel<3, true>), grid, block, 0, stream, b, group_shift);
+        else hipLaunchKernelGGL((dequant_batch_kernel<2, true>), grid, block, 0, stream, b, group_shift);
+    } else {
+        if (bits == 3) hipLaunchKernelGGL((dequant_batch_kernel<3, false>), grid, block, 0, stream, b, group_shift);
+        else hipLaunchKernelGGL((dequant_batch_kernel<2, false>), grid, block, 0, stream, b, group_shift);
+    }
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------

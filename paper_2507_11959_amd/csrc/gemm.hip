@@ -1,120 +1,222 @@
 // Fused de-quantise + GEMM on the matrix cores (tiled layout), gfx950.
 //
-// Y[m,n] = sum_k X[m,k] W~[n,k].  A wavefront owns one 16-row tile of W and a
-// strip of tokens.  Per scale group (128 columns) lane (r = lane % 16,
-// q = lane / 16) fetches the 32 codes of row r, column block q, builds the
-// group's byte table by integer addition into the scale's exponent field
-// (Sec. 4.2) and expands the codes, eight at a time, straight into the A
-// operand of v_mfma_f32_16x16x32_f16: A row = weight row r, A k-slot (q, i) =
-// column 32q + 8*step + i of the group.  The B operand is X with the same
-// k-slot assignment, so each lane reads 16 contiguous bytes of a token's row.
-// Accumulation is fp32 in the MFMA accumulators; one rounding to fp16 at the end.
+// Y[m,n] = sum_k X[m,k] W~[n,k].  A workgroup of WAVES wavefronts owns
+// WAVES*RM 16-row tiles of W and a strip of 16*CN tokens, and walks K one scale
+// group (128 columns) at a time.
+//
+//  - Weights never touch LDS.  Lane (r = lane % 16, q = lane / 16) fetches the
+//    32 codes of row r, column block q of the group (`bits` dwords), builds the
+//    group's byte table by integer addition into the scale's exponent field
+//    (Sec. 4.2) and expands the codes, eight at a time, straight into the A
+//    operand of v_mfma_f32_16x16x32_f16: A row = weight row r, A k-slot (q, i)
+//    = column 32q + 8*step + i of the group.
+//  - X goes through LDS, double buffered, already in B-operand order: for
+//    k-slot group (step, q) the 16*CN tokens' 8-value runs are contiguous, so a
+//    B fragment is one conflict-free ds_read_b128 per lane and is reused by all
+//    RM row tiles of the wavefront.
+//  - Accumulation is fp32 in the MFMA accumulators; one rounding to fp16 at the end.
 #include "potq_device.hpp"
 
 namespace potq {
 
-constexpr int kGemmBlock = 256;
-constexpr int kGemmWaves = kGemmBlock / kWave;
-constexpr int kTokTiles = 4;                       // 16-token MFMA tiles per wavefront
-constexpr int kTokPerBlock = 16 * kTokTiles;
-
-template <int BITS, bool IS_INT>
-__global__ __launch_bounds__(kGemmBlock) void gemm_tile16_kernel(
+template <int BITS, bool IS_INT, int WAVES, int RM, int CN>
+__global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
     const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, int M, int64_t N, int K)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
+    constexpr int MT = 16 * CN;                       // tokens per workgroup
+    constexpr int THREADS = WAVES * kWave;
+    constexpr int PPT = (MT * 16) / THREADS;          // 16-byte pieces of an X chunk per thread
+    static_assert((MT * 16) % THREADS == 0, "X chunk must divide evenly over the workgroup");
+    extern __shared__ u32x4 smem[];                   // [2 buffers][16 k-slot groups][MT tokens]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
     const int r = lane & 15;
     const int q = lane >> 4;
     const int G = K / kTileCols;
-    const int64_t rowtile = (int64_t)blockIdx.x * kGemmWaves + wave;
-    if (rowtile * kTileRows >= N) return;
-    const int m0 = blockIdx.y * kTokPerBlock;
-    const int64_t row = rowtile * kTileRows + r;
+    const int64_t rowtiles = N / kTileRows;
+    const int64_t rt0 = ((int64_t)blockIdx.x * WAVES + wave) * RM;
+    const int m0 = blockIdx.y * MT;
 
-    float4_t acc[kTokTiles];
+    // weight side: per row tile, pointer to this lane's word of slab 0 of group 0, and its scale row
+    const uint32_t *cptr[RM];
+    const uint16_t *sptr[RM];
+    const uint16_t *zptr[RM];
 #pragma unroll
-    for (int c = 0; c < kTokTiles; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int rm = 0; rm < RM; ++rm) {
+        int64_t rt = rt0 + rm;
+        if (rt >= rowtiles) rt = rowtiles - 1;        // surplus wavefronts redo the last tile and store nothing
+        cptr[rm] = codes + rt * G * (BITS * 64) + r * 4 + q;
+        sptr[rm] = scales + (rt * kTileRows + r) * G;
+        zptr[rm] = IS_INT ? zeros + (rt * kTileRows + r) * G : nullptr;
+    }
 
-    // token row of this lane in each token tile (B operand column = lane % 16)
-    const uint16_t *xrow[kTokTiles];
-    bool xok[kTokTiles];
+    // X side: this thread's pieces of a chunk (16 tokens x 4 consecutive 8-value runs per wavefront)
+    const uint16_t *xsrc[PPT];
+    int xslot[PPT];
+    bool xok[PPT];
 #pragma unroll
-    for (int c = 0; c < kTokTiles; ++c) {
-        const int m = m0 + 16 * c + r;
-        xok[c] = m < M;
-        xrow[c] = X + (int64_t)(xok[c] ? m : 0) * K + 32 * q;
+    for (int i = 0; i < PPT; ++i) {
+        const int p = tid + THREADS * i;
+        const int st = (p >> 4) & 3;                  // run inside a 32-column block = MFMA step
+        const int blk = p >> 6;
+        const int m = (p & 15) + 16 * (blk % CN);
+        const int qq = blk / CN;                      // 32-column block = A/B k-slice
+        xok[i] = (m0 + m) < M;
+        xsrc[i] = X + (int64_t)(xok[i] ? m0 + m : 0) * K + 32 * qq + 8 * st;
+        xslot[i] = (st * 4 + qq) * MT + m;
+    }
+
+    float4_t acc[RM][CN];
+#pragma unroll
+    for (int rm = 0; rm < RM; ++rm)
+#pragma unroll
+        for (int c = 0; c < CN; ++c) acc[rm][c] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    // prefetch group 0
+    u32x4 xreg[PPT];
+    uint32_t w[RM][BITS], s[RM], z[RM];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) xreg[i] = xok[i] ? *(const u32x4 *)(xsrc[i]) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int rm = 0; rm < RM; ++rm) {
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) w[rm][j] = cptr[rm][64 * j];
+        s[rm] = sptr[rm][0];
+        z[rm] = IS_INT ? (uint32_t)zptr[rm][0] : 0u;
     }
 
     for (int g = 0; g < G; ++g) {
-        const uint32_t *tp = codes + (rowtile * G + g) * (BITS * 64) + r * 4 + q;
-        uint32_t w[BITS];
+        u32x4 *buf = smem + (g & 1) * (16 * MT);
 #pragma unroll
-        for (int j = 0; j < BITS; ++j) w[j] = tp[64 * j];
-        const uint32_t s = scales[row * G + g];
-        PotTable pt;
-        IntTable it;
-        if (IS_INT)
-            it = int_table<BITS>(s, zeros[row * G + g]);
-        else
-            pt = pot_table<BITS>(s);
-        uint32_t sel[8];
-        if (BITS == 3)
-            selectors3(w[0], w[1], w[BITS - 1], sel);
-        else
-            selectors2(w[0], w[1], sel);
+        for (int i = 0; i < PPT; ++i) buf[xslot[i]] = xreg[i];
+        __syncthreads();    // buffer (g & 1) was last read in iteration g - 2, before the previous barrier
+
+        uint32_t wn[RM][BITS], sn[RM], zn[RM];
+        if (g + 1 < G) {
+#pragma unroll
+            for (int i = 0; i < PPT; ++i)
+                xreg[i] = xok[i] ? *(const u32x4 *)(xsrc[i] + (g + 1) * kTileCols) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int rm = 0; rm < RM; ++rm) {
+#pragma unroll
+                for (int j = 0; j < BITS; ++j) wn[rm][j] = cptr[rm][(int64_t)(g + 1) * (BITS * 64) + 64 * j];
+                sn[rm] = sptr[rm][g + 1];
+                zn[rm] = IS_INT ? (uint32_t)zptr[rm][g + 1] : 0u;
+            }
+        }
+
+        PotTable pt[RM];
+        IntTable it[RM];
+        uint32_t sel[RM][8];
+#pragma unroll
+        for (int rm = 0; rm < RM; ++rm) {
+            if (IS_INT)
+                it[rm] = int_table<BITS>(s[rm], z[rm]);
+            else
+                pt[rm] = pot_table<BITS>(s[rm]);
+            if (BITS == 3)
+                selectors3(w[rm][0], w[rm][1], w[rm][BITS - 1], sel[rm]);
+            else
+                selectors2(w[rm][0], w[rm][1], sel[rm]);
+        }
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            uint32_t a0, a1, a2, a3;
-            if (IS_INT) {
-                int_lookup(it, sel[2 * st], a0, a1);
-                int_lookup(it, sel[2 * st + 1], a2, a3);
-            } else {
-                pot_lookup(pt, sel[2 * st], a0, a1);
-                pot_lookup(pt, sel[2 * st + 1], a2, a3);
-            }
-            const half8_t av = __builtin_bit_cast(half8_t, (u32x4{a0, a1, a2, a3}));
+            half8_t b[CN];
 #pragma unroll
-            for (int c = 0; c < kTokTiles; ++c) {
-                u32x4 b = u32x4{0u, 0u, 0u, 0u};
-                if (xok[c]) b = *(const u32x4 *)(xrow[c] + g * kTileCols + 8 * st);
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, __builtin_bit_cast(half8_t, b), acc[c], 0, 0, 0);
+            for (int c = 0; c < CN; ++c) b[c] = __builtin_bit_cast(half8_t, buf[(st * 4 + q) * MT + 16 * c + r]);
+#pragma unroll
+            for (int rm = 0; rm < RM; ++rm) {
+                uint32_t a0, a1, a2, a3;
+                if (IS_INT) {
+                    int_lookup(it[rm], sel[rm][2 * st], a0, a1);
+                    int_lookup(it[rm], sel[rm][2 * st + 1], a2, a3);
+                } else {
+                    pot_lookup(pt[rm], sel[rm][2 * st], a0, a1);
+                    pot_lookup(pt[rm], sel[rm][2 * st + 1], a2, a3);
+                }
+                const half8_t av = __builtin_bit_cast(half8_t, (u32x4{a0, a1, a2, a3}));
+#pragma unroll
+                for (int c = 0; c < CN; ++c)
+                    acc[rm][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[c], acc[rm][c], 0, 0, 0);
+            }
+        }
+
+        if (g + 1 < G) {
+#pragma unroll
+            for (int rm = 0; rm < RM; ++rm) {
+#pragma unroll
+                for (int j = 0; j < BITS; ++j) w[rm][j] = wn[rm][j];
+                s[rm] = sn[rm];
+                z[rm] = zn[rm];
             }
         }
     }
 
-    // D: lane holds token m0 + 16c + (lane % 16), weight rows 4*(lane / 16) + i
+    // D: lane holds token m0 + 16c + (lane % 16), weight rows 4*(lane / 16) + i of each row tile
+    typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int c = 0; c < kTokTiles; ++c) {
-        const int m = m0 + 16 * c + r;
-        if (m < M) {
-            typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-            half4_t h;
+    for (int rm = 0; rm < RM; ++rm) {
+        const int64_t rt = rt0 + rm;
+        if (rt >= rowtiles) continue;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) h[i] = (_Float16)acc[c][i];
-            *(half4_t *)(Y + (int64_t)m * N + rowtile * kTileRows + 4 * q) = h;
+        for (int c = 0; c < CN; ++c) {
+            const int m = m0 + 16 * c + r;
+            if (m < M) {
+                half4_t h;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) h[i] = (_Float16)acc[rm][c][i];
+                *(half4_t *)(Y + (int64_t)m * N + rt * kTileRows + 4 * q) = h;
+            }
         }
     }
+}
+
+template <int BITS, bool IS_INT, int WAVES, int RM, int CN>
+static void launch_gemm_cfg(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
+                            int64_t M, int64_t N, int64_t K, hipStream_t stream)
+{
+    const int64_t rowtiles = N / kTileRows;
+    const dim3 grid((unsigned)((rowtiles + WAVES * RM - 1) / (WAVES * RM)), (unsigned)((M + 16 * CN - 1) / (16 * CN)));
+    const size_t lds = (size_t)2 * 16 * (16 * CN) * sizeof(u32x4);
+    hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN>), grid, dim3(WAVES * kWave), lds, stream,
+                       (const uint32_t *)codes, (const uint16_t *)scales, (const uint16_t *)zeros,
+                       (const uint16_t *)X, (uint16_t *)Y, (int)M, N, (int)K);
+}
+
+#ifndef POTQ_GEMM_BIG_RM
+#define POTQ_GEMM_BIG_RM 2
+#endif
+#ifndef POTQ_GEMM_BIG_CN
+#define POTQ_GEMM_BIG_CN 8
+#endif
+
+template <int BITS, bool IS_INT>
+static void launch_gemm(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
+                        int64_t M, int64_t N, int64_t K, hipStream_t stream)
+{
+    if (M <= 16)
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, stream);
+    else if (M <= 32)
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2>(codes, scales, zeros, X, Y, M, N, K, stream);
+    else if (M <= 64)
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4>(codes, scales, zeros, X, Y, M, N, K, stream);
+    else
+        launch_gemm_cfg<BITS, IS_INT, 4, POTQ_GEMM_BIG_RM, POTQ_GEMM_BIG_CN>(codes, scales, zeros, X, Y, M, N, K, stream);
 }
 
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, hipStream_t stream)
 {
-    const int64_t rowtiles = N / kTileRows;
-    const dim3 grid((unsigned)((rowtiles + kGemmWaves - 1) / kGemmWaves),
-                    (unsigned)((M + kTokPerBlock - 1) / kTokPerBlock));
-    const dim3 block(kGemmBlock);
-#define POTQ_LAUNCH_GEMM(B, I)                                                                             \
-    hipLaunchKernelGGL((gemm_tile16_kernel<B, I>), grid, block, 0, stream, (const uint32_t *)codes,        \
-                       (const uint16_t *)scales, (const uint16_t *)zeros, (const uint16_t *)X, (uint16_t *)Y, \
-                       (int)M, N, (int)K)
     if (is_int) {
-        if (bits == 3) POTQ_LAUNCH_GEMM(3, true); else POTQ_LAUNCH_GEMM(2, true);
+        if (bits == 3) launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, stream);
+        else launch_gemm<2, true>(codes, scales, zeros, X, Y, M, N, K, stream);
     } else {
-        if (bits == 3) POTQ_LAUNCH_GEMM(3, false); else POTQ_LAUNCH_GEMM(2, false);
+        if (bits == 3) launch_gemm<3, false>(codes, scales, zeros, X, Y, M, N, K, stream);
+        else launch_gemm<2, false>(codes, scales, zeros, X, Y, M, N, K, stream);
     }
-#undef POTQ_LAUNCH_GEMM
     return hipGetLastError();
 }
 

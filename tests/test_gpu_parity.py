@@ -47,6 +47,42 @@ def test_int_dequant_bit_exact(potq, bits, group, N, K):
 
 
 @pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("is_int", [False, True])
+def test_dequant_batch_equals_single_calls_and_oracle(potq, bits, is_int):
+    # several matrices of different sizes (ragged tails, one empty) in one launch
+    shapes = [(37, 640), (1, 128), (0, 256), (16, 2048), (129, 4096), (5, 11008), (64, 128)]
+    G = 128
+    mats, wants = [], []
+    for i, (N, K) in enumerate(shapes):
+        packed = workloads.packed_codes(31 * i + bits, N, K, bits)
+        if is_int:
+            S, Z = workloads.int_scales_zeros(37 * i + bits, N, K, bits, G)
+            want = oracle.int_dequant(packed, S, Z, K, bits, G, nthreads=4)
+        else:
+            S, Z = workloads.pot_scales(41 * i + bits, N, K, G), None
+            want = oracle.pot_dequant(packed, S, K, bits, G, nthreads=4)
+        out = torch.full((N, K), 7.0, dtype=torch.float16, device="cuda:0")
+        if is_int:
+            mats.append((dev(packed), dev(S), dev(Z), out, K))
+        else:
+            mats.append((dev(packed), dev(S), out, K))
+        wants.append(want)
+    if is_int:
+        potq.int_dequant_batch(mats, bits, G)
+    else:
+        potq.pot_dequant_batch(mats, bits, G)
+    for m, want in zip(mats, wants):
+        got = host_bits(m[-2])
+        assert np.array_equal(got, want)
+    # too many matrices is an error, not a crash
+    from paper_2507_11959_amd import binding
+    arr = binding.make_batch([(m[0], m[1], None, m[-2], m[-1], bits) for m in mats if m[0].numel()])
+    assert binding.raw().pot_dequant_batch(arr, 17, bits, G, None) == 4
+    assert binding.raw().pot_dequant_batch(None, 3, bits, G, None) == 1
+    assert binding.raw().pot_dequant_batch(None, 0, bits, G, None) == 0
+
+
+@pytest.mark.parametrize("bits", [2, 3])
 def test_pot_dequant_structured_pattern(potq, bits):
     # code(n,k) = (n + k) mod 2^b, scale(n,g) = 2^((n+g) mod 8 - 8): index mix-ups change the output
     N, K, G = 40, 1024, 128
