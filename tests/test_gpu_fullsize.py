@@ -1,0 +1,149 @@
+"""GPU parity at the full sizes of the benchmark workloads, through the same
+entry points and launch configurations bench.py times.  Where the oracle can
+afford it the whole output is compared; for the 70B / 13B sizes a random sample
+of weight rows is compared against the oracle and properties that hold for any
+in-domain input are checked on the whole output (on the GPU, with integer ops)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_util import REL_TOL, dev, host_bits, rel_err
+
+pytestmark = pytest.mark.gpu
+G = workloads.GROUP
+
+
+@pytest.fixture(scope="module")
+def potq():
+    import paper_2507_11959_amd as p
+    return p
+
+
+def _threads():
+    import os
+    return min(16, len(os.sched_getaffinity(0)))
+
+
+def _invariants(out: torch.Tensor, scales: torch.Tensor, codes_sampled_ok: bool, bits: int):
+    """Low 10 bits = the group's scale's, exponent field moved by 0..qmax, computed on the GPU."""
+    qmax = 2 ** (bits - 1) - 1
+    o = out.view(torch.int16).to(torch.int32) & 0xFFFF
+    s = scales.view(torch.int16).to(torch.int32) & 0xFFFF
+    s = s.repeat_interleave(G, dim=1)
+    assert bool(((o & 0x3FF) == (s & 0x3FF)).all())
+    d = ((o >> 10) & 31) - ((s >> 10) & 31)
+    assert int(d.min()) >= 0 and int(d.max()) <= qmax
+    # with uniform random codes every level and both signs occur
+    assert int(d.max()) == qmax and int((o >> 15).max()) == 1 and int((o >> 15).min()) == 0
+
+
+def test_config0_single_4096_3bit_dequant_full(potq):
+    N, K, bits = 4096, 4096, 3
+    packed, scales = workloads.pot_matrix(0, 0, N, K, bits, G)
+    want = oracle.pot_dequant(packed, scales, K, bits, G, nthreads=_threads())
+    got = host_bits(potq.pot_dequant(dev(packed), dev(scales), K, bits, G))
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("is_int", [False, True])
+def test_config1_llama7b_layer_2bit_batch_full(potq, is_int):
+    bits = 2
+    mats, wants = [], []
+    for i, (name, N, K) in enumerate(workloads.LLAMA2_7B_LAYER):
+        packed = workloads.packed_codes(workloads.seed_of(1, i, 0), N, K, bits)
+        out = torch.empty((N, K), dtype=torch.float16, device="cuda:0")
+        if is_int:
+            S, Z = workloads.int_scales_zeros(workloads.seed_of(1, i, 3), N, K, bits, G)
+            mats.append((dev(packed), dev(S), dev(Z), out, K))
+            wants.append((packed, S, Z))
+        else:
+            S = workloads.pot_scales(workloads.seed_of(1, i, 1), N, K, G)
+            mats.append((dev(packed), dev(S), out, K))
+            wants.append((packed, S, None))
+    if is_int:
+        potq.int_dequant_batch(mats, bits, G)
+    else:
+        potq.pot_dequant_batch(mats, bits, G)
+    for m, (packed, S, Z), (name, N, K) in zip(mats, wants, workloads.LLAMA2_7B_LAYER):
+        if is_int:
+            want = oracle.int_dequant(packed, S, Z, K, bits, G, nthreads=_threads())
+        else:
+            want = oracle.pot_dequant(packed, S, K, bits, G, nthreads=_threads())
+        assert np.array_equal(host_bits(m[-2]), want), name
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_config3_llama70b_layer_dequant_sampled_and_invariants(potq, bits):
+    rng = np.random.default_rng(70 + bits)
+    mats, keep = [], []
+    for i, (name, N, K) in enumerate(workloads.LLAMA2_70B_LAYER):
+        packed, scales = workloads.pot_matrix(3, i, N, K, bits, G)
+        out = torch.empty((N, K), dtype=torch.float16, device="cuda:0")
+        d_scales = dev(scales)
+        mats.append((dev(packed), d_scales, out, K))
+        keep.append((name, N, K, packed, scales))
+    potq.pot_dequant_batch(mats, bits, G)
+    for (name, N, K, packed, scales), m in zip(keep, mats):
+        rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 96)]))
+        want = oracle.pot_dequant(packed[rows], scales[rows], K, bits, G, nthreads=_threads())
+        got = host_bits(m[2][torch.from_numpy(rows).to("cuda:0")])
+        assert np.array_equal(got, want), name
+        _invariants(m[2], m[1], True, bits)
+
+
+@pytest.mark.parametrize("is_int", [False, True])
+def test_config2_gemv_3bit_7b_shapes_full(potq, is_int):
+    bits = 3
+    for i, (name, N, K) in enumerate(workloads.GEMV_7B_SHAPES):
+        packed = workloads.packed_codes(workloads.seed_of(2, i, 0), N, K, bits)
+        x = workloads.activations(workloads.seed_of(2, i, 2), 1, K)
+        tiled = potq.potq_repack(dev(packed), K, bits)
+        if is_int:
+            S, Z = workloads.int_scales_zeros(workloads.seed_of(2, i, 3), N, K, bits, G)
+            got = host_bits(potq.int_gemv(tiled, dev(S), dev(Z), dev(x[0]), K, bits))
+        else:
+            S, Z = workloads.pot_scales(workloads.seed_of(2, i, 1), N, K, G), None
+            got = host_bits(potq.pot_gemv(tiled, dev(S), dev(x[0]), K, bits))
+        want = oracle.gemm(packed, S, Z, x, K, bits, G, nthreads=_threads())[0]
+        e, nw, nfloor = rel_err(got, want)
+        assert e <= REL_TOL, (name, e, nw, nfloor)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_config3_llama70b_gemv_full(potq, bits):
+    for i, (name, N, K) in enumerate(workloads.LLAMA2_70B_LAYER):
+        if i in (1, 3, 5):      # o, v, up repeat the shapes of q, k, gate
+            continue
+        packed, S = workloads.pot_matrix(3, i, N, K, bits, G)
+        x = workloads.activations(workloads.seed_of(3, i, 2), 1, K)
+        tiled = potq.potq_repack(dev(packed), K, bits)
+        got = host_bits(potq.pot_gemv(tiled, dev(S), dev(x[0]), K, bits))
+        want = oracle.gemm(packed, S, None, x, K, bits, G, nthreads=_threads())[0]
+        e, nw, nfloor = rel_err(got, want)
+        assert e <= REL_TOL, (name, e, nw, nfloor)
+
+
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("M", workloads.GEMM_TOKENS)
+def test_config4_gemm_3bit_13b_shapes_sampled_rows(potq, M, is_int):
+    bits = 3
+    rng = np.random.default_rng(13 + M)
+    for i, (name, N, K) in enumerate(workloads.GEMM_13B_SHAPES):
+        packed = workloads.packed_codes(workloads.seed_of(4, i, 0), N, K, bits)
+        X = workloads.activations(workloads.seed_of(4, i, 2) + M, M, K)
+        tiled = potq.potq_repack(dev(packed), K, bits)
+        if is_int:
+            S, Z = workloads.int_scales_zeros(workloads.seed_of(4, i, 3), N, K, bits, G)
+            Y = potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits)
+        else:
+            S, Z = workloads.pot_scales(workloads.seed_of(4, i, 1), N, K, G), None
+            Y = potq.pot_gemm(tiled, dev(S), dev(X), K, bits)
+        rows = np.unique(np.concatenate([[0, 15, 16, N - 1], rng.integers(0, N, 200)]))
+        want = oracle.gemm(packed[rows], S[rows], None if Z is None else Z[rows], X, K, bits, G,
+                           nthreads=_threads())
+        got = host_bits(Y[:, torch.from_numpy(rows).to("cuda:0")].contiguous())
+        e, nw, nfloor = rel_err(got, want)
+        assert e <= REL_TOL, (name, M, e, nw, nfloor)
+        assert bool(torch.isfinite(Y).all())
