@@ -250,9 +250,11 @@ def main() -> int:
             for M in workloads.GEMM_TOKENS:
                 X = to_dev(workloads.activations(workloads.seed_of(4, i, 2) + M, M, K))
                 Y = torch.empty((M, N), dtype=torch.float16, device=dev)
-                pa = (tiled.data_ptr(), sc.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1, stream)
+                ws = potq.gemm_workspace(M, N, K, b3)
+                wp, wn = (ws.data_ptr(), ws.numel()) if ws is not None else (None, 0)
+                pa = (tiled.data_ptr(), sc.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1, wp, wn, stream)
                 ia = (tiled.data_ptr(), Sd.data_ptr(), Zd.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1,
-                      stream)
+                      wp, wn, stream)
                 us_p = _time_steps(torch, lambda: check(lib.pot_gemm(*pa)), 30, 3) * 1e3
                 us_i = _time_steps(torch, lambda: check(lib.int_gemm(*ia)), 30, 3) * 1e3
                 tf = 2.0 * M * N * K / us_p / 1e6

@@ -159,13 +159,26 @@ int int_gemv(const void *codes, const void *scales, const void *zeros, const voi
  *   Y[m,n] = fp16( sum_k X[m,k] * W~[n,k] ),   X: M x K fp16 row-major,
  *   Y: M x N fp16 row-major (Y = X . W~^T, the nn.Linear convention).
  * fp16 MFMA with fp32 accumulation.  `codes` must be in POTQ_LAYOUT_TILE16.
+ *
+ * `workspace` is optional device scratch memory (16-byte aligned) owned by the
+ * caller.  With few tokens there are too few output tiles to occupy the chip, so
+ * the kernel splits K, writes fp32 partial sums to the workspace and adds them
+ * in a fixed order in a second small kernel (results stay reproducible).
+ * potq_gemm_workspace_bytes() returns the size that allows the preferred split
+ * (0 when no split would be used); a NULL or smaller workspace is valid and
+ * only means fewer splits.  The workspace may be reused by the next call on the
+ * same stream; concurrent calls on different streams need separate workspaces.
  */
+size_t potq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
+
 int pot_gemm(const void *codes, const void *scales, const void *X_f16, void *Y_f16,
-             int64_t M, int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
+             int64_t M, int64_t N, int64_t K, int bits, int group, int layout,
+             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* int_gemm -- the same with W~ as defined by int_dequant. */
 int int_gemm(const void *codes, const void *scales, const void *zeros, const void *X_f16, void *Y_f16,
-             int64_t M, int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
+             int64_t M, int64_t N, int64_t K, int bits, int group, int layout,
+             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * pot_check_scales -- count the scales outside the domain on which the

@@ -39,8 +39,9 @@ EXPORTS = {
     "potq_repack": (_int, [_vp, _vp, _i64, _i64, _int, _int, _vp]),
     "pot_gemv": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
     "int_gemv": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
-    "pot_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp]),
-    "int_gemm": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp]),
+    "potq_gemm_workspace_bytes": (ctypes.c_size_t, [_i64, _i64, _i64, _int]),
+    "pot_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
+    "int_gemm": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
     "pot_check_scales": (_int, [_vp, _i64, _int, _vp, _vp]),
 }
 for _name, (_res, _args) in EXPORTS.items():
@@ -186,29 +187,45 @@ def int_gemv(codes, scales, zeros, x, K: int, bits: int, group: int = 128, layou
     return out
 
 
-def pot_gemm(codes, scales, X, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16, out=None):
+def gemm_workspace(M: int, N: int, K: int, bits: int, device="cuda:0"):
+    """A workspace tensor of the size potq_gemm_workspace_bytes() asks for (None if it asks for nothing)."""
+    n = _lib.potq_gemm_workspace_bytes(M, N, K, bits)
+    return torch.empty((n,), dtype=torch.uint8, device=device) if n else None
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+
+
+def pot_gemm(codes, scales, X, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16, out=None,
+             workspace=None):
     N = _shape_codes(codes, K, bits)
     if X.dim() != 2 or X.shape[1] != K:
         raise ValueError("X must be (M, K)")
     M = X.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=codes.device)
+    wp, wn = _ws(workspace)
     _ok(_lib.pot_gemm(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                       _dev(X, torch.float16, "X"), _dev(out, torch.float16, "Y"), M, N, K, bits, group, layout,
-                      _stream()))
+                      wp, wn, _stream()))
     return out
 
 
-def int_gemm(codes, scales, zeros, X, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16, out=None):
+def int_gemm(codes, scales, zeros, X, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16, out=None,
+             workspace=None):
     N = _shape_codes(codes, K, bits)
     if X.dim() != 2 or X.shape[1] != K:
         raise ValueError("X must be (M, K)")
     M = X.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=codes.device)
+    wp, wn = _ws(workspace)
     _ok(_lib.int_gemm(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                       _dev(zeros, torch.float16, "zeros"), _dev(X, torch.float16, "X"),
-                      _dev(out, torch.float16, "Y"), M, N, K, bits, group, layout, _stream()))
+                      _dev(out, torch.float16, "Y"), M, N, K, bits, group, layout, wp, wn, _stream()))
     return out
 
 

@@ -19,7 +19,9 @@ size_t gemv_lds_bytes(int64_t K);
 hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
                            void *y, int64_t N, int64_t K, int bits, hipStream_t stream);
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
-                           void *Y, int64_t M, int64_t N, int64_t K, int bits, hipStream_t stream);
+                           void *Y, int64_t M, int64_t N, int64_t K, int bits, void *ws, size_t ws_bytes,
+                           hipStream_t stream);
+size_t gemm_workspace_bytes(int64_t M, int64_t N);
 }  // namespace potq
 
 namespace {
@@ -102,7 +104,8 @@ int gemv_entry(bool is_int, const void *codes, const void *scales, const void *z
 }
 
 int gemm_entry(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
-               int64_t M, int64_t N, int64_t K, int bits, int group, int layout, void *stream)
+               int64_t M, int64_t N, int64_t K, int bits, int group, int layout, void *workspace,
+               size_t workspace_bytes, void *stream)
 {
     const int st = check_common(N, K, bits, group, true);
     if (st != POTQ_OK) return st;
@@ -116,7 +119,10 @@ int gemm_entry(bool is_int, const void *codes, const void *scales, const void *z
     if (!codes || !scales || !X || (is_int && !zeros)) return POTQ_ERR_NULL;
     if (misaligned(codes) || misaligned(scales) || misaligned(X) || (is_int && misaligned(zeros)))
         return POTQ_ERR_ALIGN;
-    return finish(potq::run_gemm_tile16(is_int, codes, scales, zeros, X, Y, M, N, K, bits, (hipStream_t)stream));
+    if (workspace && misaligned(workspace)) return POTQ_ERR_ALIGN;
+    if (!workspace) workspace_bytes = 0;
+    return finish(potq::run_gemm_tile16(is_int, codes, scales, zeros, X, Y, M, N, K, bits, workspace, workspace_bytes,
+                                        (hipStream_t)stream));
 }
 
 }  // namespace
@@ -198,16 +204,27 @@ int int_gemv(const void *codes, const void *scales, const void *zeros, const voi
     return gemv_entry(true, codes, scales, zeros, x_f16, y_f16, N, K, bits, group, layout, hip_stream);
 }
 
-int pot_gemm(const void *codes, const void *scales, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,
-             int bits, int group, int layout, void *hip_stream)
+size_t potq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits)
 {
-    return gemm_entry(false, codes, scales, nullptr, X_f16, Y_f16, M, N, K, bits, group, layout, hip_stream);
+    (void)K;
+    (void)bits;
+    if (M <= 0 || N <= 0) return 0;
+    return potq::gemm_workspace_bytes(M, N);
+}
+
+int pot_gemm(const void *codes, const void *scales, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,
+             int bits, int group, int layout, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return gemm_entry(false, codes, scales, nullptr, X_f16, Y_f16, M, N, K, bits, group, layout, workspace,
+                      workspace_bytes, hip_stream);
 }
 
 int int_gemm(const void *codes, const void *scales, const void *zeros, const void *X_f16, void *Y_f16, int64_t M,
-             int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream)
+             int64_t N, int64_t K, int bits, int group, int layout, void *workspace, size_t workspace_bytes,
+             void *hip_stream)
 {
-    return gemm_entry(true, codes, scales, zeros, X_f16, Y_f16, M, N, K, bits, group, layout, hip_stream);
+    return gemm_entry(true, codes, scales, zeros, X_f16, Y_f16, M, N, K, bits, group, layout, workspace,
+                      workspace_bytes, hip_stream);
 }
 
 int pot_check_scales(const void *scales, int64_t count, int bits, void *bad_count_dev, void *hip_stream)

@@ -15,6 +15,9 @@
 //    B fragment is one conflict-free ds_read_b128 per lane and is reused by all
 //    RM row tiles of the wavefront.
 //  - Accumulation is fp32 in the MFMA accumulators; one rounding to fp16 at the end.
+//  - Few-token shapes do not have enough output tiles to occupy 256 CUs, so K is
+//    split over blockIdx.z: every split writes its fp32 sums to the caller's
+//    workspace and a small second kernel adds them in a fixed order.
 #include "potq_device.hpp"
 
 namespace potq {
@@ -22,7 +25,8 @@ namespace potq {
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN>
 __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
-    const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, int M, int64_t N, int K)
+    const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, float *__restrict__ partial, int M, int64_t N, int K,
+    int groups_per_split)
 {
     constexpr int MT = 16 * CN;                       // tokens per workgroup
     constexpr int THREADS = WAVES * kWave;
@@ -39,6 +43,9 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     const int64_t rowtiles = N / kTileRows;
     const int64_t rt0 = ((int64_t)blockIdx.x * WAVES + wave) * RM;
     const int m0 = blockIdx.y * MT;
+    // split-K: blockIdx.z owns scale groups [g_begin, g_end); its fp32 sums go to partial[z] when gridDim.z > 1
+    const int g_begin = blockIdx.z * groups_per_split;
+    const int g_end = min(G, g_begin + groups_per_split);
 
     // weight side: per row tile, pointer to this lane's word of slab 0 of group 0, and its scale row
     const uint32_t *cptr[RM];
@@ -75,27 +82,28 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
 #pragma unroll
         for (int c = 0; c < CN; ++c) acc[rm][c] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    // prefetch group 0
+    // prefetch the first group
     u32x4 xreg[PPT];
     uint32_t w[RM][BITS], s[RM], z[RM];
 #pragma unroll
-    for (int i = 0; i < PPT; ++i) xreg[i] = xok[i] ? *(const u32x4 *)(xsrc[i]) : u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < PPT; ++i)
+        xreg[i] = xok[i] ? *(const u32x4 *)(xsrc[i] + g_begin * kTileCols) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
     for (int rm = 0; rm < RM; ++rm) {
 #pragma unroll
-        for (int j = 0; j < BITS; ++j) w[rm][j] = cptr[rm][64 * j];
-        s[rm] = sptr[rm][0];
-        z[rm] = IS_INT ? (uint32_t)zptr[rm][0] : 0u;
+        for (int j = 0; j < BITS; ++j) w[rm][j] = cptr[rm][(int64_t)g_begin * (BITS * 64) + 64 * j];
+        s[rm] = sptr[rm][g_begin];
+        z[rm] = IS_INT ? (uint32_t)zptr[rm][g_begin] : 0u;
     }
 
-    for (int g = 0; g < G; ++g) {
-        u32x4 *buf = smem + (g & 1) * (16 * MT);
+    for (int g = g_begin; g < g_end; ++g) {
+        u32x4 *buf = smem + ((g - g_begin) & 1) * (16 * MT);
 #pragma unroll
         for (int i = 0; i < PPT; ++i) buf[xslot[i]] = xreg[i];
         __syncthreads();    // buffer (g & 1) was last read in iteration g - 2, before the previous barrier
 
         uint32_t wn[RM][BITS], sn[RM], zn[RM];
-        if (g + 1 < G) {
+        if (g + 1 < g_end) {
 #pragma unroll
             for (int i = 0; i < PPT; ++i)
                 xreg[i] = xok[i] ? *(const u32x4 *)(xsrc[i] + (g + 1) * kTileCols) : u32x4{0u, 0u, 0u, 0u};
@@ -144,7 +152,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
             }
         }
 
-        if (g + 1 < G) {
+        if (g + 1 < g_end) {
 #pragma unroll
             for (int rm = 0; rm < RM; ++rm) {
 #pragma unroll
@@ -165,26 +173,73 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
         for (int c = 0; c < CN; ++c) {
             const int m = m0 + 16 * c + r;
             if (m < M) {
-                half4_t h;
+                const int64_t at = (int64_t)m * N + rt * kTileRows + 4 * q;
+                if (gridDim.z > 1) {
+                    *(float4_t *)(partial + (int64_t)blockIdx.z * M * N + at) = acc[rm][c];
+                } else {
+                    half4_t h;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) h[i] = (_Float16)acc[rm][c][i];
-                *(half4_t *)(Y + (int64_t)m * N + rt * kTileRows + 4 * q) = h;
+                    for (int i = 0; i < 4; ++i) h[i] = (_Float16)acc[rm][c][i];
+                    *(half4_t *)(Y + at) = h;
+                }
             }
         }
     }
 }
 
+// Y = fp16(sum over splits of partial[s]), summed in ascending s: reproducible.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4_t *__restrict__ partial,
+                                                          uint16_t *__restrict__ Y, int64_t quads, int splits)
+{
+    typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= quads) return;
+    float4_t sum = partial[i];
+    for (int s = 1; s < splits; ++s) sum += partial[(int64_t)s * quads + i];
+    half4_t h;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) h[k] = (_Float16)sum[k];
+    *(half4_t *)(Y + 4 * i) = h;
+}
+
+// Number of K splits: enough workgroups to occupy the chip about three times over,
+// at least four scale groups per split, and only as many as the workspace holds.
+static int choose_splits(int64_t workgroups, int64_t G, int64_t M, int64_t N, size_t workspace_bytes)
+{
+    int64_t want = (768 + workgroups - 1) / workgroups;
+    if (want > G / 4) want = G / 4;
+    if (want > 16) want = 16;
+    const int64_t fit = (int64_t)(workspace_bytes / ((size_t)M * (size_t)N * sizeof(float)));
+    if (want > fit) want = fit;
+    return want < 2 ? 1 : (int)want;
+}
+
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN>
 static void launch_gemm_cfg(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
-                            int64_t M, int64_t N, int64_t K, hipStream_t stream)
+                            int64_t M, int64_t N, int64_t K, void *workspace, size_t workspace_bytes,
+                            hipStream_t stream)
 {
     const int64_t rowtiles = N / kTileRows;
-    const dim3 grid((unsigned)((rowtiles + WAVES * RM - 1) / (WAVES * RM)), (unsigned)((M + 16 * CN - 1) / (16 * CN)));
+    const int64_t G = K / kTileCols;
+    const unsigned gx = (unsigned)((rowtiles + WAVES * RM - 1) / (WAVES * RM));
+    const unsigned gy = (unsigned)((M + 16 * CN - 1) / (16 * CN));
+    int splits = workspace ? choose_splits((int64_t)gx * gy, G, M, N, workspace_bytes) : 1;
+    int per = (int)((G + splits - 1) / splits);
+    splits = (int)((G + per - 1) / per);              // no empty split
     const size_t lds = (size_t)2 * 16 * (16 * CN) * sizeof(u32x4);
-    hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN>), grid, dim3(WAVES * kWave), lds, stream,
-                       (const uint32_t *)codes, (const uint16_t *)scales, (const uint16_t *)zeros,
-                       (const uint16_t *)X, (uint16_t *)Y, (int)M, N, (int)K);
+    hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN>), dim3(gx, gy, (unsigned)splits),
+                       dim3(WAVES * kWave), lds, stream, (const uint32_t *)codes, (const uint16_t *)scales,
+                       (const uint16_t *)zeros, (const uint16_t *)X, (uint16_t *)Y, (float *)workspace, (int)M, N,
+                       (int)K, per);
+    if (splits > 1) {
+        const int64_t quads = M * N / 4;
+        hipLaunchKernelGGL(gemm_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
+                           (const float4_t *)workspace, (uint16_t *)Y, quads, splits);
+    }
 }
+
+// Workspace that lets every supported shape use its preferred number of splits.
+size_t gemm_workspace_bytes(int64_t M, int64_t N) { return M <= 64 ? (size_t)16 * M * N * sizeof(float) : 0; }
 
 #ifndef POTQ_GEMM_BIG_RM
 #define POTQ_GEMM_BIG_RM 2
@@ -195,27 +250,29 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
 
 template <int BITS, bool IS_INT>
 static void launch_gemm(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
-                        int64_t M, int64_t N, int64_t K, hipStream_t stream)
+                        int64_t M, int64_t N, int64_t K, void *ws, size_t ws_bytes, hipStream_t stream)
 {
     if (M <= 16)
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
     else if (M <= 32)
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2>(codes, scales, zeros, X, Y, M, N, K, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
     else if (M <= 64)
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4>(codes, scales, zeros, X, Y, M, N, K, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
     else
-        launch_gemm_cfg<BITS, IS_INT, 4, POTQ_GEMM_BIG_RM, POTQ_GEMM_BIG_CN>(codes, scales, zeros, X, Y, M, N, K, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, POTQ_GEMM_BIG_RM, POTQ_GEMM_BIG_CN>(codes, scales, zeros, X, Y, M, N, K,
+                                                                              nullptr, 0, stream);
 }
 
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
-                           void *Y, int64_t M, int64_t N, int64_t K, int bits, hipStream_t stream)
+                           void *Y, int64_t M, int64_t N, int64_t K, int bits, void *ws, size_t ws_bytes,
+                           hipStream_t stream)
 {
     if (is_int) {
-        if (bits == 3) launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, stream);
-        else launch_gemm<2, true>(codes, scales, zeros, X, Y, M, N, K, stream);
+        if (bits == 3) launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        else launch_gemm<2, true>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
     } else {
-        if (bits == 3) launch_gemm<3, false>(codes, scales, zeros, X, Y, M, N, K, stream);
-        else launch_gemm<2, false>(codes, scales, zeros, X, Y, M, N, K, stream);
+        if (bits == 3) launch_gemm<3, false>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        else launch_gemm<2, false>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
     }
     return hipGetLastError();
 }

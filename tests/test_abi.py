@@ -27,7 +27,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"pot_dequant", "int_dequant", "pot_gemv", "int_gemv", "pot_gemm", "int_gemm", "potq_repack",
-            "pot_check_scales", "potq_version", "potq_strerror", "potq_packed_row_bytes",
+            "pot_check_scales", "pot_dequant_batch", "int_dequant_batch", "potq_gemm_workspace_bytes", "potq_version", "potq_strerror", "potq_packed_row_bytes",
             "potq_packed_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -73,10 +73,14 @@ def test_host_side_validation(lib):
     assert g(A, A, A, None, 16, 128, 3, 128, 1, None) == NULL
     assert g(None, None, None, None, 0, 128, 3, 128, 1, None) == OK
     m = lib.pot_gemm
-    assert m(A, A, A, A, -2, 16, 128, 3, 128, 1, None) == SHAPE
-    assert m(A, A, A, A, 4, 16, 128, 3, 128, 0, None) == LAYOUT
-    assert m(None, None, None, None, 0, 16, 128, 3, 128, 1, None) == OK
-    assert lib.int_gemm(A, A, None, A, A, 4, 16, 128, 3, 128, 1, None) == NULL
+    assert m(A, A, A, A, -2, 16, 128, 3, 128, 1, None, 0, None) == SHAPE
+    assert m(A, A, A, A, 4, 16, 128, 3, 128, 0, None, 0, None) == LAYOUT
+    assert m(None, None, None, None, 0, 16, 128, 3, 128, 1, None, 0, None) == OK
+    assert m(A, A, A, A, 4, 16, 128, 3, 128, 1, MIS, 1 << 20, None) == ALIGN
+    assert lib.int_gemm(A, A, None, A, A, 4, 16, 128, 3, 128, 1, None, 0, None) == NULL
+    assert lib.potq_gemm_workspace_bytes(16, 4096, 4096, 3) == 16 * 16 * 4096 * 4
+    assert lib.potq_gemm_workspace_bytes(256, 4096, 4096, 3) == 0
+    assert lib.potq_gemm_workspace_bytes(0, 4096, 4096, 3) == 0
     assert lib.int_gemv(A, A, A, MIS, A, 16, 128, 3, 128, 1, None) == ALIGN
     r = lib.potq_repack
     assert r(A, A, 24, 128, 3, 1, None) == SHAPE

@@ -136,10 +136,10 @@ def test_config4_gemm_3bit_13b_shapes_sampled_rows(potq, M, is_int):
         tiled = potq.potq_repack(dev(packed), K, bits)
         if is_int:
             S, Z = workloads.int_scales_zeros(workloads.seed_of(4, i, 3), N, K, bits, G)
-            Y = potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits)
+            Y = potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits, workspace=potq.gemm_workspace(M, N, K, bits))
         else:
             S, Z = workloads.pot_scales(workloads.seed_of(4, i, 1), N, K, G), None
-            Y = potq.pot_gemm(tiled, dev(S), dev(X), K, bits)
+            Y = potq.pot_gemm(tiled, dev(S), dev(X), K, bits, workspace=potq.gemm_workspace(M, N, K, bits))
         rows = np.unique(np.concatenate([[0, 15, 16, N - 1], rng.integers(0, N, 200)]))
         want = oracle.gemm(packed[rows], S[rows], None if Z is None else Z[rows], X, K, bits, G,
                            nthreads=_threads())

@@ -151,8 +151,9 @@ def _gemv_inputs(seed, N, K, bits, is_int):
     return packed, S, Z
 
 
-def _run_gemm(potq, packed, S, Z, X, K, bits):
+def _run_gemm(potq, packed, S, Z, X, K, bits, use_workspace=True):
     tiled = potq.potq_repack(dev(packed), K, bits)
+    ws = potq.gemm_workspace(X.shape[0], packed.shape[0], K, bits) if use_workspace else None
     if X.shape[0] == 1:
         if Z is None:
             y = potq.pot_gemv(tiled, dev(S), dev(X[0]), K, bits)
@@ -160,8 +161,8 @@ def _run_gemm(potq, packed, S, Z, X, K, bits):
             y = potq.int_gemv(tiled, dev(S), dev(Z), dev(X[0]), K, bits)
         return host_bits(y)[None, :]
     if Z is None:
-        return host_bits(potq.pot_gemm(tiled, dev(S), dev(X), K, bits))
-    return host_bits(potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits))
+        return host_bits(potq.pot_gemm(tiled, dev(S), dev(X), K, bits, workspace=ws))
+    return host_bits(potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits, workspace=ws))
 
 
 @pytest.mark.parametrize("is_int", [False, True])
@@ -213,6 +214,27 @@ def test_gemm_vs_oracle(potq, bits, M, is_int):
     assert e <= REL_TOL, (e, nw, nfloor)
 
 
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("M,N,K", [(16, 64, 4096), (8, 48, 11008), (40, 128, 2560), (64, 32, 8192)])
+def test_gemm_split_k_matches_oracle_and_is_reproducible(potq, bits, M, N, K):
+    # few tokens and few rows: the workspace path splits K over several workgroups
+    packed, S, Z = _gemv_inputs(700 + M + bits, N, K, bits, False)
+    X = workloads.activations(800 + M, M, K)
+    want = oracle.gemm(packed, S, None, X, K, bits, 128, nthreads=8)
+    a = _run_gemm(potq, packed, S, None, X, K, bits, use_workspace=True)
+    b = _run_gemm(potq, packed, S, None, X, K, bits, use_workspace=True)
+    c = _run_gemm(potq, packed, S, None, X, K, bits, use_workspace=False)
+    assert np.array_equal(a, b)                       # fixed summation order: bit-identical reruns
+    for got in (a, c):
+        e, nw, nfloor = rel_err(got, want)
+        assert e <= REL_TOL, (e, nw, nfloor)
+    # a workspace too small for two splits is accepted and simply not used
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    tiny = torch.empty((64,), dtype=torch.uint8, device="cuda:0")
+    d = host_bits(potq.pot_gemm(tiled, dev(S), dev(X), K, bits, workspace=tiny))
+    assert np.array_equal(d, c)
+
+
 @pytest.mark.parametrize("is_int", [False, True])
 @pytest.mark.parametrize("bits", [2, 3])
 def test_gemm_one_hot_rows_give_exact_columns(potq, bits, is_int):
@@ -231,7 +253,7 @@ def test_empty_inputs_are_accepted(potq):
     e16 = torch.empty((0,), dtype=torch.float16, device="cuda:0")
     lib = __import__("paper_2507_11959_amd.binding", fromlist=["raw"]).raw()
     assert lib.pot_dequant(None, None, None, 0, 4096, 3, 128, None) == 0
-    assert lib.pot_gemm(None, None, None, None, 0, 16, 128, 3, 128, 1, None) == 0
+    assert lib.pot_gemm(None, None, None, None, 0, 16, 128, 3, 128, 1, None, 0, None) == 0
     # K = 0: products over an empty K are zero
     y = torch.full((16,), 7.0, dtype=torch.float16, device="cuda:0")
     assert lib.pot_gemv(None, None, None, y.data_ptr(), 16, 0, 3, 128, 1, None) == 0
