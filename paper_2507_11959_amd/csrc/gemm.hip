@@ -22,6 +22,16 @@
 
 namespace potq {
 
+#ifndef POTQ_GEMM_DEPTH_BIG
+#define POTQ_GEMM_DEPTH_BIG 2
+#endif
+#ifndef POTQ_GEMM_DEPTH_SMALL
+#define POTQ_GEMM_DEPTH_SMALL 2
+#endif
+#ifndef POTQ_GEMM_NT
+#define POTQ_GEMM_NT 0
+#endif
+
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN>
 __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
@@ -82,83 +92,98 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
 #pragma unroll
         for (int c = 0; c < CN; ++c) acc[rm][c] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    // prefetch the first group
-    u32x4 xreg[PPT];
-    uint32_t w[RM][BITS], s[RM], z[RM];
-#pragma unroll
-    for (int i = 0; i < PPT; ++i)
-        xreg[i] = xok[i] ? *(const u32x4 *)(xsrc[i] + g_begin * kTileCols) : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int rm = 0; rm < RM; ++rm) {
-#pragma unroll
-        for (int j = 0; j < BITS; ++j) w[rm][j] = cptr[rm][(int64_t)g_begin * (BITS * 64) + 64 * j];
-        s[rm] = sptr[rm][g_begin];
-        z[rm] = IS_INT ? (uint32_t)zptr[rm][g_begin] : 0u;
-    }
+    // Software pipeline.  Packed codes stream from HBM: they are requested kDepth
+    // groups ahead into a small register ring.  X comes from L2: it is requested
+    // kXStages groups ahead into registers and moves through two LDS buffers.
+    constexpr int kDepth = (CN >= 8) ? POTQ_GEMM_DEPTH_BIG : POTQ_GEMM_DEPTH_SMALL;
+    constexpr int kXStages = (PPT <= 4) ? 2 : 1;
+    static_assert(kDepth % 2 == 0, "LDS buffer and X stage are selected by the parity of the unrolled index");
+    uint32_t wr[kDepth][RM][BITS], sr[kDepth][RM], zr[kDepth][RM];
+    u32x4 xreg[kXStages][PPT];
 
-    for (int g = g_begin; g < g_end; ++g) {
-        u32x4 *buf = smem + ((g - g_begin) & 1) * (16 * MT);
-#pragma unroll
-        for (int i = 0; i < PPT; ++i) buf[xslot[i]] = xreg[i];
-        __syncthreads();    // buffer (g & 1) was last read in iteration g - 2, before the previous barrier
-
-        uint32_t wn[RM][BITS], sn[RM], zn[RM];
-        if (g + 1 < g_end) {
-#pragma unroll
-            for (int i = 0; i < PPT; ++i)
-                xreg[i] = xok[i] ? *(const u32x4 *)(xsrc[i] + (g + 1) * kTileCols) : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int rm = 0; rm < RM; ++rm) {
-#pragma unroll
-                for (int j = 0; j < BITS; ++j) wn[rm][j] = cptr[rm][(int64_t)(g + 1) * (BITS * 64) + 64 * j];
-                sn[rm] = sptr[rm][g + 1];
-                zn[rm] = IS_INT ? (uint32_t)zptr[rm][g + 1] : 0u;
-            }
-        }
-
-        PotTable pt[RM];
-        IntTable it[RM];
-        uint32_t sel[RM][8];
+    auto fetch_codes = [&](int slot, int g) {
+        const int gc = g < g_end ? g : g_end - 1;     // past the end: re-read the last group, never used
 #pragma unroll
         for (int rm = 0; rm < RM; ++rm) {
-            if (IS_INT)
-                it[rm] = int_table<BITS>(s[rm], z[rm]);
-            else
-                pt[rm] = pot_table<BITS>(s[rm]);
-            if (BITS == 3)
-                selectors3(w[rm][0], w[rm][1], w[rm][BITS - 1], sel[rm]);
-            else
-                selectors2(w[rm][0], w[rm][1], sel[rm]);
+#pragma unroll
+            for (int j = 0; j < BITS; ++j)
+#if POTQ_GEMM_NT
+                wr[slot][rm][j] = __builtin_nontemporal_load(cptr[rm] + (int64_t)gc * (BITS * 64) + 64 * j);
+#else
+                wr[slot][rm][j] = cptr[rm][(int64_t)gc * (BITS * 64) + 64 * j];
+#endif
+            sr[slot][rm] = sptr[rm][gc];
+            zr[slot][rm] = IS_INT ? (uint32_t)zptr[rm][gc] : 0u;
         }
+    };
+    auto fetch_x = [&](int stage, int g) {
+        const int gc = g < g_end ? g : g_end - 1;
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            half8_t b[CN];
+        for (int i = 0; i < PPT; ++i)
+            xreg[stage][i] = xok[i] ? *(const u32x4 *)(xsrc[i] + gc * kTileCols) : u32x4{0u, 0u, 0u, 0u};
+    };
+
 #pragma unroll
-            for (int c = 0; c < CN; ++c) b[c] = __builtin_bit_cast(half8_t, buf[(st * 4 + q) * MT + 16 * c + r]);
+    for (int d = 0; d < kDepth; ++d) fetch_codes(d, g_begin + d);
+#pragma unroll
+    for (int x = 0; x < kXStages; ++x) fetch_x(x, g_begin + x);
+
+    for (int gb = g_begin; gb < g_end; gb += kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            const int g = gb + d;
+            if (g >= g_end) break;                    // uniform over the workgroup
+            u32x4 *buf = smem + (d & 1) * (16 * MT);  // (g - g_begin) & 1 == d & 1
+#pragma unroll
+            for (int i = 0; i < PPT; ++i) buf[xslot[i]] = xreg[d % kXStages][i];
+            __syncthreads();    // this buffer was last read two groups ago, before the previous barrier
+            fetch_x(d % kXStages, g + kXStages);
+
+            uint32_t w[RM][BITS], s[RM], z[RM];
 #pragma unroll
             for (int rm = 0; rm < RM; ++rm) {
-                uint32_t a0, a1, a2, a3;
-                if (IS_INT) {
-                    int_lookup(it[rm], sel[rm][2 * st], a0, a1);
-                    int_lookup(it[rm], sel[rm][2 * st + 1], a2, a3);
-                } else {
-                    pot_lookup(pt[rm], sel[rm][2 * st], a0, a1);
-                    pot_lookup(pt[rm], sel[rm][2 * st + 1], a2, a3);
-                }
-                const half8_t av = __builtin_bit_cast(half8_t, (u32x4{a0, a1, a2, a3}));
+#pragma unroll
+                for (int j = 0; j < BITS; ++j) w[rm][j] = wr[d][rm][j];
+                s[rm] = sr[d][rm];
+                z[rm] = zr[d][rm];
+            }
+            fetch_codes(d, g + kDepth);
+
+            PotTable pt[RM];
+            IntTable it[RM];
+            uint32_t sel[RM][8];
+#pragma unroll
+            for (int rm = 0; rm < RM; ++rm) {
+                if (IS_INT)
+                    it[rm] = int_table<BITS>(s[rm], z[rm]);
+                else
+                    pt[rm] = pot_table<BITS>(s[rm]);
+                if (BITS == 3)
+                    selectors3(w[rm][0], w[rm][1], w[rm][BITS - 1], sel[rm]);
+                else
+                    selectors2(w[rm][0], w[rm][1], sel[rm]);
+            }
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                half8_t b[CN];
 #pragma unroll
                 for (int c = 0; c < CN; ++c)
-                    acc[rm][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[c], acc[rm][c], 0, 0, 0);
-            }
-        }
-
-        if (g + 1 < g_end) {
+                    b[c] = __builtin_bit_cast(half8_t, buf[(st * 4 + q) * MT + 16 * c + r]);
 #pragma unroll
-            for (int rm = 0; rm < RM; ++rm) {
+                for (int rm = 0; rm < RM; ++rm) {
+                    uint32_t a0, a1, a2, a3;
+                    if (IS_INT) {
+                        int_lookup(it[rm], sel[rm][2 * st], a0, a1);
+                        int_lookup(it[rm], sel[rm][2 * st + 1], a2, a3);
+                    } else {
+                        pot_lookup(pt[rm], sel[rm][2 * st], a0, a1);
+                        pot_lookup(pt[rm], sel[rm][2 * st + 1], a2, a3);
+                    }
+                    const half8_t av = __builtin_bit_cast(half8_t, (u32x4{a0, a1, a2, a3}));
 #pragma unroll
-                for (int j = 0; j < BITS; ++j) w[rm][j] = wn[rm][j];
-                s[rm] = sn[rm];
-                z[rm] = zn[rm];
+                    for (int c = 0; c < CN; ++c)
+                        acc[rm][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[c], acc[rm][c], 0, 0, 0);
+                }
             }
         }
     }

@@ -37,11 +37,7 @@ __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, u
             selectors2(L[0][b], L[1][b], sel);
 #pragma unroll
         for (int m = 0; m < 8; m += 2) {
-#if defined(POTQ_GEMV_DEBUG) && (POTQ_GEMV_DEBUG == 3 || POTQ_GEMV_DEBUG == 5)
-            const u32x4 xv = u32x4{s, s + 1, z, s ^ 5u};
-#else
             const u32x4 xv = xg[b * 4 + m / 2];     // columns 32b + 4m .. + 7
-#endif
             uint32_t e0, o0, e1, o1;
             if (IS_INT) {
                 int_lookup(it, sel[m], e0, o0);
@@ -51,26 +47,26 @@ __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, u
                 pot_lookup(pt, sel[m + 1], e1, o1);
             }
             const half8_t av = __builtin_bit_cast(half8_t, (u32x4{e0, o0, e1, o1}));
-#if defined(POTQ_GEMV_DEBUG) && (POTQ_GEMV_DEBUG == 4 || POTQ_GEMV_DEBUG == 5)
-            acc[m / 2] += __builtin_bit_cast(float4_t, (u32x4{e0, o0, e1, o1} ^ xv) & 0x3fffffffu);
-#else
             acc[m / 2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, __builtin_bit_cast(half8_t, xv), acc[m / 2], 0, 0, 0);
-#endif
         }
     }
 }
 
 constexpr int kXRun = 17;   // uint4 per scale group of x in LDS (16 + 1 of padding)
+constexpr int kGemvWaves = 8;
 
-// WAVES wavefronts per workgroup share one 16-row tile: wavefront w, lane group
-// t takes scale groups 4w + t, 4w + t + 4*WAVES, ...  The codes of the next
-// group are requested before the current one is expanded, and the first request
-// goes out before x is staged, so HBM latency overlaps the staging and the math.
-template <int BITS, bool IS_INT, int WAVES>
-__global__ __launch_bounds__(WAVES * kWave) void gemv_tile16_kernel(
+// A workgroup of 8 wavefronts stages x in LDS once and serves 8/S row tiles of 16
+// rows.  S wavefronts share a tile and split its scale groups: wavefront part p,
+// lane group t takes groups 4p + t, 4p + t + 4S, ...  Long rows want S = 8 (all
+// of K in flight at once), tall matrices want S = 1 or 2 (long-lived wavefronts,
+// no cross-wavefront sums).  The codes of the next round are requested before
+// the current one is expanded, and the first request goes out before x is staged.
+template <int BITS, bool IS_INT, int S>
+__global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
-    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int K)
+    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K)
 {
+    constexpr int R = kGemvWaves / S;                   // row tiles per workgroup
     extern __shared__ u32x4 smem[];
     // x as fp16 pairs, one 256-byte run per scale group, runs padded to 272 bytes so
     // that the four lane groups of a wavefront (four consecutive groups) read
@@ -83,8 +79,11 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_tile16_kernel(
     const int r = lane & 15;
     const int t = lane >> 4;
     const int G = K / kTileCols;
-    constexpr int kStep = 4 * WAVES;
-    const int64_t rowtile = blockIdx.x;
+    constexpr int kStep = 4 * S;
+    const int part = wave % S;
+    int64_t rowtile = (int64_t)blockIdx.x * R + wave / S;
+    const bool live = rowtile < rowtiles;
+    if (!live) rowtile = rowtiles - 1;                  // surplus wavefronts redo the last tile, store nothing
     const int64_t row = rowtile * kTileRows + r;
     const u32x4 *tile0 = codes + rowtile * G * (BITS * 16) + r;
     const uint16_t *srow = scales + row * G;
@@ -96,9 +95,9 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_tile16_kernel(
     // weights) and multiplies by a block of zeros instead of x.
     const int rounds = (G + kStep - 1) / kStep;
     u32x4 *zero_block = smem + (K / kTileCols) * kXRun; // 16 uint4 of zeros
-    float *red = (float *)(zero_block + 16);            // WAVES * 16 partial sums
+    float *red = (float *)(zero_block + 16);            // 8 wavefronts x 16 partial sums
 
-    int g = wave * 4 + t;
+    int g = part * 4 + t;
     u32x4 L[BITS];
     uint32_t s, z = 0;
     {
@@ -109,7 +108,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_tile16_kernel(
         if (IS_INT) z = g < G ? (uint32_t)zrow[gc] : 0u;
     }
 
-    for (int i = tid; i < K / 8; i += WAVES * kWave) xs[(i >> 4) * kXRun + (i & 15)] = x[i];
+    for (int i = tid; i < K / 8; i += kGemvWaves * kWave) xs[(i >> 4) * kXRun + (i & 15)] = x[i];
     if (tid < 16) zero_block[tid] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
@@ -124,22 +123,13 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_tile16_kernel(
             const int gc = gn < G ? gn : G - 1;
 #pragma unroll
             for (int j = 0; j < BITS; ++j)
-#if defined(POTQ_GEMV_DEBUG) && POTQ_GEMV_DEBUG >= 2
-                Ln[j] = L[j] + (uint32_t)gc;
-#else
                 Ln[j] = __builtin_nontemporal_load(tile0 + (int64_t)gc * (BITS * 16) + 16 * j);
-#endif
             if (gn < G) {
                 sn = srow[gc];
                 if (IS_INT) zn = zrow[gc];
             }
         }
-#if defined(POTQ_GEMV_DEBUG) && POTQ_GEMV_DEBUG == 1
-        for (int j = 0; j < BITS; ++j) acc[0] += __builtin_bit_cast(float4_t, L[j] & 0x3fffffffu);
-        acc[1][0] += (float)s;
-#else
         gemv_group<BITS, IS_INT>(L, s, z, g < G ? xs + g * kXRun : zero_block, acc);
-#endif
         g = gn;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
@@ -148,44 +138,59 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_tile16_kernel(
     }
 
     // The MFMA already summed the four lane groups.  Lane (c, q) holds rows 4q..4q+3
-    // (identical in every column c); combine the wavefronts in a fixed order.
-    const float4_t part = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-    if (r == 0) *(float4_t *)(red + wave * kTileRows + 4 * t) = part;
+    // (identical in every column c); combine the S wavefronts of a tile in a fixed order.
+    const float4_t part_sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    if (S == 1) {
+        if (live && r == 0) {
+            typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+            half4_t h;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) h[i] = (_Float16)part_sum[i];
+            *(half4_t *)(y + rowtile * kTileRows + 4 * t) = h;
+        }
+        return;
+    }
+    if (r == 0) *(float4_t *)(red + wave * kTileRows + 4 * t) = part_sum;
     __syncthreads();
-    if (tid < kTileRows) {
+    if (tid < R * kTileRows) {
+        const int tile = tid / kTileRows, rr = tid % kTileRows;
+        const int64_t rt = (int64_t)blockIdx.x * R + tile;
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) sum += red[w * kTileRows + tid];
+        for (int p = 0; p < S; ++p) sum += red[(tile * S + p) * kTileRows + rr];
         const _Float16 h = (_Float16)sum;
-        y[rowtile * kTileRows + tid] = __builtin_bit_cast(uint16_t, h);
+        if (rt < rowtiles) y[rt * kTileRows + rr] = __builtin_bit_cast(uint16_t, h);
     }
 }
 
-constexpr int kGemvMaxWaves = 16;
-
 size_t gemv_lds_bytes(int64_t K)
 {
-    return (size_t)(K / kTileCols) * kXRun * 16 + 256 + kGemvMaxWaves * kTileRows * sizeof(float);
+    return (size_t)(K / kTileCols) * kXRun * 16 + 256 + kGemvWaves * kTileRows * sizeof(float);
 }
 
 template <int BITS, bool IS_INT>
 static void launch_gemv(const void *codes, const void *scales, const void *zeros, const void *x, void *y,
                         int64_t N, int64_t K, hipStream_t stream)
 {
-    const dim3 grid((unsigned)(N / kTileRows));
+    const int64_t rowtiles = N / kTileRows;
     const size_t lds = gemv_lds_bytes(K);
     const int64_t G = K / kTileCols;
-    // 8 wavefronts (32 scale groups in flight per tile) measured best; few-row matrices get 16
-#define POTQ_LAUNCH_GEMV(W)                                                                                  \
-    hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, W>), grid, dim3(W * kWave), lds, stream,            \
-                       (const u32x4 *)codes, (const uint16_t *)scales, (const uint16_t *)zeros,              \
-                       (const u32x4 *)x, (uint16_t *)y, (int)K)
-#ifdef POTQ_GEMV_WAVES
-    POTQ_LAUNCH_GEMV(POTQ_GEMV_WAVES);
+#define POTQ_LAUNCH_GEMV(SPLIT)                                                                                \
+    hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT>),                                              \
+                       dim3((unsigned)((rowtiles + (kGemvWaves / SPLIT) - 1) / (kGemvWaves / SPLIT))),         \
+                       dim3(kGemvWaves * kWave), lds, stream, (const u32x4 *)codes, (const uint16_t *)scales,  \
+                       (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K)
+    // Eight wavefronts per tile measured best or equal on every decoder shape (all of a
+    // row's groups in flight at once); short rows take fewer so that no wavefront idles.
+#ifdef POTQ_GEMV_SPLIT
+    POTQ_LAUNCH_GEMV(POTQ_GEMV_SPLIT);
 #else
-    if (G <= 16) POTQ_LAUNCH_GEMV(4);
-    else if (N >= 2048 || G <= 32) POTQ_LAUNCH_GEMV(8);
-    else POTQ_LAUNCH_GEMV(16);
+    int split = 8;
+    while (split > 1 && G < 4 * split) split /= 2;
+    if (split == 8) POTQ_LAUNCH_GEMV(8);
+    else if (split == 4) POTQ_LAUNCH_GEMV(4);
+    else if (split == 2) POTQ_LAUNCH_GEMV(2);
+    else POTQ_LAUNCH_GEMV(1);
 #endif
 #undef POTQ_LAUNCH_GEMV
 }
