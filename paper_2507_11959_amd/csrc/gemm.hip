@@ -1,8 +1,8 @@
 // Fused de-quantise + GEMM on the matrix cores (tiled layout), gfx950.
 //
 // Y[m,n] = sum_k X[m,k] W~[n,k].  A workgroup of WAVES wavefronts owns
-// WAVES*RM 16-row tiles of W and a strip of 16*CN tokens, and walks K one scale
-// group (128 columns) at a time.
+// WAVES*RM 16-row tiles of W and a strip of 16*CN tokens, and walks K in chunks
+// of GC scale groups (128 columns each), one workgroup barrier per chunk.
 //
 //  - Weights never touch LDS.  Lane (r = lane % 16, q = lane / 16) fetches the
 //    32 codes of row r, column block q of the group (`bits` dwords), builds the
@@ -22,17 +22,7 @@
 
 namespace potq {
 
-#ifndef POTQ_GEMM_DEPTH_BIG
-#define POTQ_GEMM_DEPTH_BIG 2
-#endif
-#ifndef POTQ_GEMM_DEPTH_SMALL
-#define POTQ_GEMM_DEPTH_SMALL 2
-#endif
-#ifndef POTQ_GEMM_NT
-#define POTQ_GEMM_NT 0
-#endif
-
-template <int BITS, bool IS_INT, int WAVES, int RM, int CN>
+template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC>
 __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
     const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, float *__restrict__ partial, int M, int64_t N, int K,
@@ -42,7 +32,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     constexpr int THREADS = WAVES * kWave;
     constexpr int PPT = (MT * 16) / THREADS;          // 16-byte pieces of an X chunk per thread
     static_assert((MT * 16) % THREADS == 0, "X chunk must divide evenly over the workgroup");
-    extern __shared__ u32x4 smem[];                   // [2 buffers][16 k-slot groups][MT tokens]
+    extern __shared__ u32x4 smem[];                   // [2 buffers][GC groups][16 k-slot groups][MT tokens]
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -57,7 +47,11 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     const int g_begin = blockIdx.z * groups_per_split;
     const int g_end = min(G, g_begin + groups_per_split);
 
-    // weight side: per row tile, pointer to this lane's word of slab 0 of group 0, and its scale row
+    // Weight side.  The L1 processes a load instruction one 64-byte line per group
+    // of four consecutive lanes, so loads are issued in memory order -- lane l takes
+    // word l of a slab, and the scale of row l/4, group (g & ~3) + l%4 -- and a
+    // cross-lane permute (ds_bpermute) then hands lane (r, q) the word 4r + q and the
+    // scale of row r it needs as MFMA operand owner.
     const uint32_t *cptr[RM];
     const uint16_t *sptr[RM];
     const uint16_t *zptr[RM];
@@ -65,10 +59,11 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     for (int rm = 0; rm < RM; ++rm) {
         int64_t rt = rt0 + rm;
         if (rt >= rowtiles) rt = rowtiles - 1;        // surplus wavefronts redo the last tile and store nothing
-        cptr[rm] = codes + rt * G * (BITS * 64) + r * 4 + q;
-        sptr[rm] = scales + (rt * kTileRows + r) * G;
-        zptr[rm] = IS_INT ? zeros + (rt * kTileRows + r) * G : nullptr;
+        cptr[rm] = codes + rt * G * (BITS * 64) + lane;
+        sptr[rm] = scales + (rt * kTileRows + (lane >> 2)) * G;
+        zptr[rm] = IS_INT ? zeros + (rt * kTileRows + (lane >> 2)) * G : nullptr;
     }
+    const int word_owner = (4 * r + q) * 4;           // ds_bpermute byte address of the lane holding word 4r + q
 
     // X side: this thread's pieces of a chunk (16 tokens x 4 consecutive 8-value runs per wavefront)
     const uint16_t *xsrc[PPT];
@@ -77,98 +72,119 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
         const int p = tid + THREADS * i;
-        const int st = (p >> 4) & 3;                  // run inside a 32-column block = MFMA step
+        const int st = p & 3;                         // run inside a 32-column block = MFMA step
         const int blk = p >> 6;
-        const int m = (p & 15) + 16 * (blk % CN);
+        const int m = ((p >> 2) & 15) + 16 * (blk % CN);   // four consecutive lanes read 64 contiguous bytes
         const int qq = blk / CN;                      // 32-column block = A/B k-slice
         xok[i] = (m0 + m) < M;
         xsrc[i] = X + (int64_t)(xok[i] ? m0 + m : 0) * K + 32 * qq + 8 * st;
         xslot[i] = (st * 4 + qq) * MT + m;
     }
 
-    float4_t acc[RM][CN];
+    // with few output tiles per wavefront the MFMAs of one tile form a dependent chain:
+    // two accumulator sets, alternated by MFMA step, halve it
+    constexpr int ACCS = (RM * CN <= 2) ? 2 : 1;
+    float4_t acc[ACCS][RM][CN];
 #pragma unroll
-    for (int rm = 0; rm < RM; ++rm)
+    for (int a = 0; a < ACCS; ++a)
 #pragma unroll
-        for (int c = 0; c < CN; ++c) acc[rm][c] = float4_t{0.f, 0.f, 0.f, 0.f};
+        for (int rm = 0; rm < RM; ++rm)
+#pragma unroll
+            for (int c = 0; c < CN; ++c) acc[a][rm][c] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    // Software pipeline.  Packed codes stream from HBM: they are requested kDepth
-    // groups ahead into a small register ring.  X comes from L2: it is requested
-    // kXStages groups ahead into registers and moves through two LDS buffers.
-    constexpr int kDepth = (CN >= 8) ? POTQ_GEMM_DEPTH_BIG : POTQ_GEMM_DEPTH_SMALL;
-    constexpr int kXStages = (PPT <= 4) ? 2 : 1;
-    static_assert(kDepth % 2 == 0, "LDS buffer and X stage are selected by the parity of the unrolled index");
-    uint32_t wr[kDepth][RM][BITS], sr[kDepth][RM], zr[kDepth][RM];
-    u32x4 xreg[kXStages][PPT];
+    // Software pipeline, two chunks of GC scale groups deep; one barrier per chunk.
+    // Every load is unconditional (indices are clamped, tokens past M are masked to
+    // zero afterwards) and every iteration issues the same loads in the same order.
+    constexpr bool kAlignedChunks = (GC % 4 == 0);     // chunks start on multiples of four groups (see launch)
+    constexpr int kXStages = (GC * PPT <= 4) ? 2 : 1;  // register stages of X (the LDS buffer is the other stage)
+    uint32_t wr[2][GC][RM][BITS], sr[2][GC][RM], zr[2][GC][RM];
+    u32x4 xreg[kXStages][GC][PPT];
+    uint32_t xmask[PPT];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) xmask[i] = xok[i] ? 0xFFFFFFFFu : 0u;
 
-    auto fetch_codes = [&](int slot, int g) {
-        const int gc = g < g_end ? g : g_end - 1;     // past the end: re-read the last group, never used
+    auto fetch_x = [&](int stage, int g0) {
 #pragma unroll
-        for (int rm = 0; rm < RM; ++rm) {
+        for (int gi = 0; gi < GC; ++gi) {
+            const int gc = g0 + gi < g_end ? g0 + gi : g_end - 1;   // past the end: re-read the last group
 #pragma unroll
-            for (int j = 0; j < BITS; ++j)
-#if POTQ_GEMM_NT
-                wr[slot][rm][j] = __builtin_nontemporal_load(cptr[rm] + (int64_t)gc * (BITS * 64) + 64 * j);
-#else
-                wr[slot][rm][j] = cptr[rm][(int64_t)gc * (BITS * 64) + 64 * j];
-#endif
-            sr[slot][rm] = sptr[rm][gc];
-            zr[slot][rm] = IS_INT ? (uint32_t)zptr[rm][gc] : 0u;
+            for (int i = 0; i < PPT; ++i) xreg[stage][gi][i] = *(const u32x4 *)(xsrc[i] + gc * kTileCols);
         }
     };
-    auto fetch_x = [&](int stage, int g) {
-        const int gc = g < g_end ? g : g_end - 1;
+    auto fetch_w = [&](int stage, int g0) {
 #pragma unroll
-        for (int i = 0; i < PPT; ++i)
-            xreg[stage][i] = xok[i] ? *(const u32x4 *)(xsrc[i] + gc * kTileCols) : u32x4{0u, 0u, 0u, 0u};
-    };
-
-#pragma unroll
-    for (int d = 0; d < kDepth; ++d) fetch_codes(d, g_begin + d);
-#pragma unroll
-    for (int x = 0; x < kXStages; ++x) fetch_x(x, g_begin + x);
-
-    for (int gb = g_begin; gb < g_end; gb += kDepth) {
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-            const int g = gb + d;
-            if (g >= g_end) break;                    // uniform over the workgroup
-            u32x4 *buf = smem + (d & 1) * (16 * MT);  // (g - g_begin) & 1 == d & 1
-#pragma unroll
-            for (int i = 0; i < PPT; ++i) buf[xslot[i]] = xreg[d % kXStages][i];
-            __syncthreads();    // this buffer was last read two groups ago, before the previous barrier
-            fetch_x(d % kXStages, g + kXStages);
-
-            uint32_t w[RM][BITS], s[RM], z[RM];
+        for (int gi = 0; gi < GC; ++gi) {
+            const int gc = g0 + gi < g_end ? g0 + gi : g_end - 1;
 #pragma unroll
             for (int rm = 0; rm < RM; ++rm) {
 #pragma unroll
-                for (int j = 0; j < BITS; ++j) w[rm][j] = wr[d][rm][j];
-                s[rm] = sr[d][rm];
-                z[rm] = zr[d][rm];
+                for (int j = 0; j < BITS; ++j)
+                    wr[stage][gi][rm][j] = cptr[rm][(int64_t)gc * (BITS * 64) + 64 * j];
+                // one scale load serves the four groups of an aligned quadruple
+                if (gi % 4 == 0 || !kAlignedChunks) {
+                    const int gs = min((gc & ~3) + (lane & 3), G - 1);
+                    sr[stage][gi][rm] = sptr[rm][gs];
+                    zr[stage][gi][rm] = IS_INT ? (uint32_t)zptr[rm][gs] : 0u;
+                } else {
+                    sr[stage][gi][rm] = sr[stage][gi & ~3][rm];
+                    zr[stage][gi][rm] = zr[stage][gi & ~3][rm];
+                }
             }
-            fetch_codes(d, g + kDepth);
+        }
+    };
 
+    auto process = [&](int stage, int g0) {
+        u32x4 *buf = smem + stage * (GC * 16 * MT);
+        constexpr int xs = kXStages == 2 ? 1 : 0;
+#pragma unroll
+        for (int gi = 0; gi < GC; ++gi)
+#pragma unroll
+            for (int i = 0; i < PPT; ++i)
+                buf[gi * 16 * MT + xslot[i]] = xreg[kXStages == 2 ? stage : 0][gi][i] & xmask[i];
+        (void)xs;
+        __syncthreads();    // this buffer was last read two chunks ago, before the previous barrier
+        fetch_x(kXStages == 2 ? stage : 0, g0 + kXStages * GC);
+
+        uint32_t w[GC][RM][BITS], s[GC][RM], z[GC][RM];
+#pragma unroll
+        for (int gi = 0; gi < GC; ++gi) {
+            const int gc = g0 + gi < g_end ? g0 + gi : g_end - 1;
+            const int scale_owner = (4 * r + (gc & 3)) * 4;
+#pragma unroll
+            for (int rm = 0; rm < RM; ++rm) {
+#pragma unroll
+                for (int j = 0; j < BITS; ++j)
+                    w[gi][rm][j] = (uint32_t)__builtin_amdgcn_ds_bpermute(word_owner, (int)wr[stage][gi][rm][j]);
+                s[gi][rm] = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)sr[stage][gi][rm]);
+                z[gi][rm] = IS_INT ? (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)zr[stage][gi][rm]) : 0u;
+            }
+        }
+        fetch_w(stage, g0 + 2 * GC);
+
+#pragma unroll
+        for (int gi = 0; gi < GC; ++gi) {
+            if (g0 + gi >= g_end) break;              // uniform: only the last chunk of a split can be short
+            const u32x4 *xb = buf + gi * 16 * MT;
             PotTable pt[RM];
             IntTable it[RM];
             uint32_t sel[RM][8];
 #pragma unroll
             for (int rm = 0; rm < RM; ++rm) {
                 if (IS_INT)
-                    it[rm] = int_table<BITS>(s[rm], z[rm]);
+                    it[rm] = int_table<BITS>(s[gi][rm], z[gi][rm]);
                 else
-                    pt[rm] = pot_table<BITS>(s[rm]);
+                    pt[rm] = pot_table<BITS>(s[gi][rm]);
                 if (BITS == 3)
-                    selectors3(w[rm][0], w[rm][1], w[rm][BITS - 1], sel[rm]);
+                    selectors3(w[gi][rm][0], w[gi][rm][1], w[gi][rm][BITS - 1], sel[rm]);
                 else
-                    selectors2(w[rm][0], w[rm][1], sel[rm]);
+                    selectors2(w[gi][rm][0], w[gi][rm][1], sel[rm]);
             }
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
                 half8_t b[CN];
 #pragma unroll
                 for (int c = 0; c < CN; ++c)
-                    b[c] = __builtin_bit_cast(half8_t, buf[(st * 4 + q) * MT + 16 * c + r]);
+                    b[c] = __builtin_bit_cast(half8_t, xb[(st * 4 + q) * MT + 16 * c + r]);
 #pragma unroll
                 for (int rm = 0; rm < RM; ++rm) {
                     uint32_t a0, a1, a2, a3;
@@ -182,11 +198,23 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
                     const half8_t av = __builtin_bit_cast(half8_t, (u32x4{a0, a1, a2, a3}));
 #pragma unroll
                     for (int c = 0; c < CN; ++c)
-                        acc[rm][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[c], acc[rm][c], 0, 0, 0);
+                        acc[(st & (ACCS - 1))][rm][c] =
+                            __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[c], acc[(st & (ACCS - 1))][rm][c], 0, 0, 0);
                 }
             }
         }
+    };
+
+    fetch_x(0, g_begin);
+    if (kXStages == 2) fetch_x(1, g_begin + GC);
+    fetch_w(0, g_begin);
+    fetch_w(1, g_begin + GC);
+    int g = g_begin;
+    for (; g + GC < g_end; g += 2 * GC) {
+        process(0, g);
+        process(1, g + GC);
     }
+    if (g < g_end) process(0, g);
 
     // D: lane holds token m0 + 16c + (lane % 16), weight rows 4*(lane / 16) + i of each row tile
     typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
@@ -199,12 +227,13 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
             const int m = m0 + 16 * c + r;
             if (m < M) {
                 const int64_t at = (int64_t)m * N + rt * kTileRows + 4 * q;
+                const float4_t total = ACCS == 2 ? acc[0][rm][c] + acc[ACCS - 1][rm][c] : acc[0][rm][c];
                 if (gridDim.z > 1) {
-                    *(float4_t *)(partial + (int64_t)blockIdx.z * M * N + at) = acc[rm][c];
+                    *(float4_t *)(partial + (int64_t)blockIdx.z * M * N + at) = total;
                 } else {
                     half4_t h;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) h[i] = (_Float16)acc[rm][c][i];
+                    for (int i = 0; i < 4; ++i) h[i] = (_Float16)total[i];
                     *(half4_t *)(Y + at) = h;
                 }
             }
@@ -227,19 +256,26 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4_t *__rest
     *(half4_t *)(Y + 4 * i) = h;
 }
 
+#ifndef POTQ_GEMM_TARGET_WGS
+#define POTQ_GEMM_TARGET_WGS 768
+#endif
+#ifndef POTQ_GEMM_MIN_GROUPS
+#define POTQ_GEMM_MIN_GROUPS 4
+#endif
+
 // Number of K splits: enough workgroups to occupy the chip about three times over,
 // at least four scale groups per split, and only as many as the workspace holds.
 static int choose_splits(int64_t workgroups, int64_t G, int64_t M, int64_t N, size_t workspace_bytes)
 {
-    int64_t want = (768 + workgroups - 1) / workgroups;
-    if (want > G / 4) want = G / 4;
+    int64_t want = (POTQ_GEMM_TARGET_WGS + workgroups - 1) / workgroups;
+    if (want > G / POTQ_GEMM_MIN_GROUPS) want = G / POTQ_GEMM_MIN_GROUPS;
     if (want > 16) want = 16;
     const int64_t fit = (int64_t)(workspace_bytes / ((size_t)M * (size_t)N * sizeof(float)));
     if (want > fit) want = fit;
     return want < 2 ? 1 : (int)want;
 }
 
-template <int BITS, bool IS_INT, int WAVES, int RM, int CN>
+template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC>
 static void launch_gemm_cfg(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                             int64_t M, int64_t N, int64_t K, void *workspace, size_t workspace_bytes,
                             hipStream_t stream)
@@ -250,9 +286,10 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
     const unsigned gy = (unsigned)((M + 16 * CN - 1) / (16 * CN));
     int splits = workspace ? choose_splits((int64_t)gx * gy, G, M, N, workspace_bytes) : 1;
     int per = (int)((G + splits - 1) / splits);
+    per = (per + GC - 1) / GC * GC;                   // whole chunks
     splits = (int)((G + per - 1) / per);              // no empty split
-    const size_t lds = (size_t)2 * 16 * (16 * CN) * sizeof(u32x4);
-    hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN>), dim3(gx, gy, (unsigned)splits),
+    const size_t lds = (size_t)2 * GC * 16 * (16 * CN) * sizeof(u32x4);
+    hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN, GC>), dim3(gx, gy, (unsigned)splits),
                        dim3(WAVES * kWave), lds, stream, (const uint32_t *)codes, (const uint16_t *)scales,
                        (const uint16_t *)zeros, (const uint16_t *)X, (uint16_t *)Y, (float *)workspace, (int)M, N,
                        (int)K, per);
@@ -266,6 +303,15 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
 // Workspace that lets every supported shape use its preferred number of splits.
 size_t gemm_workspace_bytes(int64_t M, int64_t N) { return M <= 64 ? (size_t)16 * M * N * sizeof(float) : 0; }
 
+#ifndef POTQ_GEMM_GC1
+#define POTQ_GEMM_GC1 4
+#endif
+#ifndef POTQ_GEMM_GC2
+#define POTQ_GEMM_GC2 2
+#endif
+#ifndef POTQ_GEMM_GC4
+#define POTQ_GEMM_GC4 2
+#endif
 #ifndef POTQ_GEMM_BIG_RM
 #define POTQ_GEMM_BIG_RM 2
 #endif
@@ -278,14 +324,14 @@ static void launch_gemm(const void *codes, const void *scales, const void *zeros
                         int64_t M, int64_t N, int64_t K, void *ws, size_t ws_bytes, hipStream_t stream)
 {
     if (M <= 16)
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1, POTQ_GEMM_GC1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
     else if (M <= 32)
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2, POTQ_GEMM_GC2>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
     else if (M <= 64)
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4, POTQ_GEMM_GC4>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
     else
-        launch_gemm_cfg<BITS, IS_INT, 4, POTQ_GEMM_BIG_RM, POTQ_GEMM_BIG_CN>(codes, scales, zeros, X, Y, M, N, K,
-                                                                              nullptr, 0, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, POTQ_GEMM_BIG_RM, POTQ_GEMM_BIG_CN, 1>(codes, scales, zeros, X, Y, M, N, K,
+                                                                                 nullptr, 0, stream);
 }
 
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,

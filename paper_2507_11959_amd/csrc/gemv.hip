@@ -86,8 +86,13 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     if (!live) rowtile = rowtiles - 1;                  // surplus wavefronts redo the last tile, store nothing
     const int64_t row = rowtile * kTileRows + r;
     const u32x4 *tile0 = codes + rowtile * G * (BITS * 16) + r;
-    const uint16_t *srow = scales + row * G;
-    const uint16_t *zrow = IS_INT ? zeros + row * G : nullptr;
+    // Scales are fetched in memory order -- lane l takes row l/4, group (first group of the
+    // round) + l%4, so four consecutive lanes share one 64-byte line, which is the unit the
+    // L1 processes per cycle -- and a cross-lane permute hands lane (r, t) its own scale.
+    const uint16_t *srow = scales + (rowtile * kTileRows + (lane >> 2)) * G;
+    const uint16_t *zrow = IS_INT ? zeros + (rowtile * kTileRows + (lane >> 2)) * G : nullptr;
+    const int scale_owner = (4 * r + t) * 4;            // ds_bpermute byte address
+    (void)row;
 
     // MFMA ignores the execution mask, so the group loop must be uniform: every
     // lane runs ceil(G / kStep) rounds.  A lane whose group index runs past G
@@ -99,13 +104,14 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
 
     int g = part * 4 + t;
     u32x4 L[BITS];
-    uint32_t s, z = 0;
+    uint32_t s, z = 0;       // raw loads (memory order); permuted to their owners when consumed
     {
         const int gc = g < G ? g : G - 1;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) L[j] = __builtin_nontemporal_load(tile0 + (int64_t)gc * (BITS * 16) + 16 * j);
-        s = g < G ? (uint32_t)srow[gc] : 0x3C00u;
-        if (IS_INT) z = g < G ? (uint32_t)zrow[gc] : 0u;
+        const int gs = min(part * 4 + (lane & 3), G - 1);
+        s = srow[gs];
+        if (IS_INT) z = zrow[gs];
     }
 
     for (int i = tid; i < K / 8; i += kGemvWaves * kWave) xs[(i >> 4) * kXRun + (i & 15)] = x[i];
@@ -118,18 +124,23 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     for (int round = 0; round < rounds; ++round) {
         const int gn = g + kStep;
         u32x4 Ln[BITS];
-        uint32_t sn = 0x3C00u, zn = 0;
-        if (round + 1 < rounds) {
-            const int gc = gn < G ? gn : G - 1;
+        uint32_t sn = 0, zn = 0;
+        {
+            const int gc = gn < G ? gn : G - 1;         // past the end: re-read the last group, never used
 #pragma unroll
             for (int j = 0; j < BITS; ++j)
                 Ln[j] = __builtin_nontemporal_load(tile0 + (int64_t)gc * (BITS * 16) + 16 * j);
-            if (gn < G) {
-                sn = srow[gc];
-                if (IS_INT) zn = zrow[gc];
-            }
+            const int gs = min(part * 4 + (round + 1) * kStep + (lane & 3), G - 1);
+            sn = srow[gs];
+            if (IS_INT) zn = zrow[gs];
         }
-        gemv_group<BITS, IS_INT>(L, s, z, g < G ? xs + g * kXRun : zero_block, acc);
+        uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)s);
+        uint32_t zo = IS_INT ? (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)z) : 0u;
+        if (g >= G) {
+            so = 0x3C00u;
+            zo = 0u;
+        }
+        gemv_group<BITS, IS_INT>(L, so, zo, g < G ? xs + g * kXRun : zero_block, acc);
         g = gn;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
