@@ -78,7 +78,9 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
         const int qq = blk / CN;                      // 32-column block = A/B k-slice
         xok[i] = (m0 + m) < M;
         xsrc[i] = X + (int64_t)(xok[i] ? m0 + m : 0) * K + 32 * qq + 8 * st;
-        xslot[i] = (st * 4 + qq) * MT + m;
+        // rotate the token index inside its 16-token tile by 4*st: the four lanes of a quad (same
+        // token, st = 0..3) then write to four different LDS bank groups
+        xslot[i] = (st * 4 + qq) * MT + (m & ~15) + ((m + 4 * st) & 15);
     }
 
     // with few output tiles per wavefront the MFMAs of one tile form a dependent chain:
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
                 half8_t b[CN];
 #pragma unroll
                 for (int c = 0; c < CN; ++c)
-                    b[c] = __builtin_bit_cast(half8_t, xb[(st * 4 + q) * MT + 16 * c + r]);
+                    b[c] = __builtin_bit_cast(half8_t, xb[(st * 4 + q) * MT + 16 * c + ((r + 4 * st) & 15)]);
 #pragma unroll
                 for (int rm = 0; rm < RM; ++rm) {
                     uint32_t a0, a1, a2, a3;
@@ -265,9 +267,12 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4_t *__rest
 
 // Number of K splits: enough workgroups to occupy the chip about three times over,
 // at least four scale groups per split, and only as many as the workspace holds.
-static int choose_splits(int64_t workgroups, int64_t G, int64_t M, int64_t N, size_t workspace_bytes)
+static int choose_splits(int64_t workgroups, int64_t G, int64_t M, int64_t N, size_t workspace_bytes, bool big)
 {
-    int64_t want = (POTQ_GEMM_TARGET_WGS + workgroups - 1) / workgroups;
+    // the many-token configuration moves M*N*4 bytes per split through the workspace: split only when
+    // fewer than ~60 % of the CUs would have a workgroup, and then just enough to cover them
+    int64_t want = big ? (workgroups < 160 ? (320 + workgroups - 1) / workgroups : 1)
+                       : (POTQ_GEMM_TARGET_WGS + workgroups - 1) / workgroups;
     if (want > G / POTQ_GEMM_MIN_GROUPS) want = G / POTQ_GEMM_MIN_GROUPS;
     if (want > 16) want = 16;
     const int64_t fit = (int64_t)(workspace_bytes / ((size_t)M * (size_t)N * sizeof(float)));
@@ -284,7 +289,7 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
     const int64_t G = K / kTileCols;
     const unsigned gx = (unsigned)((rowtiles + WAVES * RM - 1) / (WAVES * RM));
     const unsigned gy = (unsigned)((M + 16 * CN - 1) / (16 * CN));
-    int splits = workspace ? choose_splits((int64_t)gx * gy, G, M, N, workspace_bytes) : 1;
+    int splits = workspace ? choose_splits((int64_t)gx * gy, G, M, N, workspace_bytes, CN >= 8) : 1;
     int per = (int)((G + splits - 1) / splits);
     per = (per + GC - 1) / GC * GC;                   // whole chunks
     splits = (int)((G + per - 1) / per);              // no empty split
@@ -300,38 +305,53 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
     }
 }
 
-// Workspace that lets every supported shape use its preferred number of splits.
-size_t gemm_workspace_bytes(int64_t M, int64_t N) { return M <= 64 ? (size_t)16 * M * N * sizeof(float) : 0; }
 
-#ifndef POTQ_GEMM_GC1
-#define POTQ_GEMM_GC1 4
-#endif
-#ifndef POTQ_GEMM_GC2
-#define POTQ_GEMM_GC2 2
-#endif
-#ifndef POTQ_GEMM_GC4
-#define POTQ_GEMM_GC4 2
-#endif
-#ifndef POTQ_GEMM_BIG_RM
-#define POTQ_GEMM_BIG_RM 2
-#endif
-#ifndef POTQ_GEMM_BIG_CN
-#define POTQ_GEMM_BIG_CN 8
-#endif
+// Tile shapes for more than 64 tokens: (row tiles per wavefront, 16-token tiles per workgroup).
+// More row tiles per wavefront reuse each X fragment read from LDS more often (two row
+// tiles leave LDS as busy as the matrix pipe), more token tiles amortise the decode; both
+// cost output tiles, so the large shapes are only used where enough of them remain.
+static void big_tile(int64_t M, int64_t N, int *rm, int *cn)
+{
+    if (M >= 512 && N >= 8192) { *rm = 4; *cn = 8; }
+    else if (M >= 512 || (M >= 256 && N >= 8192)) { *rm = 4; *cn = 4; }
+    else { *rm = 2; *cn = 8; }
+}
+
+static int64_t big_workgroups(int64_t M, int64_t N)
+{
+    int rm, cn;
+    big_tile(M, N, &rm, &cn);
+    return ((N / kTileRows + 4 * rm - 1) / (4 * rm)) * ((M + 16 * cn - 1) / (16 * cn));
+}
+
+// Workspace that lets every supported shape use its preferred number of splits.
+size_t gemm_workspace_bytes(int64_t M, int64_t N)
+{
+    if (M <= 64) return (size_t)16 * M * N * sizeof(float);
+    const int64_t workgroups = big_workgroups(M, N);
+    return workgroups < 160 ? (size_t)((320 + workgroups - 1) / workgroups) * M * N * sizeof(float) : 0;
+}
 
 template <int BITS, bool IS_INT>
 static void launch_gemm(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                         int64_t M, int64_t N, int64_t K, void *ws, size_t ws_bytes, hipStream_t stream)
 {
-    if (M <= 16)
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1, POTQ_GEMM_GC1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
-    else if (M <= 32)
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2, POTQ_GEMM_GC2>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
-    else if (M <= 64)
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4, POTQ_GEMM_GC4>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
-    else
-        launch_gemm_cfg<BITS, IS_INT, 4, POTQ_GEMM_BIG_RM, POTQ_GEMM_BIG_CN, 1>(codes, scales, zeros, X, Y, M, N, K,
-                                                                                 nullptr, 0, stream);
+    if (M <= 16) {
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1, 4>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+    } else if (M <= 32) {
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2, 2>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+    } else if (M <= 64) {
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4, 2>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+    } else {
+        int rm, cn;
+        big_tile(M, N, &rm, &cn);
+        if (rm == 4 && cn == 8)
+            launch_gemm_cfg<BITS, IS_INT, 4, 4, 8, 1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        else if (rm == 4)
+            launch_gemm_cfg<BITS, IS_INT, 4, 4, 4, 1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        else
+            launch_gemm_cfg<BITS, IS_INT, 4, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+    }
 }
 
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
