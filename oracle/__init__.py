@@ -25,7 +25,8 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP over rows only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC,
+             "-lm"]
         )
     return _LIB
 
@@ -68,6 +69,9 @@ def _L():
         lib.orc_gemm.restype = None
         lib.orc_gemm.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
                                  c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int, c.c_int]
+        lib.orc_pot_quantize.restype = None
+        lib.orc_pot_quantize.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64,
+                                         c.c_int, c.c_int, c.c_int]
         lib.orc_max_threads.restype = c.c_int
         lib.orc_max_threads.argtypes = []
         _lib = lib
@@ -202,3 +206,17 @@ def gemv(packed, scales, zeros, x, K: int, bits: int, group: int, nthreads: int 
     if want_f64:
         return r[0][0], r[1][0]
     return r[0]
+
+
+def pot_quantize(W, bits: int, group: int, nthreads: int = 1, want_index: bool = False):
+    """Step 1 scale search (Algorithm 1).  W: (N, K) fp16 (or uint16 bits).
+
+    -> codes (N, K) uint8 one code per element, scales (N, K/group) uint16 bits [, best multiplier index]."""
+    W = _u16(W)
+    N, K = W.shape
+    assert K % group == 0
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, K // group), dtype=np.uint16)
+    idx = np.empty((N, K // group), dtype=np.int32) if want_index else None
+    _L().orc_pot_quantize(_p(W), _p(codes), _p(scales), _p(idx) if want_index else None, N, K, bits, group, nthreads)
+    return (codes, scales, idx) if want_index else (codes, scales)

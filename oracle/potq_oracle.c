@@ -294,3 +294,95 @@ int orc_max_threads(void)
     return 1;
 #endif
 }
+
+/* ------------------------------------------- Step 1 scale search (Alg. 1) -- */
+
+/*
+ * Data-agnostic scale initialisation, Sec. 3.2 / Algorithm 1, for one matrix of
+ * binary16 weights: for every group of `group` consecutive weights of a row
+ *     s0 = max|w| / (2^qmax - 1)
+ *     for i = 1..200:  s = s0 * (0.01 * i)
+ *         E_k = clamp(round(log2(|w_k| / s)), 0, qmax),   w~_k = sign(w_k) * s * 2^E_k
+ *         Q(i) = sum_k (w_k - w~_k)^2 ;  keep i if Q(i) < best so far (strict: first minimum wins)
+ *     scale = s0 * (0.01 * i*),  codes = (sign, E) under that scale.
+ *
+ * The paper leaves the arithmetic open.  So that the integer decisions (E, the
+ * arg-min) are well defined and can be reproduced bit for bit, this oracle fixes
+ * it as IEEE binary32 throughout, one rounding per operation, no contraction:
+ *   - b_i = (float)i * 0.01f ; s = s0 * b_i ; s0 by a binary32 division;
+ *   - round(log2(|w|/s)) is taken through its decision thresholds: E = number of
+ *     e in 1..qmax with |w| >= s * c_e, c_e = (float)2^(e - 1/2) (a tie on a
+ *     threshold rounds up; |w| = 0 gives E = 0 as clamp(-inf) does);
+ *   - w~ = s * 2^E is exact; d = w - w~ ; Q = fmaf(d, d, Q), k ascending;
+ *   - sign(0) = +, i.e. the sign bit is set only for w < 0;
+ *   - an all-zero group (s0 = 0) gets E = 0 everywhere;
+ *   - the scale is rounded once to binary16 and clamped into the domain on which
+ *     the de-quantisation recipe is exact ([2^-14, largest value with exponent
+ *     field 30 - qmax]).
+ * codes: N*K bytes, one code per byte.  best_i (optional): N*(K/group) ints.
+ */
+static const float k_round_thresholds[8] = {
+    0.0f, 1.41421356237309504880f, 2.82842712474619009760f, 5.65685424949238019521f,
+    11.3137084989847603904f, 22.6274169979695207808f, 45.2548339959390415616f, 90.5096679918780831232f};
+
+void orc_pot_quantize(const uint16_t *W, uint8_t *codes, uint16_t *scales, int32_t *best_i,
+                      int64_t N, int64_t K, int bits, int group, int nthreads)
+{
+    const int qmax = (1 << (bits - 1)) - 1;
+    const int64_t ngroups = K / group;
+    const float denom = (float)((1 << qmax) - 1);
+    (void)nthreads;
+#if defined(_OPENMP)
+#pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n) {
+        float *w = (float *)malloc(sizeof(float) * (size_t)group);
+        for (int64_t g = 0; g < ngroups; ++g) {
+            const uint16_t *src = W + n * K + g * group;
+            uint8_t *dst = codes + n * K + g * group;
+            float wmax = 0.0f;
+            for (int k = 0; k < group; ++k) {
+                w[k] = (float)orc_half_to_double(src[k]);      /* exact: binary16 is a subset of binary32 */
+                if (fabsf(w[k]) > wmax) wmax = fabsf(w[k]);
+            }
+            const float s0 = wmax / denom;
+            int ibest = 1;
+            float qbest = INFINITY;
+            for (int i = 1; i <= 200; ++i) {
+                const float b = (float)i * 0.01f;
+                const float s = s0 * b;
+                float q = 0.0f;
+                for (int k = 0; k < group; ++k) {
+                    const float a = fabsf(w[k]);
+                    int E = 0;
+                    for (int e = 1; e <= qmax; ++e)
+                        if (a >= s * k_round_thresholds[e]) E = e;
+                    const float mag = ldexpf(s, E);
+                    const float wq = w[k] < 0.0f ? -mag : mag;
+                    const float d = w[k] - wq;
+                    q = fmaf(d, d, q);
+                }
+                if (q < qbest) {
+                    qbest = q;
+                    ibest = i;
+                }
+            }
+            const float sbest = s0 * ((float)ibest * 0.01f);
+            for (int k = 0; k < group; ++k) {
+                const float a = fabsf(w[k]);
+                int E = 0;
+                if (s0 > 0.0f)
+                    for (int e = 1; e <= qmax; ++e)
+                        if (a >= sbest * k_round_thresholds[e]) E = e;
+                dst[k] = (uint8_t)((w[k] < 0.0f ? (1 << (bits - 1)) : 0) | E);
+            }
+            uint16_t sb = orc_double_to_half((double)sbest);
+            const uint16_t lo = 0x0400, hi = (uint16_t)(((30 - qmax) << 10) | 0x3FF);
+            if (sb < lo) sb = lo;          /* positive patterns order like the values */
+            if (sb > hi) sb = hi;
+            scales[n * ngroups + g] = sb;
+            if (best_i) best_i[n * ngroups + g] = ibest;
+        }
+        free(w);
+    }
+}

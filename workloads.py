@@ -91,6 +91,11 @@ def activations(seed: int, M: int, K: int) -> np.ndarray:
     return _rng(seed).standard_normal(size=(M, K)).astype(np.float16)
 
 
+def weights_f16(seed: int, N: int, K: int, sigma: float = SIGMA_W) -> np.ndarray:
+    """(N, K) float16 ~ N(0, sigma^2): stand-in for a trained weight matrix (input of the scale search)."""
+    return (_rng(seed).standard_normal(size=(N, K), dtype=np.float32) * np.float32(sigma)).astype(np.float16)
+
+
 def pot_matrix(config: int, matrix: int, N: int, K: int, bits: int, group: int = GROUP):
     """(packed codes, scales) of one PoT-quantised weight matrix."""
     return (packed_codes(seed_of(config, matrix, 0), N, K, bits),
