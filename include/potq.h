@@ -181,6 +181,28 @@ int int_gemm(const void *codes, const void *scales, const void *zeros, const voi
              void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * pot_quantize -- Step 1 of the method, the data-agnostic scale search (Sec. 3.2,
+ * Algorithm 1), producing the inputs of the entry points above from fp16 weights.
+ * For every group of `group` consecutive weights of a row:
+ *     s0 = max|w| / (2^qmax - 1),  qmax = 2^(bits-1) - 1
+ *     for i = 1..200:  s = s0 * (0.01 i);  E_k = clamp(round(log2(|w_k|/s)), 0, qmax);
+ *                      Q(i) = sum_k (w_k - sign(w_k) s 2^E_k)^2
+ *     i* = the first i with the smallest Q;  scale = fp16(s0 * 0.01 i*);  codes = (sign, E) under it.
+ * The paper leaves the arithmetic open; it is fixed here as IEEE binary32, one
+ * rounding per operation, no contraction: b_i = (float)i * 0.01f; s = s0 * b_i
+ * (s0 by a binary32 division); E = number of e in 1..qmax with |w| >= s * (float)2^(e-1/2)
+ * (a tie rounds up, |w| = 0 gives E = 0); w~ = s * 2^E exactly; d = w - w~;
+ * Q = fma(d, d, Q) for k ascending; the sign bit is set only for w < 0; an all-zero
+ * group gets E = 0 everywhere; the fp16 scale is clamped into [2^-14, largest value with
+ * exponent field 30 - qmax] so that it lies in pot_dequant's exact domain.
+ *   W_f16      in   N x K fp16, row-major
+ *   codes_out  out  canonical layout, N rows of K*bits/8 bytes
+ *   scales_out out  N x (K/group) fp16
+ */
+int pot_quantize(const void *W_f16, void *codes_out, void *scales_out,
+                 int64_t N, int64_t K, int bits, int group, void *hip_stream);
+
+/*
  * pot_check_scales -- count the scales outside the domain on which the
  * integer-add recipe equals the definition (not positive, subnormal or zero,
  * exponent field above 30 - q_max, infinity, NaN).  The count is written, as

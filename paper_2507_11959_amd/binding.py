@@ -43,6 +43,7 @@ EXPORTS = {
     "pot_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
     "int_gemm": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
     "pot_check_scales": (_int, [_vp, _i64, _int, _vp, _vp]),
+    "pot_quantize": (_int, [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]),
 }
 for _name, (_res, _args) in EXPORTS.items():
     _f = getattr(_lib, _name)
@@ -227,6 +228,18 @@ def int_gemm(codes, scales, zeros, X, K: int, bits: int, group: int = 128, layou
                       _dev(zeros, torch.float16, "zeros"), _dev(X, torch.float16, "X"),
                       _dev(out, torch.float16, "Y"), M, N, K, bits, group, layout, wp, wn, _stream()))
     return out
+
+
+def pot_quantize(W, bits: int, group: int = 128):
+    """W: fp16 (N, K) -> (packed codes uint8 (N, K*bits/8) canonical, scales fp16 (N, K/group))."""
+    if W.dim() != 2:
+        raise ValueError("W must be (N, K)")
+    N, K = W.shape
+    codes = torch.empty((N, K * bits // 8), dtype=torch.uint8, device=W.device)
+    scales = torch.empty((N, K // group), dtype=torch.float16, device=W.device)
+    _ok(_lib.pot_quantize(_dev(W, torch.float16, "W"), _dev(codes, torch.uint8, "codes"),
+                          _dev(scales, torch.float16, "scales"), N, K, bits, group, _stream()))
+    return codes, scales
 
 
 def pot_check_scales(scales, bits: int) -> int:

@@ -22,6 +22,8 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, void *ws, size_t ws_bytes,
                            hipStream_t stream);
 size_t gemm_workspace_bytes(int64_t M, int64_t N);
+hipError_t run_quantize(const void *W, void *codes, void *scales, int64_t N, int64_t K, int bits, int group,
+                        hipStream_t stream);
 }  // namespace potq
 
 namespace {
@@ -225,6 +227,17 @@ int int_gemm(const void *codes, const void *scales, const void *zeros, const voi
 {
     return gemm_entry(true, codes, scales, zeros, X_f16, Y_f16, M, N, K, bits, group, layout, workspace,
                       workspace_bytes, hip_stream);
+}
+
+int pot_quantize(const void *W_f16, void *codes_out, void *scales_out, int64_t N, int64_t K, int bits, int group,
+                 void *hip_stream)
+{
+    const int st = check_common(N, K, bits, group, false);
+    if (st != POTQ_OK) return st;
+    if (N == 0 || K == 0) return POTQ_OK;
+    if (!W_f16 || !codes_out || !scales_out) return POTQ_ERR_NULL;
+    if (misaligned(W_f16) || misaligned(codes_out) || misaligned(scales_out, 2)) return POTQ_ERR_ALIGN;
+    return finish(potq::run_quantize(W_f16, codes_out, scales_out, N, K, bits, group, (hipStream_t)hip_stream));
 }
 
 int pot_check_scales(const void *scales, int64_t count, int bits, void *bad_count_dev, void *hip_stream)

@@ -27,7 +27,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"pot_dequant", "int_dequant", "pot_gemv", "int_gemv", "pot_gemm", "int_gemm", "potq_repack",
-            "pot_check_scales", "pot_dequant_batch", "int_dequant_batch", "potq_gemm_workspace_bytes", "potq_version", "potq_strerror", "potq_packed_row_bytes",
+            "pot_check_scales", "pot_dequant_batch", "int_dequant_batch", "potq_gemm_workspace_bytes", "pot_quantize", "potq_version", "potq_strerror", "potq_packed_row_bytes",
             "potq_packed_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -87,6 +87,12 @@ def test_host_side_validation(lib):
     assert r(A, A, 24, 128, 3, 1, None) == SHAPE
     assert r(A, A, 16, 128, 3, 5, None) == LAYOUT
     assert r(A, None, 16, 128, 3, 1, None) == NULL
+    qz = lib.pot_quantize
+    assert qz(None, A, A, 16, 128, 3, 128, None) == NULL
+    assert qz(A, A, A, 16, 128, 4, 128, None) == BITS
+    assert qz(A, A, A, 16, 128, 3, 100, None) == GROUP
+    assert qz(A, MIS, A, 16, 128, 3, 128, None) == ALIGN
+    assert qz(None, None, None, 0, 128, 3, 128, None) == OK
     c = lib.pot_check_scales
     assert c(A, 4, 3, None, None) == NULL
     assert c(A, 4, 5, A, None) == BITS
