@@ -17,9 +17,9 @@ hipError_t run_repack(const void *src, void *dst, int64_t N, int64_t K, int bits
 hipError_t run_fill_zero(void *p, int64_t count, hipStream_t stream);
 size_t gemv_lds_bytes(int64_t K);
 hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
-                           void *y, int64_t N, int64_t K, int bits, hipStream_t stream);
+                           void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
-                           void *Y, int64_t M, int64_t N, int64_t K, int bits, void *ws, size_t ws_bytes,
+                           void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, void *ws, size_t ws_bytes,
                            hipStream_t stream);
 size_t gemm_workspace_bytes(int64_t M, int64_t N);
 hipError_t run_quantize(const void *W, void *codes, void *scales, int64_t N, int64_t K, int bits, int group,
@@ -36,7 +36,8 @@ bool misaligned(const void *p, uintptr_t a = 16) { return ((uintptr_t)p & (a - 1
 int check_common(int64_t N, int64_t K, int bits, int group, bool fused)
 {
     if (bits != 2 && bits != 3) return POTQ_ERR_BITS;
-    if (fused ? (group != 128) : (group != 64 && group != 128)) return POTQ_ERR_GROUP;
+    (void)fused;
+    if (group != 64 && group != 128) return POTQ_ERR_GROUP;
     if (N < 0 || K < 0 || N > kMaxDim || K > kMaxDim || (K % 128) != 0) return POTQ_ERR_SHAPE;
     return POTQ_OK;
 }
@@ -102,7 +103,7 @@ int gemv_entry(bool is_int, const void *codes, const void *scales, const void *z
     if (misaligned(codes) || misaligned(scales) || misaligned(x) || (is_int && misaligned(zeros)))
         return POTQ_ERR_ALIGN;
     if (potq::gemv_lds_bytes(K) > 64 * 1024) return POTQ_ERR_SHAPE;
-    return finish(potq::run_gemv_tile16(is_int, codes, scales, zeros, x, y, N, K, bits, (hipStream_t)stream));
+    return finish(potq::run_gemv_tile16(is_int, codes, scales, zeros, x, y, N, K, bits, group, (hipStream_t)stream));
 }
 
 int gemm_entry(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
@@ -123,7 +124,7 @@ int gemm_entry(bool is_int, const void *codes, const void *scales, const void *z
         return POTQ_ERR_ALIGN;
     if (workspace && misaligned(workspace)) return POTQ_ERR_ALIGN;
     if (!workspace) workspace_bytes = 0;
-    return finish(potq::run_gemm_tile16(is_int, codes, scales, zeros, X, Y, M, N, K, bits, workspace, workspace_bytes,
+    return finish(potq::run_gemm_tile16(is_int, codes, scales, zeros, X, Y, M, N, K, bits, group, workspace, workspace_bytes,
                                         (hipStream_t)stream));
 }
 
@@ -139,7 +140,7 @@ const char *potq_strerror(int status)
     case POTQ_OK: return "ok";
     case POTQ_ERR_NULL: return "a required pointer is NULL";
     case POTQ_ERR_BITS: return "bits must be 2 or 3";
-    case POTQ_ERR_GROUP: return "group size not supported (64 or 128; fused kernels: 128)";
+    case POTQ_ERR_GROUP: return "group size not supported (64 or 128)";
     case POTQ_ERR_SHAPE: return "bad shape (negative, K not a multiple of 128, N not a multiple of 16, or K too large)";
     case POTQ_ERR_ALIGN: return "a pointer is not 16-byte aligned";
     case POTQ_ERR_LAYOUT: return "layout not supported by this entry point";

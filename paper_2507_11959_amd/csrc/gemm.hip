@@ -26,8 +26,9 @@ template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC>
 __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
     const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, float *__restrict__ partial, int M, int64_t N, int K,
-    int groups_per_split)
+    int groups_per_split, int gs)
 {
+    // gs = 0: one scale per 128 columns; gs = 1: one per 64 (lane (r, q) then uses scale column 2g + q/2)
     constexpr int MT = 16 * CN;                       // tokens per workgroup
     constexpr int THREADS = WAVES * kWave;
     constexpr int PPT = (MT * 16) / THREADS;          // 16-byte pieces of an X chunk per thread
@@ -60,8 +61,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
         int64_t rt = rt0 + rm;
         if (rt >= rowtiles) rt = rowtiles - 1;        // surplus wavefronts redo the last tile and store nothing
         cptr[rm] = codes + rt * G * (BITS * 64) + lane;
-        sptr[rm] = scales + (rt * kTileRows + (lane >> 2)) * G;
-        zptr[rm] = IS_INT ? zeros + (rt * kTileRows + (lane >> 2)) * G : nullptr;
+        sptr[rm] = scales + (rt * kTileRows + (lane >> 2)) * ((int64_t)G << gs);
+        zptr[rm] = IS_INT ? zeros + (rt * kTileRows + (lane >> 2)) * ((int64_t)G << gs) : nullptr;
     }
     const int word_owner = (4 * r + q) * 4;           // ds_bpermute byte address of the lane holding word 4r + q
 
@@ -123,10 +124,10 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
                 for (int j = 0; j < BITS; ++j)
                     wr[stage][gi][rm][j] = cptr[rm][(int64_t)gc * (BITS * 64) + 64 * j];
                 // one scale load serves the four groups of an aligned quadruple
-                if (gi % 4 == 0 || !kAlignedChunks) {
-                    const int gs = min((gc & ~3) + (lane & 3), G - 1);
-                    sr[stage][gi][rm] = sptr[rm][gs];
-                    zr[stage][gi][rm] = IS_INT ? (uint32_t)zptr[rm][gs] : 0u;
+                if (gi % 4 == 0 || !kAlignedChunks || gs) {
+                    const int gq = min(((gc << gs) & ~3) + (lane & 3), (G << gs) - 1);
+                    sr[stage][gi][rm] = sptr[rm][gq];
+                    zr[stage][gi][rm] = IS_INT ? (uint32_t)zptr[rm][gq] : 0u;
                 } else {
                     sr[stage][gi][rm] = sr[stage][gi & ~3][rm];
                     zr[stage][gi][rm] = zr[stage][gi & ~3][rm];
@@ -151,7 +152,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
 #pragma unroll
         for (int gi = 0; gi < GC; ++gi) {
             const int gc = g0 + gi < g_end ? g0 + gi : g_end - 1;
-            const int scale_owner = (4 * r + (gc & 3)) * 4;
+            const int scale_owner = (4 * r + (((gc << gs) + ((q >> 1) & -gs)) & 3)) * 4;
 #pragma unroll
             for (int rm = 0; rm < RM; ++rm) {
 #pragma unroll
@@ -282,7 +283,7 @@ static int choose_splits(int64_t workgroups, int64_t G, int64_t M, int64_t N, si
 
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC>
 static void launch_gemm_cfg(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
-                            int64_t M, int64_t N, int64_t K, void *workspace, size_t workspace_bytes,
+                            int64_t M, int64_t N, int64_t K, int group, void *workspace, size_t workspace_bytes,
                             hipStream_t stream)
 {
     const int64_t rowtiles = N / kTileRows;
@@ -297,7 +298,7 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
     hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN, GC>), dim3(gx, gy, (unsigned)splits),
                        dim3(WAVES * kWave), lds, stream, (const uint32_t *)codes, (const uint16_t *)scales,
                        (const uint16_t *)zeros, (const uint16_t *)X, (uint16_t *)Y, (float *)workspace, (int)M, N,
-                       (int)K, per);
+                       (int)K, per, group == 64 ? 1 : 0);
     if (splits > 1) {
         const int64_t quads = M * N / 4;
         hipLaunchKernelGGL(gemm_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
@@ -334,36 +335,36 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N)
 
 template <int BITS, bool IS_INT>
 static void launch_gemm(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
-                        int64_t M, int64_t N, int64_t K, void *ws, size_t ws_bytes, hipStream_t stream)
+                        int64_t M, int64_t N, int64_t K, int group, void *ws, size_t ws_bytes, hipStream_t stream)
 {
     if (M <= 16) {
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1, 4>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else if (M <= 32) {
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2, 2>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else if (M <= 64) {
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4, 2>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
         int rm, cn;
         big_tile(M, N, &rm, &cn);
         if (rm == 4 && cn == 8)
-            launch_gemm_cfg<BITS, IS_INT, 4, 4, 8, 1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+            launch_gemm_cfg<BITS, IS_INT, 4, 4, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else if (rm == 4)
-            launch_gemm_cfg<BITS, IS_INT, 4, 4, 4, 1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+            launch_gemm_cfg<BITS, IS_INT, 4, 4, 4, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else
-            launch_gemm_cfg<BITS, IS_INT, 4, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+            launch_gemm_cfg<BITS, IS_INT, 4, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     }
 }
 
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
-                           void *Y, int64_t M, int64_t N, int64_t K, int bits, void *ws, size_t ws_bytes,
+                           void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, void *ws, size_t ws_bytes,
                            hipStream_t stream)
 {
     if (is_int) {
-        if (bits == 3) launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
-        else launch_gemm<2, true>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        if (bits == 3) launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else launch_gemm<2, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
-        if (bits == 3) launch_gemm<3, false>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
-        else launch_gemm<2, false>(codes, scales, zeros, X, Y, M, N, K, ws, ws_bytes, stream);
+        if (bits == 3) launch_gemm<3, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else launch_gemm<2, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     }
     return hipGetLastError();
 }

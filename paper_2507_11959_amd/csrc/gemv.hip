@@ -18,18 +18,23 @@ namespace potq {
 // lane / 16) of v_mfma_f32_16x16x32_f16; the B operand is the matching eight x
 // values, the same in all 16 columns, so every column of the 16x16 result holds
 // the partial products of the 16 rows.  Products are exact, sums fp32.
+// `s`/`z` serve columns 0..63, `s_hi`/`z_hi` columns 64..127 (the same values for group size 128).
 template <int BITS, bool IS_INT>
-__device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, uint32_t z,
-                                           const u32x4 *__restrict__ xg, float4_t (&acc)[4])
+__device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, uint32_t z, uint32_t s_hi,
+                                           uint32_t z_hi, const u32x4 *__restrict__ xg, float4_t (&acc)[4])
 {
     PotTable pt;
     IntTable it;
-    if (IS_INT)
-        it = int_table<BITS>(s, z);
-    else
-        pt = pot_table<BITS>(s);
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
+        if (b == 0 || b == 2) {
+            // b == 2 rebuilds the table from the second scale; with one scale per 128 columns
+            // the inputs are identical and the compiler keeps the first table
+            if (IS_INT)
+                it = int_table<BITS>(b ? s_hi : s, b ? z_hi : z);
+            else
+                pt = pot_table<BITS>(b ? s_hi : s);
+        }
         uint32_t sel[8];
         if (BITS == 3)
             selectors3(L[0][b], L[1][b], L[BITS - 1][b], sel);
@@ -64,8 +69,9 @@ constexpr int kGemvWaves = 8;
 template <int BITS, bool IS_INT, int S>
 __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
-    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K)
+    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K, int gs)
 {
+    // gs = 0: one scale per 128 columns; gs = 1: one per 64 (two per tile row)
     constexpr int R = kGemvWaves / S;                   // row tiles per workgroup
     extern __shared__ u32x4 smem[];
     // x as fp16 pairs, one 256-byte run per scale group, runs padded to 272 bytes so
@@ -92,7 +98,9 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     const uint16_t *srow = scales + (rowtile * kTileRows + (lane >> 2)) * G;
     const uint16_t *zrow = IS_INT ? zeros + (rowtile * kTileRows + (lane >> 2)) * G : nullptr;
     const int scale_owner = (4 * r + t) * 4;            // ds_bpermute byte address
-    (void)row;
+    // group size 64: lane (r, t) reads its own two scales as one 32-bit word (less well coalesced)
+    const uint32_t *srow2 = (const uint32_t *)(scales + row * (int64_t)(2 * G));
+    const uint32_t *zrow2 = IS_INT ? (const uint32_t *)(zeros + row * (int64_t)(2 * G)) : nullptr;
 
     // MFMA ignores the execution mask, so the group loop must be uniform: every
     // lane runs ceil(G / kStep) rounds.  A lane whose group index runs past G
@@ -109,9 +117,14 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
         const int gc = g < G ? g : G - 1;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) L[j] = __builtin_nontemporal_load(tile0 + (int64_t)gc * (BITS * 16) + 16 * j);
-        const int gs = min(part * 4 + (lane & 3), G - 1);
-        s = srow[gs];
-        if (IS_INT) z = zrow[gs];
+        if (gs) {
+            s = srow2[gc];
+            if (IS_INT) z = zrow2[gc];
+        } else {
+            const int gq = min(part * 4 + (lane & 3), G - 1);
+            s = srow[gq];
+            if (IS_INT) z = zrow[gq];
+        }
     }
 
     for (int i = tid; i < K / 8; i += kGemvWaves * kWave) xs[(i >> 4) * kXRun + (i & 15)] = x[i];
@@ -130,17 +143,34 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
 #pragma unroll
             for (int j = 0; j < BITS; ++j)
                 Ln[j] = __builtin_nontemporal_load(tile0 + (int64_t)gc * (BITS * 16) + 16 * j);
-            const int gs = min(part * 4 + (round + 1) * kStep + (lane & 3), G - 1);
-            sn = srow[gs];
-            if (IS_INT) zn = zrow[gs];
+            if (gs) {
+                sn = srow2[gc];
+                if (IS_INT) zn = zrow2[gc];
+            } else {
+                const int gq = min(part * 4 + (round + 1) * kStep + (lane & 3), G - 1);
+                sn = srow[gq];
+                if (IS_INT) zn = zrow[gq];
+            }
         }
-        uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)s);
-        uint32_t zo = IS_INT ? (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)z) : 0u;
+        uint32_t so, zo = 0u, so_hi, zo_hi = 0u;
+        if (gs) {
+            so = s & 0xFFFFu;
+            so_hi = s >> 16;
+            if (IS_INT) {
+                zo = z & 0xFFFFu;
+                zo_hi = z >> 16;
+            }
+        } else {
+            so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)s);
+            if (IS_INT) zo = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)z);
+            so_hi = so;
+            zo_hi = zo;
+        }
         if (g >= G) {
-            so = 0x3C00u;
-            zo = 0u;
+            so = so_hi = 0x3C00u;
+            zo = zo_hi = 0u;
         }
-        gemv_group<BITS, IS_INT>(L, so, zo, g < G ? xs + g * kXRun : zero_block, acc);
+        gemv_group<BITS, IS_INT>(L, so, zo, so_hi, zo_hi, g < G ? xs + g * kXRun : zero_block, acc);
         g = gn;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
@@ -181,7 +211,7 @@ size_t gemv_lds_bytes(int64_t K)
 
 template <int BITS, bool IS_INT>
 static void launch_gemv(const void *codes, const void *scales, const void *zeros, const void *x, void *y,
-                        int64_t N, int64_t K, hipStream_t stream)
+                        int64_t N, int64_t K, int group, hipStream_t stream)
 {
     const int64_t rowtiles = N / kTileRows;
     const size_t lds = gemv_lds_bytes(K);
@@ -190,7 +220,8 @@ static void launch_gemv(const void *codes, const void *scales, const void *zeros
     hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT>),                                              \
                        dim3((unsigned)((rowtiles + (kGemvWaves / SPLIT) - 1) / (kGemvWaves / SPLIT))),         \
                        dim3(kGemvWaves * kWave), lds, stream, (const u32x4 *)codes, (const uint16_t *)scales,  \
-                       (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K)
+                       (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K,     \
+                       group == 64 ? 1 : 0)
     // Eight wavefronts per tile measured best or equal on every decoder shape (all of a
     // row's groups in flight at once); short rows take fewer so that no wavefront idles.
 #ifdef POTQ_GEMV_SPLIT
@@ -207,14 +238,14 @@ static void launch_gemv(const void *codes, const void *scales, const void *zeros
 }
 
 hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
-                           void *y, int64_t N, int64_t K, int bits, hipStream_t stream)
+                           void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream)
 {
     if (is_int) {
-        if (bits == 3) launch_gemv<3, true>(codes, scales, zeros, x, y, N, K, stream);
-        else launch_gemv<2, true>(codes, scales, zeros, x, y, N, K, stream);
+        if (bits == 3) launch_gemv<3, true>(codes, scales, zeros, x, y, N, K, group, stream);
+        else launch_gemv<2, true>(codes, scales, zeros, x, y, N, K, group, stream);
     } else {
-        if (bits == 3) launch_gemv<3, false>(codes, scales, zeros, x, y, N, K, stream);
-        else launch_gemv<2, false>(codes, scales, zeros, x, y, N, K, stream);
+        if (bits == 3) launch_gemv<3, false>(codes, scales, zeros, x, y, N, K, group, stream);
+        else launch_gemv<2, false>(codes, scales, zeros, x, y, N, K, group, stream);
     }
     return hipGetLastError();
 }

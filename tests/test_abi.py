@@ -66,7 +66,7 @@ def test_host_side_validation(lib):
     assert i(A, A, None, A, 16, 128, 3, 128, None) == NULL
     assert i(A, A, MIS, A, 16, 128, 2, 128, None) == ALIGN
     g = lib.pot_gemv
-    assert g(A, A, A, A, 16, 128, 3, 64, 1, None) == GROUP            # fused kernels: group 128 only
+    assert g(A, A, A, A, 16, 128, 3, 32, 1, None) == GROUP
     assert g(A, A, A, A, 16, 128, 3, 128, 7, None) == LAYOUT
     assert g(A, A, A, A, 8, 128, 3, 128, 1, None) == SHAPE            # tiled layout: N % 16
     assert g(A, A, None, A, 16, 128, 3, 128, 1, None) == NULL

@@ -142,27 +142,27 @@ def test_repack_round_trip_and_permutation(potq, bits, N, K):
     assert not np.array_equal(t.ravel(), packed.ravel())
 
 
-def _gemv_inputs(seed, N, K, bits, is_int):
+def _gemv_inputs(seed, N, K, bits, is_int, group=128):
     packed = workloads.packed_codes(seed, N, K, bits)
     if is_int:
-        S, Z = workloads.int_scales_zeros(seed + 3, N, K, bits)
+        S, Z = workloads.int_scales_zeros(seed + 3, N, K, bits, group)
     else:
-        S, Z = workloads.pot_scales(seed + 1, N, K), None
+        S, Z = workloads.pot_scales(seed + 1, N, K, group), None
     return packed, S, Z
 
 
-def _run_gemm(potq, packed, S, Z, X, K, bits, use_workspace=True):
+def _run_gemm(potq, packed, S, Z, X, K, bits, use_workspace=True, group=128):
     tiled = potq.potq_repack(dev(packed), K, bits)
     ws = potq.gemm_workspace(X.shape[0], packed.shape[0], K, bits) if use_workspace else None
     if X.shape[0] == 1:
         if Z is None:
-            y = potq.pot_gemv(tiled, dev(S), dev(X[0]), K, bits)
+            y = potq.pot_gemv(tiled, dev(S), dev(X[0]), K, bits, group)
         else:
-            y = potq.int_gemv(tiled, dev(S), dev(Z), dev(X[0]), K, bits)
+            y = potq.int_gemv(tiled, dev(S), dev(Z), dev(X[0]), K, bits, group)
         return host_bits(y)[None, :]
     if Z is None:
-        return host_bits(potq.pot_gemm(tiled, dev(S), dev(X), K, bits, workspace=ws))
-    return host_bits(potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits, workspace=ws))
+        return host_bits(potq.pot_gemm(tiled, dev(S), dev(X), K, bits, group, workspace=ws))
+    return host_bits(potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits, group, workspace=ws))
 
 
 @pytest.mark.parametrize("is_int", [False, True])
@@ -190,6 +190,33 @@ def test_gemv_vs_oracle(potq, bits, N, K, is_int):
     got = _run_gemm(potq, packed, S, Z, X, K, bits)
     e, nw, nfloor = rel_err(got, want)
     assert e <= REL_TOL, (e, nw, nfloor)
+
+
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("M,N,K", [(1, 48, 640), (1, 272, 4096), (1, 32, 11008), (16, 80, 1280), (70, 64, 2560),
+                                   (256, 144, 1024)])
+def test_group_size_64_in_fused_kernels(potq, bits, M, N, K, is_int):
+    # Sec. 3.1 names 64 as the other group size: two scales per 128-column tile row
+    packed, S, Z = _gemv_inputs(1100 + M + N + bits, N, K, bits, is_int, group=64)
+    assert S.shape == (N, K // 64)
+    X = workloads.activations(1200 + M, M, K)
+    want = oracle.gemm(packed, S, Z, X, K, bits, 64, nthreads=8)
+    got = _run_gemm(potq, packed, S, Z, X, K, bits, group=64)
+    e, nw, nfloor = rel_err(got, want)
+    assert e <= REL_TOL, (e, nw, nfloor)
+    # exact columns through one-hot activations, on both halves of a tile row
+    W = oracle.int_dequant(packed, S, Z, K, bits, 64) if is_int else oracle.pot_dequant(packed, S, K, bits, 64)
+    ks = [0, 63, 64, 127, 128, K - 65, K - 1]
+    E = np.zeros((len(ks) if M > 1 else 1, K), np.float16)
+    if M > 1:
+        E[np.arange(len(ks)), ks] = 1.0
+        assert np.array_equal(_run_gemm(potq, packed, S, Z, E, K, bits, group=64), W[:, ks].T)
+    else:
+        for k in ks:
+            E[:] = 0
+            E[0, k] = 1.0
+            assert np.array_equal(_run_gemm(potq, packed, S, Z, E, K, bits, group=64)[0], W[:, k]), k
 
 
 def test_gemv_all_ones_zero_codes(potq):
