@@ -240,6 +240,41 @@ def main() -> int:
         extras["pot_gemv_3bit_7b_shapes"] = gemv
         torch.cuda.empty_cache()
 
+        # shared-activation batches: q/k/v (3 x 4096x4096) and gate/up (2 x 11008x4096) in one launch each
+        shared = []
+        for label, (N, K), copies in (("qkv 3x4096x4096", (4096, 4096), 3), ("gate_up 2x11008x4096", (11008, 4096), 2)):
+            nbytes = copies * workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
+            R = rotate(nbytes)
+            codes_h, scales_h = workloads.pot_matrix(2, 7, N, K, b3, G)
+            x = to_dev(workloads.activations(workloads.seed_of(2, 7, 2), 1, K)[0])
+            tiled = potq.potq_repack(to_dev(codes_h), K, b3)
+            keep, batches, singles = [], [], []
+            for r in range(R):
+                ms_ = [(tiled.clone(), to_dev(scales_h), None,
+                        torch.empty((N,), dtype=torch.float16, device=dev)) for _ in range(copies)]
+                keep.append(ms_)
+                batches.append(binding.make_gemv_batch(ms_, K, b3))
+                singles.append([(m_[0].data_ptr(), m_[1].data_ptr(), x.data_ptr(), m_[3].data_ptr(), N, K, b3, G, 1,
+                                 stream) for m_ in ms_])
+
+            def batch_rot():
+                for arr in batches:
+                    check(lib.pot_gemv_batch(arr, copies, x.data_ptr(), K, b3, G, 1, stream))
+
+            def single_rot():
+                for calls in singles:
+                    for c in calls:
+                        check(lib.pot_gemv(*c))
+
+            reps = max(2, 128 // R)
+            us_b = _time_steps(torch, batch_rot, reps, 2) * 1e3 / R
+            us_s = _time_steps(torch, single_rot, reps, 2) * 1e3 / R
+            shared.append({"batch": label, "us_one_launch": round(us_b, 2), "us_separate_launches": round(us_s, 2),
+                           "GBps": round(nbytes / us_b / 1e3, 1), "buffers_rotated": R})
+            del keep, batches, singles
+        extras["pot_gemv_batch_3bit_shared_activation"] = shared
+        torch.cuda.empty_cache()
+
         # fused MFMA GEMM, 3-bit, 13B shapes
         gemm = []
         for i, (name, N, K) in enumerate(workloads.GEMM_13B_SHAPES):

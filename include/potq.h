@@ -155,6 +155,29 @@ int int_gemv(const void *codes, const void *scales, const void *zeros, const voi
              int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
 
 /*
+ * pot_gemv_batch / int_gemv_batch -- up to POTQ_MAX_BATCH matrices that consume
+ * the SAME activation vector (the q/k/v or gate/up projections of a decoder
+ * layer) in one kernel launch: y_i = W~_i x.  At batch 1 a 4096x4096 product is
+ * a few-microsecond kernel dominated by launch and memory latency, so sharing a
+ * launch is worth more than any tuning inside it.  `items_host` is a HOST array
+ * (copied into the launch); all matrices share K, bits, group and layout, each
+ * has its own N (a multiple of 16).  Results equal `count` separate calls bit
+ * for bit.
+ */
+typedef struct potq_gemv_item {
+    const void *codes;      /* device, POTQ_LAYOUT_TILE16 */
+    const void *scales;     /* device, N x (K/group) fp16 */
+    const void *zeros;      /* device, N x (K/group) fp16; uniform baseline only */
+    void *y_f16;            /* device, N fp16 */
+    int64_t N;
+} potq_gemv_item;
+
+int pot_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f16, int64_t K,
+                   int bits, int group, int layout, void *hip_stream);
+int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f16, int64_t K,
+                   int bits, int group, int layout, void *hip_stream);
+
+/*
  * pot_gemm -- fused de-quantise + GEMM on the matrix cores:
  *   Y[m,n] = fp16( sum_k X[m,k] * W~[n,k] ),   X: M x K fp16 row-major,
  *   Y: M x N fp16 row-major (Y = X . W~^T, the nn.Linear convention).

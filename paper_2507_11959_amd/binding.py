@@ -37,6 +37,8 @@ EXPORTS = {
     "pot_dequant_batch": (_int, [_vp, _int, _int, _int, _vp]),
     "int_dequant_batch": (_int, [_vp, _int, _int, _int, _vp]),
     "potq_repack": (_int, [_vp, _vp, _i64, _i64, _int, _int, _vp]),
+    "pot_gemv_batch": (_int, [_vp, _int, _vp, _i64, _int, _int, _int, _vp]),
+    "int_gemv_batch": (_int, [_vp, _int, _vp, _i64, _int, _int, _int, _vp]),
     "pot_gemv": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
     "int_gemv": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
     "potq_gemm_workspace_bytes": (ctypes.c_size_t, [_i64, _i64, _i64, _int]),
@@ -198,6 +200,39 @@ def _ws(workspace):
     if workspace is None:
         return None, 0
     return _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+
+
+class GemvItem(ctypes.Structure):
+    """Mirror of `potq_gemv_item`."""
+    _fields_ = [("codes", _vp), ("scales", _vp), ("zeros", _vp), ("y_f16", _vp), ("N", _i64)]
+
+
+def make_gemv_batch(mats, K: int, bits: int, is_int: bool = False):
+    """mats: list of (codes, scales, zeros-or-None, y) device tensors -> ctypes descriptor array (raw pointers)."""
+    arr = (GemvItem * len(mats))()
+    for i, (codes, scales, zeros, y) in enumerate(mats):
+        arr[i].codes = _dev(codes, torch.uint8, "codes")
+        arr[i].scales = _dev(scales, torch.float16, "scales")
+        arr[i].zeros = _dev(zeros, torch.float16, "zeros") if is_int else None
+        arr[i].y_f16 = _dev(y, torch.float16, "y")
+        arr[i].N = _shape_codes(codes, K, bits)
+    return arr
+
+
+def pot_gemv_batch(mats, x, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16):
+    """mats: list of (codes, scales) sharing x; -> list of y tensors, one launch."""
+    ys = [torch.empty((_shape_codes(c, K, bits),), dtype=torch.float16, device=c.device) for (c, s) in mats]
+    arr = make_gemv_batch([(c, s, None, y) for (c, s), y in zip(mats, ys)], K, bits)
+    _ok(_lib.pot_gemv_batch(arr, len(mats), _dev(x, torch.float16, "x"), K, bits, group, layout, _stream()))
+    return ys
+
+
+def int_gemv_batch(mats, x, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16):
+    """mats: list of (codes, scales, zeros) sharing x; -> list of y tensors, one launch."""
+    ys = [torch.empty((_shape_codes(c, K, bits),), dtype=torch.float16, device=c.device) for (c, s, z) in mats]
+    arr = make_gemv_batch([(c, s, z, y) for (c, s, z), y in zip(mats, ys)], K, bits, is_int=True)
+    _ok(_lib.int_gemv_batch(arr, len(mats), _dev(x, torch.float16, "x"), K, bits, group, layout, _stream()))
+    return ys
 
 
 def pot_gemm(codes, scales, X, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16, out=None,

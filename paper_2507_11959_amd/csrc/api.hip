@@ -18,6 +18,10 @@ hipError_t run_fill_zero(void *p, int64_t count, hipStream_t stream);
 size_t gemv_lds_bytes(int64_t K);
 hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
                            void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
+int gemv_max_batch();
+hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *codes, const void *const *scales,
+                                 const void *const *zeros, void *const *y, const int64_t *N, const void *x,
+                                 int64_t K, int bits, int group, hipStream_t stream);
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, void *ws, size_t ws_bytes,
                            hipStream_t stream);
@@ -104,6 +108,48 @@ int gemv_entry(bool is_int, const void *codes, const void *scales, const void *z
         return POTQ_ERR_ALIGN;
     if (potq::gemv_lds_bytes(K) > 64 * 1024) return POTQ_ERR_SHAPE;
     return finish(potq::run_gemv_tile16(is_int, codes, scales, zeros, x, y, N, K, bits, group, (hipStream_t)stream));
+}
+
+int gemv_batch_entry(bool is_int, const potq_gemv_item *items, int count, const void *x, int64_t K, int bits,
+                     int group, int layout, void *stream)
+{
+    if (bits != 2 && bits != 3) return POTQ_ERR_BITS;
+    if (group != 64 && group != 128) return POTQ_ERR_GROUP;
+    if (K < 0 || K > kMaxDim || (K % 128) != 0) return POTQ_ERR_SHAPE;
+    if (count < 0 || count > potq::gemv_max_batch()) return POTQ_ERR_SHAPE;
+    if (layout != POTQ_LAYOUT_TILE16) return POTQ_ERR_LAYOUT;
+    if (count == 0) return POTQ_OK;
+    if (!items) return POTQ_ERR_NULL;
+    const void *codes[POTQ_MAX_BATCH], *scales[POTQ_MAX_BATCH], *zeros[POTQ_MAX_BATCH];
+    void *y[POTQ_MAX_BATCH];
+    int64_t N[POTQ_MAX_BATCH];
+    int live = 0;
+    for (int i = 0; i < count; ++i) {
+        const potq_gemv_item &it = items[i];
+        if (it.N < 0 || it.N > kMaxDim || (it.N % 16) != 0) return POTQ_ERR_SHAPE;
+        if (it.N == 0) continue;
+        if (!it.y_f16) return POTQ_ERR_NULL;
+        if (misaligned(it.y_f16)) return POTQ_ERR_ALIGN;
+        if (K == 0) {
+            const int st = finish(potq::run_fill_zero(it.y_f16, it.N, (hipStream_t)stream));
+            if (st != POTQ_OK) return st;
+            continue;
+        }
+        if (!it.codes || !it.scales || (is_int && !it.zeros)) return POTQ_ERR_NULL;
+        if (misaligned(it.codes) || misaligned(it.scales) || (is_int && misaligned(it.zeros))) return POTQ_ERR_ALIGN;
+        codes[live] = it.codes;
+        scales[live] = it.scales;
+        zeros[live] = it.zeros;
+        y[live] = it.y_f16;
+        N[live] = it.N;
+        ++live;
+    }
+    if (live == 0) return POTQ_OK;
+    if (!x) return POTQ_ERR_NULL;
+    if (misaligned(x)) return POTQ_ERR_ALIGN;
+    if (potq::gemv_lds_bytes(K) > 64 * 1024) return POTQ_ERR_SHAPE;
+    return finish(potq::run_gemv_tile16_batch(is_int, live, codes, scales, zeros, y, N, x, K, bits, group,
+                                              (hipStream_t)stream));
 }
 
 int gemm_entry(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
@@ -205,6 +251,18 @@ int int_gemv(const void *codes, const void *scales, const void *zeros, const voi
              int64_t K, int bits, int group, int layout, void *hip_stream)
 {
     return gemv_entry(true, codes, scales, zeros, x_f16, y_f16, N, K, bits, group, layout, hip_stream);
+}
+
+int pot_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f16, int64_t K, int bits, int group,
+                   int layout, void *hip_stream)
+{
+    return gemv_batch_entry(false, items_host, count, x_f16, K, bits, group, layout, hip_stream);
+}
+
+int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f16, int64_t K, int bits, int group,
+                   int layout, void *hip_stream)
+{
+    return gemv_batch_entry(true, items_host, count, x_f16, K, bits, group, layout, hip_stream);
 }
 
 size_t potq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits)

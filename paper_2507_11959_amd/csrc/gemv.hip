@@ -21,15 +21,14 @@ namespace potq {
 // `s`/`z` serve columns 0..63, `s_hi`/`z_hi` columns 64..127 (the same values for group size 128).
 template <int BITS, bool IS_INT>
 __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, uint32_t z, uint32_t s_hi,
-                                           uint32_t z_hi, const u32x4 *__restrict__ xg, float4_t (&acc)[4])
+                                           uint32_t z_hi, bool two_scales, const u32x4 *__restrict__ xg,
+                                           float4_t (&acc)[4])
 {
     PotTable pt;
     IntTable it;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-        if (b == 0 || b == 2) {
-            // b == 2 rebuilds the table from the second scale; with one scale per 128 columns
-            // the inputs are identical and the compiler keeps the first table
+        if (b == 0 || (b == 2 && two_scales)) {     // wave-uniform: the second table exists only for group size 64
             if (IS_INT)
                 it = int_table<BITS>(b ? s_hi : s, b ? z_hi : z);
             else
@@ -66,11 +65,12 @@ constexpr int kGemvWaves = 8;
 // of K in flight at once), tall matrices want S = 1 or 2 (long-lived wavefronts,
 // no cross-wavefront sums).  The codes of the next round are requested before
 // the current one is expanded, and the first request goes out before x is staged.
-template <int BITS, bool IS_INT, int S>
-__global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
+template <int BITS, bool IS_INT, int S, bool G64>
+__device__ __forceinline__ void gemv_tile16_body(
     const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
-    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K, int gs)
+    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K, int64_t block)
 {
+    constexpr int gs = G64 ? 1 : 0;
     // gs = 0: one scale per 128 columns; gs = 1: one per 64 (two per tile row)
     constexpr int R = kGemvWaves / S;                   // row tiles per workgroup
     extern __shared__ u32x4 smem[];
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     const int G = K / kTileCols;
     constexpr int kStep = 4 * S;
     const int part = wave % S;
-    int64_t rowtile = (int64_t)blockIdx.x * R + wave / S;
+    int64_t rowtile = block * R + wave / S;
     const bool live = rowtile < rowtiles;
     if (!live) rowtile = rowtiles - 1;                  // surplus wavefronts redo the last tile, store nothing
     const int64_t row = rowtile * kTileRows + r;
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
             so = so_hi = 0x3C00u;
             zo = zo_hi = 0u;
         }
-        gemv_group<BITS, IS_INT>(L, so, zo, so_hi, zo_hi, g < G ? xs + g * kXRun : zero_block, acc);
+        gemv_group<BITS, IS_INT>(L, so, zo, so_hi, zo_hi, gs != 0, g < G ? xs + g * kXRun : zero_block, acc);
         g = gn;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     __syncthreads();
     if (tid < R * kTileRows) {
         const int tile = tid / kTileRows, rr = tid % kTileRows;
-        const int64_t rt = (int64_t)blockIdx.x * R + tile;
+        const int64_t rt = block * R + tile;
         float sum = 0.f;
 #pragma unroll
         for (int p = 0; p < S; ++p) sum += red[(tile * S + p) * kTileRows + rr];
@@ -204,9 +204,50 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     }
 }
 
+template <int BITS, bool IS_INT, int S, bool G64>
+__global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
+    const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
+    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K)
+{
+    gemv_tile16_body<BITS, IS_INT, S, G64>(codes, scales, zeros, x, y, rowtiles, K, blockIdx.x);
+}
+
+// Several matrices that consume the same activation vector (q/k/v, gate/up) in one launch:
+// a batch-1 GEMV on a 4096x4096 matrix is a 4 us kernel of which most is launch and memory
+// latency, so sharing one launch pays more than anything inside the kernel.
+constexpr int kMaxGemvBatch = 16;
+struct GemvBatch {
+    const u32x4 *codes[kMaxGemvBatch];
+    const uint16_t *scales[kMaxGemvBatch];
+    const uint16_t *zeros[kMaxGemvBatch];
+    uint16_t *y[kMaxGemvBatch];
+    int64_t rowtiles[kMaxGemvBatch];
+    uint32_t first_block[kMaxGemvBatch + 1];
+    int count;
+};
+
+template <int BITS, bool IS_INT, int S, bool G64>
+__global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_batch_kernel(
+    const GemvBatch batch, const u32x4 *__restrict__ x, int K)
+{
+    int i = 0;
+    while (i + 1 < batch.count && blockIdx.x >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
+    gemv_tile16_body<BITS, IS_INT, S, G64>(batch.codes[i], batch.scales[i], batch.zeros[i], x, batch.y[i],
+                                           batch.rowtiles[i], K, blockIdx.x - batch.first_block[i]);
+}
+
 size_t gemv_lds_bytes(int64_t K)
 {
     return (size_t)(K / kTileCols) * kXRun * 16 + 256 + kGemvWaves * kTileRows * sizeof(float);
+}
+
+// Eight wavefronts per tile measured best or equal on every decoder shape (all of a row's
+// groups in flight at once); short rows take fewer so that no wavefront idles.
+static int gemv_split(int64_t G)
+{
+    int split = 8;
+    while (split > 1 && G < 4 * split) split /= 2;
+    return split;
 }
 
 template <int BITS, bool IS_INT>
@@ -216,25 +257,86 @@ static void launch_gemv(const void *codes, const void *scales, const void *zeros
     const int64_t rowtiles = N / kTileRows;
     const size_t lds = gemv_lds_bytes(K);
     const int64_t G = K / kTileCols;
-#define POTQ_LAUNCH_GEMV(SPLIT)                                                                                \
-    hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT>),                                              \
-                       dim3((unsigned)((rowtiles + (kGemvWaves / SPLIT) - 1) / (kGemvWaves / SPLIT))),         \
-                       dim3(kGemvWaves * kWave), lds, stream, (const u32x4 *)codes, (const uint16_t *)scales,  \
-                       (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K,     \
-                       group == 64 ? 1 : 0)
+#define POTQ_LAUNCH_GEMV(SPLIT)                                                                                    \
+    do {                                                                                                           \
+        const dim3 grid((unsigned)((rowtiles + (kGemvWaves / SPLIT) - 1) / (kGemvWaves / SPLIT)));                 \
+        if (group == 64)                                                                                           \
+            hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT, true>), grid, dim3(kGemvWaves * kWave),    \
+                               lds, stream, (const u32x4 *)codes, (const uint16_t *)scales,                        \
+                               (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K);        \
+        else                                                                                                       \
+            hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT, false>), grid, dim3(kGemvWaves * kWave),   \
+                               lds, stream, (const u32x4 *)codes, (const uint16_t *)scales,                        \
+                               (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K);        \
+    } while (0)
     // Eight wavefronts per tile measured best or equal on every decoder shape (all of a
     // row's groups in flight at once); short rows take fewer so that no wavefront idles.
 #ifdef POTQ_GEMV_SPLIT
     POTQ_LAUNCH_GEMV(POTQ_GEMV_SPLIT);
 #else
-    int split = 8;
-    while (split > 1 && G < 4 * split) split /= 2;
+    const int split = gemv_split(G);
     if (split == 8) POTQ_LAUNCH_GEMV(8);
     else if (split == 4) POTQ_LAUNCH_GEMV(4);
     else if (split == 2) POTQ_LAUNCH_GEMV(2);
     else POTQ_LAUNCH_GEMV(1);
 #endif
 #undef POTQ_LAUNCH_GEMV
+}
+
+int gemv_max_batch() { return kMaxGemvBatch; }
+
+template <int BITS, bool IS_INT>
+static void launch_gemv_batch(const GemvBatch &b, unsigned blocks, const void *x, int64_t K, int group, int split,
+                              hipStream_t stream)
+{
+    const size_t lds = gemv_lds_bytes(K);
+#define POTQ_LAUNCH_GEMVB(SPLIT)                                                                                   \
+    do {                                                                                                           \
+        if (group == 64)                                                                                           \
+            hipLaunchKernelGGL((gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, true>), dim3(blocks),                \
+                               dim3(kGemvWaves * kWave), lds, stream, b, (const u32x4 *)x, (int)K);                \
+        else                                                                                                       \
+            hipLaunchKernelGGL((gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, false>), dim3(blocks),               \
+                               dim3(kGemvWaves * kWave), lds, stream, b, (const u32x4 *)x, (int)K);                \
+    } while (0)
+    if (split == 8) POTQ_LAUNCH_GEMVB(8);
+    else if (split == 4) POTQ_LAUNCH_GEMVB(4);
+    else if (split == 2) POTQ_LAUNCH_GEMVB(2);
+    else POTQ_LAUNCH_GEMVB(1);
+#undef POTQ_LAUNCH_GEMVB
+}
+
+// `count` non-empty matrices (count <= kMaxGemvBatch), validated by the caller; all share x, K, bits, group.
+hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *codes, const void *const *scales,
+                                 const void *const *zeros, void *const *y, const int64_t *N, const void *x,
+                                 int64_t K, int bits, int group, hipStream_t stream)
+{
+    const int split = gemv_split(K / kTileCols);
+    const int R = kGemvWaves / split;
+    GemvBatch b;
+    uint64_t blocks = 0;
+    for (int i = 0; i < kMaxGemvBatch; ++i) {
+        const bool live = i < count;
+        b.codes[i] = live ? (const u32x4 *)codes[i] : nullptr;
+        b.scales[i] = live ? (const uint16_t *)scales[i] : nullptr;
+        b.zeros[i] = (live && is_int) ? (const uint16_t *)zeros[i] : nullptr;
+        b.y[i] = live ? (uint16_t *)y[i] : nullptr;
+        b.rowtiles[i] = live ? N[i] / kTileRows : 0;
+        b.first_block[i] = (uint32_t)blocks;
+        if (live) blocks += (uint64_t)((b.rowtiles[i] + R - 1) / R);
+    }
+    b.first_block[kMaxGemvBatch] = (uint32_t)blocks;
+    b.count = count;
+    if (blocks == 0) return hipSuccess;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (is_int) {
+        if (bits == 3) launch_gemv_batch<3, true>(b, (unsigned)blocks, x, K, group, split, stream);
+        else launch_gemv_batch<2, true>(b, (unsigned)blocks, x, K, group, split, stream);
+    } else {
+        if (bits == 3) launch_gemv_batch<3, false>(b, (unsigned)blocks, x, K, group, split, stream);
+        else launch_gemv_batch<2, false>(b, (unsigned)blocks, x, K, group, split, stream);
+    }
+    return hipGetLastError();
 }
 
 hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,

@@ -27,7 +27,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"pot_dequant", "int_dequant", "pot_gemv", "int_gemv", "pot_gemm", "int_gemm", "potq_repack",
-            "pot_check_scales", "pot_dequant_batch", "int_dequant_batch", "potq_gemm_workspace_bytes", "pot_quantize", "potq_version", "potq_strerror", "potq_packed_row_bytes",
+            "pot_check_scales", "pot_dequant_batch", "int_dequant_batch", "pot_gemv_batch", "int_gemv_batch", "potq_gemm_workspace_bytes", "pot_quantize", "potq_version", "potq_strerror", "potq_packed_row_bytes",
             "potq_packed_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n

@@ -147,3 +147,33 @@ def test_config4_gemm_3bit_13b_shapes_sampled_rows(potq, M, is_int):
         e, nw, nfloor = rel_err(got, want)
         assert e <= REL_TOL, (name, M, e, nw, nfloor)
         assert bool(torch.isfinite(Y).all())
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_second_workload_llama30b_layer(potq, bits):
+    """LLaMA-30B-shaped layer: batched dequant (sampled rows + invariants) and the q/k/v and gate/up
+    projections as shared-activation GEMV batches (whole outputs)."""
+    rng = np.random.default_rng(30 + bits)
+    layer = workloads.LLAMA_30B_LAYER
+    host, mats = [], []
+    for i, (name, N, K) in enumerate(layer):
+        packed, scales = workloads.pot_matrix(5, i, N, K, bits, G)
+        host.append((packed, scales))
+        mats.append((dev(packed), dev(scales), torch.empty((N, K), dtype=torch.float16, device="cuda:0"), K))
+    potq.pot_dequant_batch(mats, bits, G)
+    for (name, N, K), (packed, scales), m in zip(layer, host, mats):
+        rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 64)]))
+        want = oracle.pot_dequant(packed[rows], scales[rows], K, bits, G, nthreads=_threads())
+        assert np.array_equal(host_bits(m[2][torch.from_numpy(rows).to("cuda:0")]), want), name
+        _invariants(m[2], m[1], True, bits)
+    del mats
+    torch.cuda.empty_cache()
+    for idxs in ([0, 1, 2], [4, 5]):                 # q, k, v share x; gate, up share x
+        K = layer[idxs[0]][2]
+        x = workloads.activations(workloads.seed_of(5, idxs[0], 2), 1, K)
+        batch = [(potq.potq_repack(dev(host[i][0]), K, bits), dev(host[i][1])) for i in idxs]
+        ys = potq.pot_gemv_batch(batch, dev(x[0]), K, bits)
+        for i, y in zip(idxs, ys):
+            want = oracle.gemm(host[i][0], host[i][1], None, x, K, bits, G, nthreads=_threads())[0]
+            e, nw, nfloor = rel_err(host_bits(y), want)
+            assert e <= REL_TOL, (layer[i][0], e, nw, nfloor)

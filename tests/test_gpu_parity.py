@@ -219,6 +219,34 @@ def test_group_size_64_in_fused_kernels(potq, bits, M, N, K, is_int):
             assert np.array_equal(_run_gemm(potq, packed, S, Z, E, K, bits, group=64)[0], W[:, k]), k
 
 
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("bits,group", [(3, 128), (2, 128), (3, 64)])
+def test_gemv_batch_shared_activation_equals_single_calls(potq, bits, group, is_int):
+    K = 2560
+    Ns = [64, 16, 272, 0, 48]
+    x = workloads.activations(1300 + bits, 1, K)
+    dx = dev(x[0])
+    mats, singles = [], []
+    for i, N in enumerate(Ns):
+        packed, S, Z = _gemv_inputs(1400 + 7 * i + bits, N, K, bits, is_int, group)
+        tiled = potq.potq_repack(dev(packed), K, bits) if N else torch.empty((0, K * bits // 8), dtype=torch.uint8,
+                                                                               device="cuda:0")
+        if is_int:
+            mats.append((tiled, dev(S), dev(Z)))
+            singles.append(potq.int_gemv(tiled, dev(S), dev(Z), dx, K, bits, group) if N else None)
+        else:
+            mats.append((tiled, dev(S)))
+            singles.append(potq.pot_gemv(tiled, dev(S), dx, K, bits, group) if N else None)
+        if N:
+            want = oracle.gemm(packed, S, Z, x, K, bits, group, nthreads=8)[0]
+            e, nw, nfloor = rel_err(host_bits(singles[-1]), want)
+            assert e <= REL_TOL
+    ys = potq.int_gemv_batch(mats, dx, K, bits, group) if is_int else potq.pot_gemv_batch(mats, dx, K, bits, group)
+    for y, single in zip(ys, singles):
+        if single is not None:
+            assert torch.equal(y, single)
+
+
 def test_gemv_all_ones_zero_codes(potq):
     N, K = 32, 1024
     scales = (2.0 ** -(np.arange(K // 128) % 4)[None, :] * np.ones((N, 1))).astype(np.float16)

@@ -32,6 +32,9 @@ LLAMA2_7B_LAYER = [("q", 4096, 4096), ("k", 4096, 4096), ("v", 4096, 4096), ("o"
                    ("gate", 11008, 4096), ("up", 11008, 4096), ("down", 4096, 11008)]
 LLAMA2_70B_LAYER = [("q", 8192, 8192), ("o", 8192, 8192), ("k", 1024, 8192), ("v", 1024, 8192),
                     ("gate", 28672, 8192), ("up", 28672, 8192), ("down", 8192, 28672)]
+# LLaMA-30B (hidden 6656, FFN 17920): the largest model the paper evaluates (Sec. 5.1)
+LLAMA_30B_LAYER = [("q", 6656, 6656), ("k", 6656, 6656), ("v", 6656, 6656), ("o", 6656, 6656),
+                   ("gate", 17920, 6656), ("up", 17920, 6656), ("down", 6656, 17920)]
 GEMV_7B_SHAPES = [("attn", 4096, 4096), ("up", 11008, 4096), ("down", 4096, 11008)]
 GEMM_13B_SHAPES = [("attn", 5120, 5120), ("up", 13824, 5120), ("down", 5120, 13824)]
 GEMM_TOKENS = [16, 64, 256]
@@ -43,6 +46,7 @@ CONFIGS = {
     2: {"what": "fused GEMV, 3-bit, 7B shapes", "bits": [3], "shapes": GEMV_7B_SHAPES},
     3: {"what": "Llama-2-70B layer, 2/3-bit dequant + GEMV", "bits": [2, 3], "shapes": LLAMA2_70B_LAYER},
     4: {"what": "fused GEMM, 3-bit, 13B shapes, M in 16/64/256", "bits": [3], "shapes": GEMM_13B_SHAPES},
+    5: {"what": "second workload: LLaMA-30B layer, 2/3-bit dequant + GEMV", "bits": [2, 3], "shapes": LLAMA_30B_LAYER},
 }
 
 
