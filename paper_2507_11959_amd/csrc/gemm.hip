@@ -22,8 +22,16 @@
 
 namespace potq {
 
+#ifndef POTQ_GEMM_XS_LIMIT
+#define POTQ_GEMM_XS_LIMIT 99
+#endif
+#ifndef POTQ_GEMM_WPE
+#define POTQ_GEMM_WPE 2
+#endif
+
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC>
-__global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
+__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu((RM * CN == 16) ? POTQ_GEMM_WPE : 1, 8)))
+void gemm_tile16_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
     const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, float *__restrict__ partial, int M, int64_t N, int K,
     int groups_per_split, int gs)
@@ -99,7 +107,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_tile16_kernel(
     // Every load is unconditional (indices are clamped, tokens past M are masked to
     // zero afterwards) and every iteration issues the same loads in the same order.
     constexpr bool kAlignedChunks = (GC % 4 == 0);     // chunks start on multiples of four groups (see launch)
-    constexpr int kXStages = (GC * PPT <= 4) ? 2 : 1;  // register stages of X (the LDS buffer is the other stage)
+    // register stages of X (the LDS buffer is one more stage); the big tiles keep one to stay at two wavefronts per SIMD
+    constexpr int kXStages = (GC * PPT <= 4 && RM * CN < POTQ_GEMM_XS_LIMIT) ? 2 : 1;
     uint32_t wr[2][GC][RM][BITS], sr[2][GC][RM], zr[2][GC][RM];
     u32x4 xreg[kXStages][GC][PPT];
     uint32_t xmask[PPT];

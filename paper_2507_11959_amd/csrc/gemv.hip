@@ -57,7 +57,10 @@ __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, u
 }
 
 constexpr int kXRun = 17;   // uint4 per scale group of x in LDS (16 + 1 of padding)
-constexpr int kGemvWaves = 8;
+#ifndef POTQ_GEMV_WAVES
+#define POTQ_GEMV_WAVES 8
+#endif
+constexpr int kGemvWaves = POTQ_GEMV_WAVES;
 
 // A workgroup of 8 wavefronts stages x in LDS once and serves 8/S row tiles of 16
 // rows.  S wavefronts share a tile and split its scale groups: wavefront part p,
@@ -245,7 +248,7 @@ size_t gemv_lds_bytes(int64_t K)
 // groups in flight at once); short rows take fewer so that no wavefront idles.
 static int gemv_split(int64_t G)
 {
-    int split = 8;
+    int split = kGemvWaves < 8 ? kGemvWaves : 8;
     while (split > 1 && G < 4 * split) split /= 2;
     return split;
 }
@@ -275,7 +278,7 @@ static void launch_gemv(const void *codes, const void *scales, const void *zeros
     POTQ_LAUNCH_GEMV(POTQ_GEMV_SPLIT);
 #else
     const int split = gemv_split(G);
-    if (split == 8) POTQ_LAUNCH_GEMV(8);
+    if (split == 8 && kGemvWaves >= 8) POTQ_LAUNCH_GEMV((kGemvWaves >= 8 ? 8 : 1));
     else if (split == 4) POTQ_LAUNCH_GEMV(4);
     else if (split == 2) POTQ_LAUNCH_GEMV(2);
     else POTQ_LAUNCH_GEMV(1);
@@ -299,7 +302,7 @@ static void launch_gemv_batch(const GemvBatch &b, unsigned blocks, const void *x
             hipLaunchKernelGGL((gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, false>), dim3(blocks),               \
                                dim3(kGemvWaves * kWave), lds, stream, b, (const u32x4 *)x, (int)K);                \
     } while (0)
-    if (split == 8) POTQ_LAUNCH_GEMVB(8);
+    if (split == 8 && kGemvWaves >= 8) POTQ_LAUNCH_GEMVB((kGemvWaves >= 8 ? 8 : 1));
     else if (split == 4) POTQ_LAUNCH_GEMVB(4);
     else if (split == 2) POTQ_LAUNCH_GEMVB(2);
     else POTQ_LAUNCH_GEMVB(1);
