@@ -5,8 +5,19 @@ import torch
 DEV = "cuda:0"
 
 # Tolerance of the fused GEMV / GEMM against the oracle: element-wise relative
-# error with the denominator floored at 2^-10 of the output's rms value.
+# error |y - ref| / max(|ref|, delta).  The floor delta keeps an output that
+# cancelled to (nearly) zero from turning the absolute noise of fp32
+# accumulation into an unbounded relative error: the kernels round once, to
+# fp32 (2^-24 relative to the running sum, itself of the size of the output's
+# rms value), per 32-product step, K/32 times per output; eight standard
+# deviations of that random walk may use up the whole tolerance on the floor,
+#     delta = rms(ref) * max(2^-10, 8 * 2^-24 * sqrt(K / 32) / REL_TOL).
 REL_TOL = 2e-3
+
+
+def floor_fraction(K: int) -> float:
+    """delta / rms(ref) for a contraction of length K."""
+    return max(2.0 ** -10, 8.0 * 2.0 ** -24 * (K / 32.0) ** 0.5 / REL_TOL)
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
@@ -21,12 +32,12 @@ def host_bits(t: torch.Tensor) -> np.ndarray:
     return t.detach().cpu().numpy().view(np.uint16)
 
 
-def rel_err(y_bits: np.ndarray, ref_bits: np.ndarray):
+def rel_err(y_bits: np.ndarray, ref_bits: np.ndarray, K: int):
     """(max element-wise relative error with floored denominator, normwise error, #elements on the floor)."""
     y = y_bits.view(np.float16).astype(np.float64).ravel()
     r = ref_bits.view(np.float16).astype(np.float64).ravel()
     rms = np.sqrt(np.mean(r * r)) if r.size else 0.0
-    floor = rms * 2.0 ** -10
+    floor = rms * floor_fraction(K)
     den = np.maximum(np.abs(r), floor)
     den = np.where(den == 0.0, 1.0, den)
     err = np.abs(y - r) / den

@@ -53,7 +53,7 @@ def test_host_side_validation(lib):
     assert d(None, A, A, 16, 128, 3, 128, None) == NULL
     assert d(A, None, A, 16, 128, 3, 128, None) == NULL
     assert d(A, A, None, 16, 128, 3, 128, None) == NULL
-    assert d(A, A, A, 16, 128, 4, 128, None) == BITS
+    assert d(A, A, A, 16, 128, 5, 128, None) == BITS
     assert d(A, A, A, 16, 128, 1, 128, None) == BITS
     assert d(A, A, A, 16, 128, 3, 32, None) == GROUP
     assert d(A, A, A, 16, 192, 3, 64, None) == SHAPE
@@ -89,7 +89,7 @@ def test_host_side_validation(lib):
     assert r(A, None, 16, 128, 3, 1, None) == NULL
     qz = lib.pot_quantize
     assert qz(None, A, A, 16, 128, 3, 128, None) == NULL
-    assert qz(A, A, A, 16, 128, 4, 128, None) == BITS
+    assert qz(A, A, A, 16, 128, 5, 128, None) == BITS
     assert qz(A, A, A, 16, 128, 3, 100, None) == GROUP
     assert qz(A, MIS, A, 16, 128, 3, 128, None) == ALIGN
     assert qz(None, None, None, 0, 128, 3, 128, None) == OK
@@ -97,3 +97,9 @@ def test_host_side_validation(lib):
     assert c(A, 4, 3, None, None) == NULL
     assert c(A, 4, 5, A, None) == BITS
     assert c(A, -1, 3, A, None) == SHAPE
+
+
+def test_driver_entry_points_exist():
+    import importlib
+    entry = importlib.import_module("__graft_entry__")
+    assert callable(entry.build) and callable(entry.smoke)

@@ -107,7 +107,7 @@ def test_config2_gemv_3bit_7b_shapes_full(potq, is_int):
             S, Z = workloads.pot_scales(workloads.seed_of(2, i, 1), N, K, G), None
             got = host_bits(potq.pot_gemv(tiled, dev(S), dev(x[0]), K, bits))
         want = oracle.gemm(packed, S, Z, x, K, bits, G, nthreads=_threads())[0]
-        e, nw, nfloor = rel_err(got, want)
+        e, nw, nfloor = rel_err(got, want, K)
         assert e <= REL_TOL, (name, e, nw, nfloor)
 
 
@@ -121,7 +121,7 @@ def test_config3_llama70b_gemv_full(potq, bits):
         tiled = potq.potq_repack(dev(packed), K, bits)
         got = host_bits(potq.pot_gemv(tiled, dev(S), dev(x[0]), K, bits))
         want = oracle.gemm(packed, S, None, x, K, bits, G, nthreads=_threads())[0]
-        e, nw, nfloor = rel_err(got, want)
+        e, nw, nfloor = rel_err(got, want, K)
         assert e <= REL_TOL, (name, e, nw, nfloor)
 
 
@@ -144,7 +144,7 @@ def test_config4_gemm_3bit_13b_shapes_sampled_rows(potq, M, is_int):
         want = oracle.gemm(packed[rows], S[rows], None if Z is None else Z[rows], X, K, bits, G,
                            nthreads=_threads())
         got = host_bits(Y[:, torch.from_numpy(rows).to("cuda:0")].contiguous())
-        e, nw, nfloor = rel_err(got, want)
+        e, nw, nfloor = rel_err(got, want, K)
         assert e <= REL_TOL, (name, M, e, nw, nfloor)
         assert bool(torch.isfinite(Y).all())
 
@@ -175,5 +175,5 @@ def test_second_workload_llama30b_layer(potq, bits):
         ys = potq.pot_gemv_batch(batch, dev(x[0]), K, bits)
         for i, y in zip(idxs, ys):
             want = oracle.gemm(host[i][0], host[i][1], None, x, K, bits, G, nthreads=_threads())[0]
-            e, nw, nfloor = rel_err(host_bits(y), want)
+            e, nw, nfloor = rel_err(host_bits(y), want, K)
             assert e <= REL_TOL, (layer[i][0], e, nw, nfloor)
