@@ -20,7 +20,7 @@
  *  - Matrices: W is N x K (N output features, K input features, nn.Linear
  *    order).  `scales` (and `zeros`) are N x (K/group) fp16, row-major.  fp16
  *    values are IEEE binary16 stored as 16-bit words.
- *  - Requirements: bits in {2,3}; group in {64,128};
+ *  - Requirements: bits in {2,3,4} (the paper evaluates 2 and 3); group in {64,128};
  *    K a multiple of 128; every pointer 16-byte aligned; the tiled layout also
  *    needs N to be a multiple of 16.  Sizes of zero are valid and do nothing.
  *  - Return value: POTQ_OK or an error code; arguments are validated on the
@@ -56,7 +56,7 @@ extern "C" {
 typedef enum {
     POTQ_OK = 0,
     POTQ_ERR_NULL = 1,       /* a required pointer is NULL */
-    POTQ_ERR_BITS = 2,       /* bits not in {2,3} */
+    POTQ_ERR_BITS = 2,       /* bits not in {2,3,4} */
     POTQ_ERR_GROUP = 3,      /* group size not 64 or 128 */
     POTQ_ERR_SHAPE = 4,      /* negative size, K not a multiple of 128, N not a multiple of 16 (tiled) */
     POTQ_ERR_ALIGN = 5,      /* a pointer is not 16-byte aligned */

@@ -39,7 +39,7 @@ bool misaligned(const void *p, uintptr_t a = 16) { return ((uintptr_t)p & (a - 1
 // Shared checks; returns POTQ_OK when the call should proceed.
 int check_common(int64_t N, int64_t K, int bits, int group, bool fused)
 {
-    if (bits != 2 && bits != 3) return POTQ_ERR_BITS;
+    if (bits < 2 || bits > 4) return POTQ_ERR_BITS;
     (void)fused;
     if (group != 64 && group != 128) return POTQ_ERR_GROUP;
     if (N < 0 || K < 0 || N > kMaxDim || K > kMaxDim || (K % 128) != 0) return POTQ_ERR_SHAPE;
@@ -62,7 +62,7 @@ int dequant_entry(bool is_int, const void *codes, const void *scales, const void
 
 int dequant_batch_entry(bool is_int, const potq_dequant_item *items, int count, int bits, int group, void *stream)
 {
-    if (bits != 2 && bits != 3) return POTQ_ERR_BITS;
+    if (bits < 2 || bits > 4) return POTQ_ERR_BITS;
     if (group != 64 && group != 128) return POTQ_ERR_GROUP;
     if (count < 0 || count > potq::dequant_max_batch()) return POTQ_ERR_SHAPE;
     if (count == 0) return POTQ_OK;
@@ -113,7 +113,7 @@ int gemv_entry(bool is_int, const void *codes, const void *scales, const void *z
 int gemv_batch_entry(bool is_int, const potq_gemv_item *items, int count, const void *x, int64_t K, int bits,
                      int group, int layout, void *stream)
 {
-    if (bits != 2 && bits != 3) return POTQ_ERR_BITS;
+    if (bits < 2 || bits > 4) return POTQ_ERR_BITS;
     if (group != 64 && group != 128) return POTQ_ERR_GROUP;
     if (K < 0 || K > kMaxDim || (K % 128) != 0) return POTQ_ERR_SHAPE;
     if (count < 0 || count > potq::gemv_max_batch()) return POTQ_ERR_SHAPE;
@@ -185,7 +185,7 @@ const char *potq_strerror(int status)
     switch (status) {
     case POTQ_OK: return "ok";
     case POTQ_ERR_NULL: return "a required pointer is NULL";
-    case POTQ_ERR_BITS: return "bits must be 2 or 3";
+    case POTQ_ERR_BITS: return "bits must be 2, 3 or 4";
     case POTQ_ERR_GROUP: return "group size not supported (64 or 128)";
     case POTQ_ERR_SHAPE: return "bad shape (negative, K not a multiple of 128, N not a multiple of 16, or K too large)";
     case POTQ_ERR_ALIGN: return "a pointer is not 16-byte aligned";
@@ -301,7 +301,7 @@ int pot_quantize(const void *W_f16, void *codes_out, void *scales_out, int64_t N
 
 int pot_check_scales(const void *scales, int64_t count, int bits, void *bad_count_dev, void *hip_stream)
 {
-    if (bits != 2 && bits != 3) return POTQ_ERR_BITS;
+    if (bits < 2 || bits > 4) return POTQ_ERR_BITS;
     if (count < 0) return POTQ_ERR_SHAPE;
     if (!bad_count_dev || (count > 0 && !scales)) return POTQ_ERR_NULL;
     if (misaligned(bad_count_dev, 8) || misaligned(scales, 2)) return POTQ_ERR_ALIGN;

@@ -25,7 +25,7 @@ constexpr int kOctetsPerLane = POTQ_DQ_OCTETS;            // U: stores per lane
 constexpr int kDequantBlock = POTQ_DQ_BLOCK;              // threads per workgroup
 constexpr int kOctetsPerWave = kWave * kOctetsPerLane;    // 256 octets = 2048 weights
 
-// 24 (bits=3) or 16 (bits=2) code bits of octet `o`, from aligned 32-bit words.
+// 32 (bits=4), 24 (bits=3) or 16 (bits=2) code bits of octet `o`, from aligned 32-bit words.
 template <int BITS>
 __device__ __forceinline__ uint32_t load_octet_bits(const uint32_t *__restrict__ words, int64_t o)
 {
@@ -34,6 +34,8 @@ __device__ __forceinline__ uint32_t load_octet_bits(const uint32_t *__restrict__
         const uint32_t a = words[byte >> 2];
         const uint32_t b = words[(byte + 2) >> 2];        // word holding the octet's last byte
         return __builtin_amdgcn_alignbyte(b, a, (uint32_t)(byte & 3)) & 0xFFFFFFu;
+    } else if (BITS == 4) {
+        return words[o];
     } else {
         const uint32_t a = words[o >> 1];
         return (a >> (16 * (uint32_t)(o & 1))) & 0xFFFFu;
@@ -68,8 +70,10 @@ __device__ __forceinline__ u32x4 pot_octet(uint32_t f, uint32_t scale_bits)
     for (int m = 0; m < 4; ++m) {
         const uint32_t pair = spread_pair<BITS>(f, 2 * BITS * m);
         // c * (2^10 + 2^(16-BITS)) puts E on bits 10.. and the sign on bit 15; stray copies are masked off
-        const uint32_t t = (BITS == 3) ? (__umul24(pair, 0x2400u) & 0x8C008C00u)
-                                       : (__umul24(pair, 0x4400u) & 0x84008400u);
+        // (with four bits the two copies would overlap, so the sign is moved separately)
+        const uint32_t t = (BITS == 3)   ? (__umul24(pair, 0x2400u) & 0x8C008C00u)
+                           : (BITS == 2) ? (__umul24(pair, 0x4400u) & 0x84008400u)
+                                         : (((pair & 0x00070007u) << 10) | ((pair & 0x00080008u) << 12));
         out[m] = add_u16x2(s2, t);
     }
     return out;
@@ -182,10 +186,12 @@ hipError_t run_dequant(bool is_int, const void *codes, const void *scales, const
                        int64_t N, int64_t K, int bits, int group, hipStream_t stream)
 {
     if (is_int)
-        return bits == 3 ? launch_dequant<3, true>(codes, scales, zeros, out, N, K, group, stream)
-                         : launch_dequant<2, true>(codes, scales, zeros, out, N, K, group, stream);
-    return bits == 3 ? launch_dequant<3, false>(codes, scales, zeros, out, N, K, group, stream)
-                     : launch_dequant<2, false>(codes, scales, zeros, out, N, K, group, stream);
+        return bits == 4   ? launch_dequant<4, true>(codes, scales, zeros, out, N, K, group, stream)
+               : bits == 3 ? launch_dequant<3, true>(codes, scales, zeros, out, N, K, group, stream)
+                           : launch_dequant<2, true>(codes, scales, zeros, out, N, K, group, stream);
+    return bits == 4   ? launch_dequant<4, false>(codes, scales, zeros, out, N, K, group, stream)
+           : bits == 3 ? launch_dequant<3, false>(codes, scales, zeros, out, N, K, group, stream)
+                       : launch_dequant<2, false>(codes, scales, zeros, out, N, K, group, stream);
 }
 
 int dequant_max_batch() { return kMaxBatch; }
@@ -224,10 +230,12 @@ hipError_t run_dequant_batch(bool is_int, int count, const void *const *codes, c
     const int group_shift = (group == 128) ? 7 : 6;
     const dim3 grid((unsigned)blocks), block(kDequantBlock);
     if (is_int) {
-        if (bits == 3) hipLaunchKernelGGL((dequant_batch_kernel<3, true>), grid, block, 0, stream, b, group_shift);
+        if (bits == 4) hipLaunchKernelGGL((dequant_batch_kernel<4, true>), grid, block, 0, stream, b, group_shift);
+        else if (bits == 3) hipLaunchKernelGGL((dequant_batch_kernel<3, true>), grid, block, 0, stream, b, group_shift);
         else hipLaunchKernelGGL((dequant_batch_kernel<2, true>), grid, block, 0, stream, b, group_shift);
     } else {
-        if (bits == 3) hipLaunchKernelGGL((dequant_batch_kernel<3, false>), grid, block, 0, stream, b, group_shift);
+        if (bits == 4) hipLaunchKernelGGL((dequant_batch_kernel<4, false>), grid, block, 0, stream, b, group_shift);
+        else if (bits == 3) hipLaunchKernelGGL((dequant_batch_kernel<3, false>), grid, block, 0, stream, b, group_shift);
         else hipLaunchKernelGGL((dequant_batch_kernel<2, false>), grid, block, 0, stream, b, group_shift);
     }
     return hipGetLastError();

@@ -177,19 +177,11 @@ void gemm_tile16_kernel(
         for (int gi = 0; gi < GC; ++gi) {
             if (g0 + gi >= g_end) break;              // uniform: only the last chunk of a split can be short
             const u32x4 *xb = buf + gi * 16 * MT;
-            PotTable pt[RM];
-            IntTable it[RM];
-            uint32_t sel[RM][8];
+            Decoder<BITS, IS_INT> dec[RM];
 #pragma unroll
             for (int rm = 0; rm < RM; ++rm) {
-                if (IS_INT)
-                    it[rm] = int_table<BITS>(s[gi][rm], z[gi][rm]);
-                else
-                    pt[rm] = pot_table<BITS>(s[gi][rm]);
-                if (BITS == 3)
-                    selectors3(w[gi][rm][0], w[gi][rm][1], w[gi][rm][BITS - 1], sel[rm]);
-                else
-                    selectors2(w[gi][rm][0], w[gi][rm][1], sel[rm]);
+                dec[rm].set_group(s[gi][rm], z[gi][rm]);
+                dec[rm].set_block(w[gi][rm]);
             }
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
@@ -200,13 +192,8 @@ void gemm_tile16_kernel(
 #pragma unroll
                 for (int rm = 0; rm < RM; ++rm) {
                     uint32_t a0, a1, a2, a3;
-                    if (IS_INT) {
-                        int_lookup(it[rm], sel[rm][2 * st], a0, a1);
-                        int_lookup(it[rm], sel[rm][2 * st + 1], a2, a3);
-                    } else {
-                        pot_lookup(pt[rm], sel[rm][2 * st], a0, a1);
-                        pot_lookup(pt[rm], sel[rm][2 * st + 1], a2, a3);
-                    }
+                    dec[rm].get(2 * st, a0, a1);
+                    dec[rm].get(2 * st + 1, a2, a3);
                     const half8_t av = __builtin_bit_cast(half8_t, (u32x4{a0, a1, a2, a3}));
 #pragma unroll
                     for (int c = 0; c < CN; ++c)
@@ -369,10 +356,12 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
                            hipStream_t stream)
 {
     if (is_int) {
-        if (bits == 3) launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        if (bits == 4) launch_gemm<4, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else if (bits == 3) launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else launch_gemm<2, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
-        if (bits == 3) launch_gemm<3, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        if (bits == 4) launch_gemm<4, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else if (bits == 3) launch_gemm<3, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else launch_gemm<2, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     }
     return hipGetLastError();

@@ -24,32 +24,21 @@ __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, u
                                            uint32_t z_hi, bool two_scales, const u32x4 *__restrict__ xg,
                                            float4_t (&acc)[4])
 {
-    PotTable pt;
-    IntTable it;
+    Decoder<BITS, IS_INT> dec;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-        if (b == 0 || (b == 2 && two_scales)) {     // wave-uniform: the second table exists only for group size 64
-            if (IS_INT)
-                it = int_table<BITS>(b ? s_hi : s, b ? z_hi : z);
-            else
-                pt = pot_table<BITS>(b ? s_hi : s);
-        }
-        uint32_t sel[8];
-        if (BITS == 3)
-            selectors3(L[0][b], L[1][b], L[BITS - 1][b], sel);
-        else
-            selectors2(L[0][b], L[1][b], sel);
+        if (b == 0 || (b == 2 && two_scales))       // wave-uniform: the second table exists only for group size 64
+            dec.set_group(b ? s_hi : s, b ? z_hi : z);
+        uint32_t w[BITS];
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) w[j] = L[j][b];
+        dec.set_block(w);
 #pragma unroll
         for (int m = 0; m < 8; m += 2) {
             const u32x4 xv = xg[b * 4 + m / 2];     // columns 32b + 4m .. + 7
             uint32_t e0, o0, e1, o1;
-            if (IS_INT) {
-                int_lookup(it, sel[m], e0, o0);
-                int_lookup(it, sel[m + 1], e1, o1);
-            } else {
-                pot_lookup(pt, sel[m], e0, o0);
-                pot_lookup(pt, sel[m + 1], e1, o1);
-            }
+            dec.get(m, e0, o0);
+            dec.get(m + 1, e1, o1);
             const half8_t av = __builtin_bit_cast(half8_t, (u32x4{e0, o0, e1, o1}));
             acc[m / 2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, __builtin_bit_cast(half8_t, xv), acc[m / 2], 0, 0, 0);
         }
@@ -333,10 +322,12 @@ hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *code
     if (blocks == 0) return hipSuccess;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     if (is_int) {
-        if (bits == 3) launch_gemv_batch<3, true>(b, (unsigned)blocks, x, K, group, split, stream);
+        if (bits == 4) launch_gemv_batch<4, true>(b, (unsigned)blocks, x, K, group, split, stream);
+        else if (bits == 3) launch_gemv_batch<3, true>(b, (unsigned)blocks, x, K, group, split, stream);
         else launch_gemv_batch<2, true>(b, (unsigned)blocks, x, K, group, split, stream);
     } else {
-        if (bits == 3) launch_gemv_batch<3, false>(b, (unsigned)blocks, x, K, group, split, stream);
+        if (bits == 4) launch_gemv_batch<4, false>(b, (unsigned)blocks, x, K, group, split, stream);
+        else if (bits == 3) launch_gemv_batch<3, false>(b, (unsigned)blocks, x, K, group, split, stream);
         else launch_gemv_batch<2, false>(b, (unsigned)blocks, x, K, group, split, stream);
     }
     return hipGetLastError();
@@ -346,10 +337,12 @@ hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, c
                            void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream)
 {
     if (is_int) {
-        if (bits == 3) launch_gemv<3, true>(codes, scales, zeros, x, y, N, K, group, stream);
+        if (bits == 4) launch_gemv<4, true>(codes, scales, zeros, x, y, N, K, group, stream);
+        else if (bits == 3) launch_gemv<3, true>(codes, scales, zeros, x, y, N, K, group, stream);
         else launch_gemv<2, true>(codes, scales, zeros, x, y, N, K, group, stream);
     } else {
-        if (bits == 3) launch_gemv<3, false>(codes, scales, zeros, x, y, N, K, group, stream);
+        if (bits == 4) launch_gemv<4, false>(codes, scales, zeros, x, y, N, K, group, stream);
+        else if (bits == 3) launch_gemv<3, false>(codes, scales, zeros, x, y, N, K, group, stream);
         else launch_gemv<2, false>(codes, scales, zeros, x, y, N, K, group, stream);
     }
     return hipGetLastError();

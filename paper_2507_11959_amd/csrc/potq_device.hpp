@@ -58,6 +58,8 @@ __device__ __forceinline__ uint32_t as_u32(half2_t v)
 //     selector 7        : exponent = (w1 >> (8j+6)) & 3, sign = (w2 >> (8j+7)) & 1
 //   bits = 2, words (w0, w1):
 //     selector m = 0..7 : byte j holds code = (w[m/4] >> (8j + 2(m%4))) & 3
+//   bits = 4, words (w0, w1, w2, w3):
+//     selector m = 0..7 : byte j holds code = (w[m/2] >> (8j + 4(m%2))) & 15
 // Selector m, byte j is column 4m + p(j) of the block, p = (0, 2, 1, 3): bytes
 // 0 and 2 are an adjacent column pair, bytes 1 and 3 the next pair.
 // ---------------------------------------------------------------------------
@@ -175,5 +177,116 @@ __device__ __forceinline__ void int_lookup(const IntTable &t, uint32_t sel, uint
     even = byte_perm(rh, rl, 0x06020400u);   // [rl.b0, rh.b0, rl.b2, rh.b2]
     odd = byte_perm(rh, rl, 0x07030501u);    // [rl.b1, rh.b1, rl.b3, rh.b3]
 }
+
+// The eight selectors of a 4-bit block, as whole nibbles (uniform baseline) ...
+__device__ __forceinline__ void selectors4(const uint32_t (&w)[4], uint32_t sel[8])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        sel[2 * i] = w[i] & 0x0F0F0F0Fu;
+        sel[2 * i + 1] = (w[i] >> 4) & 0x0F0F0F0Fu;
+    }
+}
+
+// ... and split into exponent selectors and sign masks (PoT): the exponent indexes the
+// eight-entry byte table, the sign lands on bit 7 of each byte, where it is XOR-ed into
+// the looked-up high byte (adding 0x8000 to a 16-bit word is flipping its top bit).
+__device__ __forceinline__ void selectors4_pot(const uint32_t (&w)[4], uint32_t sel[8], uint32_t sgn[8])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        sel[2 * i] = w[i] & 0x07070707u;
+        sel[2 * i + 1] = (w[i] >> 4) & 0x07070707u;
+        sgn[2 * i] = (w[i] << 4) & 0x80808080u;
+        sgn[2 * i + 1] = w[i] & 0x80808080u;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Decoder: everything a fused kernel needs to turn the codes of one row of one
+// 32-column block into fp16 pairs, for every (bits, PoT / uniform) combination.
+//   set_group(scale, zero)  once per scale group: builds the group's table
+//   set_block(w)            once per 32-column block: builds the eight selectors
+//   get(m, even, odd)       selector m -> pairs (column 4m, 4m+1) and (4m+2, 4m+3)
+// ---------------------------------------------------------------------------
+template <int BITS, bool IS_INT>
+struct Decoder;
+
+template <int BITS>
+struct Decoder<BITS, false> {
+    static_assert(BITS == 2 || BITS == 3, "4-bit PoT has its own specialisation");
+    PotTable t;
+    uint32_t sel[8];
+    __device__ __forceinline__ void set_group(uint32_t s, uint32_t) { t = pot_table<BITS>(s); }
+    __device__ __forceinline__ void set_block(const uint32_t (&w)[BITS])
+    {
+        if (BITS == 3)
+            selectors3(w[0], w[1], w[BITS - 1], sel);
+        else
+            selectors2(w[0], w[1], sel);
+    }
+    __device__ __forceinline__ void get(int m, uint32_t &even, uint32_t &odd) const { pot_lookup(t, sel[m], even, odd); }
+};
+
+template <>
+struct Decoder<4, false> {
+    PotTable t;          // high bytes for E = 0..3 / 4..7 of the positive sign
+    uint32_t sel[8], sgn[8];
+    __device__ __forceinline__ void set_group(uint32_t s, uint32_t)
+    {
+        const uint32_t rep = ((s >> 8) & 0xFFu) * 0x01010101u;
+        t.lo = add_bytes(rep, 0x0C080400u);
+        t.hi = add_bytes(rep, 0x1C181410u);
+        const uint32_t sl = s & 0xFFu;
+        t.low2 = sl | (sl << 16);
+    }
+    __device__ __forceinline__ void set_block(const uint32_t (&w)[4]) { selectors4_pot(w, sel, sgn); }
+    __device__ __forceinline__ void get(int m, uint32_t &even, uint32_t &odd) const
+    {
+        const uint32_t r = byte_perm(t.hi, t.lo, sel[m]) ^ sgn[m];
+        even = byte_perm(r, t.low2, 0x06000400u);
+        odd = (r & 0xFF00FF00u) | t.low2;
+    }
+};
+
+template <int BITS>
+struct Decoder<BITS, true> {
+    static_assert(BITS == 2 || BITS == 3, "4-bit uniform has its own specialisation");
+    IntTable t;
+    uint32_t sel[8];
+    __device__ __forceinline__ void set_group(uint32_t s, uint32_t z) { t = int_table<BITS>(s, z); }
+    __device__ __forceinline__ void set_block(const uint32_t (&w)[BITS])
+    {
+        if (BITS == 3)
+            selectors3(w[0], w[1], w[BITS - 1], sel);
+        else
+            selectors2(w[0], w[1], sel);
+    }
+    __device__ __forceinline__ void get(int m, uint32_t &even, uint32_t &odd) const { int_lookup(t, sel[m], even, odd); }
+};
+
+// Sixteen levels do not fit the byte-permute tables: the 4-bit uniform path computes
+// (q + Z) * S with packed fp16 arithmetic instead -- q is OR-ed into the mantissa of 1024.0,
+// (1024 + q) + (Z - 1024) is exact, the product is rounded once (Sec. 4.1 Eq. (9)).
+template <>
+struct Decoder<4, true> {
+    half2_t zm1024, s2;
+    uint32_t sel[8];
+    __device__ __forceinline__ void set_group(uint32_t s, uint32_t z)
+    {
+        const _Float16 S = __builtin_bit_cast(_Float16, (uint16_t)s);
+        const _Float16 Z = __builtin_bit_cast(_Float16, (uint16_t)z) - (_Float16)1024.0f;
+        s2 = half2_t{S, S};
+        zm1024 = half2_t{Z, Z};
+    }
+    __device__ __forceinline__ void set_block(const uint32_t (&w)[4]) { selectors4(w, sel); }
+    __device__ __forceinline__ void get(int m, uint32_t &even, uint32_t &odd) const
+    {
+        const uint32_t qe = (sel[m] & 0x00FF00FFu) | 0x64006400u;          // bytes 0 and 2
+        const uint32_t qo = ((sel[m] >> 8) & 0x00FF00FFu) | 0x64006400u;   // bytes 1 and 3
+        even = as_u32((as_half2(qe) + zm1024) * s2);
+        odd = as_u32((as_half2(qo) + zm1024) * s2);
+    }
+};
 
 }  // namespace potq

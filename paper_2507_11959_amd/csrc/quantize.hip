@@ -22,17 +22,10 @@ constexpr int kCandidates = 200;
 constexpr int kGroupsPerBlock = 2;
 constexpr int kQuantThreads = 448;       // 7 wavefronts: 400 (group, multiplier) pairs + the tail
 
-template <int BITS>
-__device__ __forceinline__ int pot_exponent(float a, float t1, float t2, float t3)
-{
-    // round(log2(a / s)) clamped to [0, qmax], through its decision thresholds s * 2^(e - 1/2)
-    int E = a >= t1 ? 1 : 0;
-    if (BITS == 3) {
-        E = a >= t2 ? 2 : E;
-        E = a >= t3 ? 3 : E;
-    }
-    return E;
-}
+// (float)2^(e - 1/2), e = 1..7: the decision thresholds of round(log2(.)), relative to the scale
+__device__ __constant__ const float kRoundThreshold[8] = {
+    0.0f, 1.41421356237309504880f, 2.82842712474619009760f, 5.65685424949238019521f,
+    11.3137084989847603904f, 22.6274169979695207808f, 45.2548339959390415616f, 90.5096679918780831232f};
 
 template <int BITS>
 __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
@@ -40,7 +33,6 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     int64_t total_groups, int groups_per_row, int group)
 {
     constexpr int qmax = (1 << (BITS - 1)) - 1;
-    constexpr float c1 = 1.41421356237309504880f, c2 = 2.82842712474619009760f, c3 = 5.65685424949238019521f;
     __shared__ float w[kGroupsPerBlock][128];
     __shared__ float qs[kGroupsPerBlock][kCandidates];
     __shared__ float wmax_s[kGroupsPerBlock];
@@ -49,16 +41,14 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
 
     const int tid = threadIdx.x;
     const int64_t g0 = (int64_t)blockIdx.x * kGroupsPerBlock;
+    (void)groups_per_row;
 
     // stage the weights (binary16 -> binary32 is exact) and find max |w| per group
     if (tid < kGroupsPerBlock * 128) {
         const int gi = tid >> 7, k = tid & 127;
         float v = 0.f;
-        if (g0 + gi < total_groups && k < group) {
-            const int64_t gg = g0 + gi;
-            const int64_t n = gg / groups_per_row, g = gg % groups_per_row;
-            v = (float)__builtin_bit_cast(_Float16, W[(n * groups_per_row + g) * group + k]);
-        }
+        if (g0 + gi < total_groups && k < group)
+            v = (float)__builtin_bit_cast(_Float16, W[(g0 + gi) * group + k]);
         w[gi][k] = v;
     }
     if (tid < kGroupsPerBlock * 4 * BITS) packed[tid / (4 * BITS)][tid % (4 * BITS)] = 0u;
@@ -76,17 +66,19 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
         const int gi = tid / kCandidates, i = tid % kCandidates + 1;
         const float s0 = __fdiv_rn(wmax_s[gi], (float)((1 << qmax) - 1));
         const float s = s0 * ((float)i * 0.01f);
-        const float t1 = s * c1, t2 = s * c2, t3 = s * c3;
-        const float s2 = s * 2.f, s4 = s * 4.f, s8 = s * 8.f;   // exact
+        float thr[qmax + 1], mag_of[qmax + 1];
+#pragma unroll
+        for (int e = 0; e <= qmax; ++e) {
+            thr[e] = s * kRoundThreshold[e];            // thr[0] is not used
+            mag_of[e] = s * (float)(1 << e);            // exact
+        }
         float q = 0.f;
         for (int k = 0; k < group; ++k) {
             const float x = w[gi][k];
             const float a = fabsf(x);
-            float mag = a >= t1 ? s2 : s;
-            if (BITS == 3) {
-                mag = a >= t2 ? s4 : mag;
-                mag = a >= t3 ? s8 : mag;
-            }
+            float mag = mag_of[0];
+#pragma unroll
+            for (int e = 1; e <= qmax; ++e) mag = a >= thr[e] ? mag_of[e] : mag;
             const float d = x - (x < 0.f ? -mag : mag);
             q = __builtin_fmaf(d, d, q);
         }
@@ -126,7 +118,10 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
             const float s = s0 * ((float)best_s[gi] * 0.01f);
             const float x = w[gi][k];
             int E = 0;
-            if (s0 > 0.f) E = pot_exponent<BITS>(fabsf(x), s * c1, s * c2, s * c3);
+            if (s0 > 0.f) {
+#pragma unroll
+                for (int e = 1; e <= qmax; ++e) E = fabsf(x) >= s * kRoundThreshold[e] ? e : E;
+            }
             const uint32_t code = (uint32_t)E | (x < 0.f ? (1u << (BITS - 1)) : 0u);
             const int pos = BITS * k, idx = pos >> 5, sh = pos & 31;
             atomicOr(&packed[gi][idx], code << sh);
@@ -152,7 +147,10 @@ hipError_t run_quantize(const void *W, void *codes, void *scales, int64_t N, int
 {
     const int64_t total_groups = N * (K / group);
     const unsigned blocks = (unsigned)((total_groups + kGroupsPerBlock - 1) / kGroupsPerBlock);
-    if (bits == 3)
+    if (bits == 4)
+        hipLaunchKernelGGL((quantize_kernel<4>), dim3(blocks), dim3(kQuantThreads), 0, stream, (const uint16_t *)W,
+                           (uint32_t *)codes, (uint16_t *)scales, total_groups, (int)(K / group), group);
+    else if (bits == 3)
         hipLaunchKernelGGL((quantize_kernel<3>), dim3(blocks), dim3(kQuantThreads), 0, stream, (const uint16_t *)W,
                            (uint32_t *)codes, (uint16_t *)scales, total_groups, (int)(K / group), group);
     else

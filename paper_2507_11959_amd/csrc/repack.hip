@@ -44,6 +44,7 @@ __device__ __forceinline__ uint32_t tile_get(const uint32_t w[BITS], int m, int 
         const uint32_t s = (w[2] >> (8 * j + m)) & 1u;      // m = 6 -> bit 6, m = 7 -> bit 7
         return e | (s << 2);
     }
+    if (BITS == 4) return (w[m >> 1] >> (8 * j + 4 * (m & 1))) & 15u;
     return (w[m >> 2] >> (8 * j + 2 * (m & 3))) & 3u;
 }
 
@@ -57,6 +58,8 @@ __device__ __forceinline__ void tile_put(uint32_t w[BITS], int m, int j, uint32_
             w[m - 6] |= (c & 3u) << (8 * j + 6);
             w[2] |= (c >> 2) << (8 * j + m);
         }
+    } else if (BITS == 4) {
+        w[m >> 1] |= c << (8 * j + 4 * (m & 1));
     } else {
         w[m >> 2] |= c << (8 * j + 2 * (m & 3));
     }
@@ -110,7 +113,12 @@ hipError_t run_repack(const void *src, void *dst, int64_t N, int64_t K, int bits
     const unsigned blocks = (unsigned)((threads + 255) / 256);
     const uint32_t *s = (const uint32_t *)src;
     uint32_t *d = (uint32_t *)dst;
-    if (bits == 3) {
+    if (bits == 4) {
+        if (to_tiled)
+            hipLaunchKernelGGL((repack_kernel<4, true>), dim3(blocks), dim3(256), 0, stream, s, d, N, K);
+        else
+            hipLaunchKernelGGL((repack_kernel<4, false>), dim3(blocks), dim3(256), 0, stream, s, d, N, K);
+    } else if (bits == 3) {
         if (to_tiled)
             hipLaunchKernelGGL((repack_kernel<3, true>), dim3(blocks), dim3(256), 0, stream, s, d, N, K);
         else

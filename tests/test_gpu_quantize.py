@@ -17,7 +17,7 @@ def potq():
     return p
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("group", [64, 128])
 @pytest.mark.parametrize("N,K", [(1, 128), (7, 640), (24, 1024), (3, 11008)])
 def test_quantize_bit_exact(potq, bits, group, N, K):
@@ -33,7 +33,7 @@ def test_quantize_bit_exact(potq, bits, group, N, K):
     assert potq.pot_check_scales(scales, bits) == 0
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_quantize_then_dequant_round_trip(potq, bits):
     N, K, G = 256, 4096, 128
     W = workloads.weights_f16(77 + bits, N, K)

@@ -29,7 +29,7 @@ def _layer(potq, bits, K=1024):
     return mats
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_non_default_stream(potq, bits):
     K = 1024
     mats = _layer(potq, bits, K)
@@ -45,7 +45,7 @@ def test_non_default_stream(potq, bits):
         assert torch.equal(y, potq.pot_gemv(m["tiled"], m["s"], x, K, bits))
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_graph_capture_and_replay(potq, bits):
     K, M = 1024, 24
     mats = _layer(potq, bits, K)

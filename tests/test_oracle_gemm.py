@@ -12,7 +12,7 @@ def _f16(bits_arr):
     return np.asarray(bits_arr, dtype=np.uint16).view(np.float16)
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_gemv_one_hot_returns_columns_exactly(bits):
     N, K, G = 20, 384, 128
     packed, scales = workloads.pot_matrix(2, 0, N, K, bits, G)
@@ -32,7 +32,7 @@ def test_gemv_all_ones_zero_codes_is_group_sum_of_scales():
     assert np.all(_f16(y).astype(np.float64) == G * scales.astype(np.float64).sum(axis=1))
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_gemv_sign_flip_negates(bits):
     N, K, G = 12, 256, 128
     packed, scales = workloads.pot_matrix(2, 1, N, K, bits, G)
@@ -64,7 +64,7 @@ def test_gemm_vs_numpy_float64_matmul(bits, M):
     assert np.array_equal(oracle.gemm(packed, scales, None, X, K, bits, G, nthreads=3), Y)
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_int_gemm_vs_numpy(bits):
     N, K, G, M = 24, 512, 128, 3
     packed, S, Z = workloads.int_matrix(4, 1, N, K, bits, G)

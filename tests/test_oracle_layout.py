@@ -21,7 +21,7 @@ def test_pack_unpack_roundtrip_and_numpy_packer(bits):
     assert np.array_equal(ref.unpack(p, K, bits), codes)
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_walking_one_bit_positions(bits):
     # a single code with value v at position k sets exactly stream bits [b*k, b*k+b) (little-endian)
     K = 64
@@ -59,7 +59,7 @@ def test_dequant_index_sensitive_matrix(bits, group):
     assert np.array_equal(out, want)
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_dequant_vs_numpy_reference_on_workload_inputs(bits):
     N, K, G = 48, 1024, 128
     packed, scales = workloads.pot_matrix(0, 0, N, K, bits, G)
@@ -78,7 +78,7 @@ def test_dequant_vs_numpy_reference_on_workload_inputs(bits):
     assert np.array_equal(a, oracle.pot_dequant(packed, scales, K, bits, G, nthreads=4))
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_int_dequant_vs_numpy_reference(bits):
     N, K, G = 40, 768, 128
     packed, S, Z = workloads.int_matrix(1, 0, N, K, bits, G)

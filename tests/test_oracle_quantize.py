@@ -48,7 +48,7 @@ def test_two_level_group_is_reproduced_exactly():
     assert np.all(err <= err_naive * (1 + 1e-3))
 
 
-@pytest.mark.parametrize("bits,group", [(2, 128), (3, 128), (3, 64)])
+@pytest.mark.parametrize("bits,group", [(2, 128), (3, 128), (3, 64), (4, 128)])
 def test_against_the_literal_formula_in_float64(bits, group):
     qmax = 2 ** (bits - 1) - 1
     N, K = 6, 512
