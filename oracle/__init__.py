@@ -72,6 +72,12 @@ def _L():
         lib.orc_pot_quantize.restype = None
         lib.orc_pot_quantize.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64,
                                          c.c_int, c.c_int, c.c_int]
+        lib.orc_fakequant_forward.restype = None
+        lib.orc_fakequant_forward.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64,
+                                              c.c_int, c.c_int, c.c_int]
+        lib.orc_fakequant_backward.restype = None
+        lib.orc_fakequant_backward.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64,
+                                               c.c_int64, c.c_int, c.c_int, c.c_int]
         lib.orc_max_threads.restype = c.c_int
         lib.orc_max_threads.argtypes = []
         _lib = lib
@@ -220,3 +226,35 @@ def pot_quantize(W, bits: int, group: int, nthreads: int = 1, want_index: bool =
     idx = np.empty((N, K // group), dtype=np.int32) if want_index else None
     _L().orc_pot_quantize(_p(W), _p(codes), _p(scales), _p(idx) if want_index else None, N, K, bits, group, nthreads)
     return (codes, scales, idx) if want_index else (codes, scales)
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.float32, a.dtype
+    return a
+
+
+def fakequant_forward(W, S, Gamma, bits: int, group: int, nthreads: int = 1) -> np.ndarray:
+    """Step 2 forward (Sec. 3.3): W (N, K) fp16, S (N, K/group) fp16, Gamma (N, K/group) float32
+    -> reconstructed weights (N, K) as uint16 bit patterns of fp16."""
+    W = _u16(W)
+    S = _u16(S)
+    Gamma = _f32(Gamma)
+    N, K = W.shape
+    assert K % group == 0 and S.shape == (N, K // group) and Gamma.shape == S.shape
+    out = np.empty((N, K), dtype=np.uint16)
+    _L().orc_fakequant_forward(_p(W), _p(S), _p(Gamma), _p(out), N, K, bits, group, nthreads)
+    return out
+
+
+def fakequant_backward(W, S, Gamma, dWq, bits: int, group: int, nthreads: int = 1) -> np.ndarray:
+    """Step 2 backward (straight-through estimator): dWq (N, K) fp16 -> dL/dGamma (N, K/group) float32."""
+    W = _u16(W)
+    S = _u16(S)
+    Gamma = _f32(Gamma)
+    dWq = _u16(dWq)
+    N, K = W.shape
+    assert K % group == 0 and S.shape == (N, K // group) and Gamma.shape == S.shape and dWq.shape == W.shape
+    out = np.empty((N, K // group), dtype=np.float32)
+    _L().orc_fakequant_backward(_p(W), _p(S), _p(Gamma), _p(dWq), _p(out), N, K, bits, group, nthreads)
+    return out

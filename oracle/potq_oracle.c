@@ -386,3 +386,93 @@ void orc_pot_quantize(const uint16_t *W, uint8_t *codes, uint16_t *scales, int32
         free(w);
     }
 }
+
+/* --------------------------- Step 2 fake-quantisation op (Sec. 3.3, Alg. 2) -- */
+
+/*
+ * The weight path of one fine-tuning iteration, Sec. 3.3: with the learnable
+ * residual Gamma (one binary32 per group) the scale becomes
+ *     S^ = S * (1 + Gamma)                                   (refined scale)
+ *     E_k = clamp(round(log2(|w_k| / S^)), 0, qmax)           (exponent under S^)
+ *     w~_k = S^ * sign(w_k) * 2^E_k                           (reconstruction)
+ * and the gradient of a loss L with respect to Gamma follows from the
+ * straight-through estimator: round() is differentiated as the identity, so
+ * inside the clamp dE/dS^ = -1 / (S^ ln 2) and the two terms of
+ * dw~/dS^ = P 2^E + S^ P 2^E ln2 dE/dS^ cancel, while where the clamp is active
+ * (round(log2(|w|/S^)) < 0 or > qmax) dE/dS^ = 0 and dw~/dS^ = P 2^E.  Hence
+ *     dL/dGamma_g = S_g * sum_{k in g, clamp active at k} (dL/dw~_k) * sign(w_k) * 2^E_k .
+ * (The paper states the estimator for round() only; the clamp is differentiated
+ * as it stands, derivative 1 on the closed interval [0, qmax] and 0 outside.)
+ *
+ * Arithmetic, fixed as for the scale search so that the integer decisions can be
+ * reproduced bit for bit: binary32, one rounding per operation, no contraction;
+ * S^ = S * (1.0f + Gamma); round(log2(.)) through its thresholds S^ * (float)2^(e-1/2)
+ * (a tie rounds up); below-range means |w| < S^ * (float)2^(-1/2), above-range
+ * |w| >= S^ * (float)2^(qmax+1/2); |w| = 0 is below range, sign(0) = +.
+ * The forward result S^ * 2^E is exact in binary32 and is rounded once to
+ * binary16.  The backward sum is taken in binary64 (k ascending) and rounded
+ * once to binary32; the incoming gradient is binary16.
+ */
+static const float k_inv_sqrt2 = 0.70710678118654752440f;
+
+static int fq_exponent(float a, float shat, int qmax, int *clamped)
+{
+    int E = 0;
+    for (int e = 1; e <= qmax; ++e)
+        if (a >= shat * k_round_thresholds[e]) E = e;
+    const float top = shat * (k_round_thresholds[qmax] * 2.0f);   /* (float)2^(qmax+1/2): doubling is exact */
+    *clamped = (a < shat * k_inv_sqrt2) || (a >= top);
+    return E;
+}
+
+void orc_fakequant_forward(const uint16_t *W, const uint16_t *S, const float *Gamma, uint16_t *Wq,
+                           int64_t N, int64_t K, int bits, int group, int nthreads)
+{
+    const int qmax = (1 << (bits - 1)) - 1;
+    const int64_t ngroups = K / group;
+    (void)nthreads;
+#if defined(_OPENMP)
+#pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t g = 0; g < ngroups; ++g) {
+            const float s = (float)orc_half_to_double(S[n * ngroups + g]);
+            const float shat = s * (1.0f + Gamma[n * ngroups + g]);
+            for (int k = 0; k < group; ++k) {
+                const int64_t at = n * K + g * group + k;
+                const float w = (float)orc_half_to_double(W[at]);
+                int clamped;
+                const int E = fq_exponent(fabsf(w), shat, qmax, &clamped);
+                const float mag = ldexpf(shat, E);
+                Wq[at] = orc_double_to_half((double)(w < 0.0f ? -mag : mag));
+            }
+        }
+}
+
+void orc_fakequant_backward(const uint16_t *W, const uint16_t *S, const float *Gamma, const uint16_t *dWq,
+                            float *dGamma, int64_t N, int64_t K, int bits, int group, int nthreads)
+{
+    const int qmax = (1 << (bits - 1)) - 1;
+    const int64_t ngroups = K / group;
+    (void)nthreads;
+#if defined(_OPENMP)
+#pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t g = 0; g < ngroups; ++g) {
+            const float s = (float)orc_half_to_double(S[n * ngroups + g]);
+            const float shat = s * (1.0f + Gamma[n * ngroups + g]);
+            double sum = 0.0;
+            for (int k = 0; k < group; ++k) {
+                const int64_t at = n * K + g * group + k;
+                const float w = (float)orc_half_to_double(W[at]);
+                int clamped;
+                const int E = fq_exponent(fabsf(w), shat, qmax, &clamped);
+                if (clamped) {
+                    const double p = ldexp(1.0, E);
+                    sum += orc_half_to_double(dWq[at]) * (w < 0.0f ? -p : p);
+                }
+            }
+            dGamma[n * ngroups + g] = (float)((double)s * sum);
+        }
+}
