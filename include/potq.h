@@ -226,6 +226,42 @@ int pot_quantize(const void *W_f16, void *codes_out, void *scales_out,
                  int64_t N, int64_t K, int bits, int group, void *hip_stream);
 
 /*
+ * pot_fakequant_forward / pot_fakequant_backward -- the weight path of one
+ * iteration of Step 2, the data-dependent fine-tuning of the scales (Sec. 3.3,
+ * Algorithm 2).  With the learnable residual Gamma (one value per group):
+ *     S^   = S * (1 + Gamma)                                  refined scale
+ *     E_k  = clamp(round(log2(|w_k| / S^)), 0, qmax)           exponent under S^
+ *     w~_k = S^ * sign(w_k) * 2^E_k                            forward result
+ * and, by the straight-through estimator (round() differentiated as the
+ * identity, the clamp as it stands: derivative 1 on [0, qmax], 0 outside),
+ *     dL/dGamma_g = S_g * sum over k in g with round(log2(|w_k|/S^)) outside [0, qmax]
+ *                         of (dL/dw~_k) * sign(w_k) * 2^E_k
+ * (inside the clamp's range the two terms of dw~/dS^ cancel).  The regulariser
+ * (lambda/2)|Gamma|^2 and the update of Gamma are the caller's optimiser's.
+ * Arithmetic as for pot_quantize: binary32, one rounding per operation, no
+ * contraction; S^ = S * (1.0f + Gamma); E = number of e in 1..qmax with
+ * |w| >= S^ * (float)2^(e-1/2); the clamp is active when |w| < S^ * (float)2^(-1/2)
+ * or |w| >= S^ * (float)2^(qmax+1/2); |w| = 0 is below range with sign +.
+ * Forward rounds the exact S^ * 2^E once to fp16.  Backward adds the (exact)
+ * products in binary32, eight per lane in ascending k and then pairwise across
+ * the lanes of a group, multiplies by S once; the order is fixed, results are
+ * reproducible.  Gamma <= -1 (S^ <= 0) is outside the method; the thresholds
+ * are then non-positive and the formulas above are applied as they stand.
+ *   W_f16     in   N x K fp16 row-major, the original weights
+ *   S_f16     in   N x (K/group) fp16, the Step 1 scales
+ *   Gamma_f32 in   N x (K/group) binary32
+ *   Wq_f16    out  N x K fp16                      (forward)
+ *   dWq_f16   in   N x K fp16, dL/dw~              (backward)
+ *   dGamma_f32 out N x (K/group) binary32          (backward)
+ * W, Wq, dWq 16-byte aligned; N = 0 or K = 0 is valid and does nothing.
+ */
+int pot_fakequant_forward(const void *W_f16, const void *S_f16, const void *Gamma_f32, void *Wq_f16,
+                          int64_t N, int64_t K, int bits, int group, void *hip_stream);
+
+int pot_fakequant_backward(const void *W_f16, const void *S_f16, const void *Gamma_f32, const void *dWq_f16,
+                           void *dGamma_f32, int64_t N, int64_t K, int bits, int group, void *hip_stream);
+
+/*
  * pot_check_scales -- count the scales outside the domain on which the
  * integer-add recipe equals the definition (not positive, subnormal or zero,
  * exponent field above 30 - q_max, infinity, NaN).  The count is written, as

@@ -46,6 +46,8 @@ EXPORTS = {
     "int_gemm": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
     "pot_check_scales": (_int, [_vp, _i64, _int, _vp, _vp]),
     "pot_quantize": (_int, [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]),
+    "pot_fakequant_forward": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _vp]),
+    "pot_fakequant_backward": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _vp]),
 }
 for _name, (_res, _args) in EXPORTS.items():
     _f = getattr(_lib, _name)
@@ -275,6 +277,34 @@ def pot_quantize(W, bits: int, group: int = 128):
     _ok(_lib.pot_quantize(_dev(W, torch.float16, "W"), _dev(codes, torch.uint8, "codes"),
                           _dev(scales, torch.float16, "scales"), N, K, bits, group, _stream()))
     return codes, scales
+
+
+def pot_fakequant_forward(W, S, Gamma, bits: int, group: int = 128):
+    """Step 2 forward: W fp16 (N, K), S fp16 (N, K/group), Gamma float32 (N, K/group) -> w~ fp16 (N, K)."""
+    if W.dim() != 2:
+        raise ValueError("W must be (N, K)")
+    N, K = W.shape
+    if tuple(S.shape) != (N, K // group) or tuple(Gamma.shape) != tuple(S.shape):
+        raise ValueError("S and Gamma must be (N, K/group)")
+    Wq = torch.empty_like(W)
+    _ok(_lib.pot_fakequant_forward(_dev(W, torch.float16, "W"), _dev(S, torch.float16, "S"),
+                                   _dev(Gamma, torch.float32, "Gamma"), _dev(Wq, torch.float16, "Wq"),
+                                   N, K, bits, group, _stream()))
+    return Wq
+
+
+def pot_fakequant_backward(W, S, Gamma, dWq, bits: int, group: int = 128):
+    """Step 2 backward (straight-through estimator): dWq fp16 (N, K) -> dL/dGamma float32 (N, K/group)."""
+    if W.dim() != 2 or tuple(dWq.shape) != tuple(W.shape):
+        raise ValueError("W and dWq must be (N, K)")
+    N, K = W.shape
+    if tuple(S.shape) != (N, K // group) or tuple(Gamma.shape) != tuple(S.shape):
+        raise ValueError("S and Gamma must be (N, K/group)")
+    dGamma = torch.empty_like(Gamma)
+    _ok(_lib.pot_fakequant_backward(_dev(W, torch.float16, "W"), _dev(S, torch.float16, "S"),
+                                    _dev(Gamma, torch.float32, "Gamma"), _dev(dWq, torch.float16, "dWq"),
+                                    _dev(dGamma, torch.float32, "dGamma"), N, K, bits, group, _stream()))
+    return dGamma
 
 
 def pot_check_scales(scales, bits: int) -> int:

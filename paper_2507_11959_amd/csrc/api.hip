@@ -26,6 +26,10 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, void *ws, size_t ws_bytes,
                            hipStream_t stream);
 size_t gemm_workspace_bytes(int64_t M, int64_t N);
+hipError_t run_fakequant_forward(const void *W, const void *S, const void *Gamma, void *Wq, int64_t N, int64_t K,
+                                 int bits, int group, hipStream_t stream);
+hipError_t run_fakequant_backward(const void *W, const void *S, const void *Gamma, const void *dWq, void *dGamma,
+                                  int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 hipError_t run_quantize(const void *W, void *codes, void *scales, int64_t N, int64_t K, int bits, int group,
                         hipStream_t stream);
 }  // namespace potq
@@ -297,6 +301,33 @@ int pot_quantize(const void *W_f16, void *codes_out, void *scales_out, int64_t N
     if (!W_f16 || !codes_out || !scales_out) return POTQ_ERR_NULL;
     if (misaligned(W_f16) || misaligned(codes_out) || misaligned(scales_out, 2)) return POTQ_ERR_ALIGN;
     return finish(potq::run_quantize(W_f16, codes_out, scales_out, N, K, bits, group, (hipStream_t)hip_stream));
+}
+
+int pot_fakequant_forward(const void *W_f16, const void *S_f16, const void *Gamma_f32, void *Wq_f16, int64_t N,
+                          int64_t K, int bits, int group, void *hip_stream)
+{
+    const int st = check_common(N, K, bits, group, false);
+    if (st != POTQ_OK) return st;
+    if (N == 0 || K == 0) return POTQ_OK;
+    if (!W_f16 || !S_f16 || !Gamma_f32 || !Wq_f16) return POTQ_ERR_NULL;
+    if (misaligned(W_f16) || misaligned(Wq_f16) || misaligned(S_f16, 2) || misaligned(Gamma_f32, 4))
+        return POTQ_ERR_ALIGN;
+    return finish(potq::run_fakequant_forward(W_f16, S_f16, Gamma_f32, Wq_f16, N, K, bits, group,
+                                              (hipStream_t)hip_stream));
+}
+
+int pot_fakequant_backward(const void *W_f16, const void *S_f16, const void *Gamma_f32, const void *dWq_f16,
+                           void *dGamma_f32, int64_t N, int64_t K, int bits, int group, void *hip_stream)
+{
+    const int st = check_common(N, K, bits, group, false);
+    if (st != POTQ_OK) return st;
+    if (N == 0 || K == 0) return POTQ_OK;
+    if (!W_f16 || !S_f16 || !Gamma_f32 || !dWq_f16 || !dGamma_f32) return POTQ_ERR_NULL;
+    if (misaligned(W_f16) || misaligned(dWq_f16) || misaligned(S_f16, 2) || misaligned(Gamma_f32, 4) ||
+        misaligned(dGamma_f32, 4))
+        return POTQ_ERR_ALIGN;
+    return finish(potq::run_fakequant_backward(W_f16, S_f16, Gamma_f32, dWq_f16, dGamma_f32, N, K, bits, group,
+                                               (hipStream_t)hip_stream));
 }
 
 int pot_check_scales(const void *scales, int64_t count, int bits, void *bad_count_dev, void *hip_stream)

@@ -27,7 +27,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"pot_dequant", "int_dequant", "pot_gemv", "int_gemv", "pot_gemm", "int_gemm", "potq_repack",
-            "pot_check_scales", "pot_dequant_batch", "int_dequant_batch", "pot_gemv_batch", "int_gemv_batch", "potq_gemm_workspace_bytes", "pot_quantize", "potq_version", "potq_strerror", "potq_packed_row_bytes",
+            "pot_check_scales", "pot_dequant_batch", "int_dequant_batch", "pot_gemv_batch", "int_gemv_batch", "potq_gemm_workspace_bytes", "pot_quantize", "pot_fakequant_forward", "pot_fakequant_backward", "potq_version", "potq_strerror", "potq_packed_row_bytes",
             "potq_packed_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -93,6 +93,15 @@ def test_host_side_validation(lib):
     assert qz(A, A, A, 16, 128, 3, 100, None) == GROUP
     assert qz(A, MIS, A, 16, 128, 3, 128, None) == ALIGN
     assert qz(None, None, None, 0, 128, 3, 128, None) == OK
+    ff, fb = lib.pot_fakequant_forward, lib.pot_fakequant_backward
+    assert ff(A, A, None, A, 16, 128, 3, 128, None) == NULL
+    assert ff(A, A, A, A, 16, 128, 5, 128, None) == BITS
+    assert ff(A, A, A, MIS, 16, 128, 3, 128, None) == ALIGN
+    assert ff(None, None, None, None, 0, 128, 3, 128, None) == OK
+    assert fb(A, A, A, None, A, 16, 128, 3, 128, None) == NULL
+    assert fb(A, A, A, A, A, 16, 128, 3, 96, None) == GROUP
+    assert fb(A, A, A, A, 0x10002, 16, 128, 3, 128, None) == ALIGN
+    assert fb(None, None, None, None, None, 16, 0, 3, 128, None) == OK
     c = lib.pot_check_scales
     assert c(A, 4, 3, None, None) == NULL
     assert c(A, 4, 5, A, None) == BITS
