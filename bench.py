@@ -313,6 +313,23 @@ def main() -> int:
             "ms": round(ms_q, 4), "Mweights_per_s": round(4096 * 4096 / ms_q / 1e3, 1),
             "bound": "alu", "T_lane_ops_per_s": round(lane_ops / ms_q / 1e9, 2),
             "pct_valu_peak_39.3T": round(lane_ops / ms_q / 1e9 / 39.3 * 100, 1)}
+        # Step 2 weight path (Sec. 3.3) on one 7B MLP matrix: streaming kernels, 4 bytes per weight each way
+        fN, fK = 11008, 4096
+        fW = to_dev(workloads.weights_f16(workloads.seed_of(0, 1, 4), fN, fK))
+        fS = to_dev(workloads.pot_scales(workloads.seed_of(0, 1, 1), fN, fK, G))
+        fG = torch.zeros((fN, fK // G), dtype=torch.float32, device=dev)
+        fdG = torch.empty_like(fG)
+        fD = to_dev(workloads.weights_f16(workloads.seed_of(0, 1, 5), fN, fK))
+        fO = torch.empty_like(fW)
+        fa = (fW.data_ptr(), fS.data_ptr(), fG.data_ptr(), fO.data_ptr(), fN, fK, b3, G, stream)
+        ba = (fW.data_ptr(), fS.data_ptr(), fG.data_ptr(), fD.data_ptr(), fdG.data_ptr(), fN, fK, b3, G, stream)
+        ms_f = _time_steps(torch, lambda: check(lib.pot_fakequant_forward(*fa)), 50, 5)
+        ms_b = _time_steps(torch, lambda: check(lib.pot_fakequant_backward(*ba)), 50, 5)
+        fbytes = fN * fK * 4 + fN * (fK // G) * 6
+        extras["pot_fakequant_3bit_11008x4096"] = {
+            "forward_us": round(ms_f * 1e3, 2), "forward_GBps": round(fbytes / ms_f / 1e6, 1),
+            "backward_us": round(ms_b * 1e3, 2), "backward_GBps": round((fbytes + fN * (fK // G) * 4) / ms_b / 1e6, 1),
+            "bound": "hbm", "note": "single buffer set (180 MB per pass: partly served by the 256 MB last-level cache)"}
         result["extras"] = extras
 
     print(json.dumps(result))
