@@ -12,18 +12,18 @@
 
 namespace potq {
 
-#ifndef POTQ_DQ_OCTETS
-#define POTQ_DQ_OCTETS 2
-#endif
-#ifndef POTQ_DQ_BLOCK
-#define POTQ_DQ_BLOCK 512
-#endif
 #ifndef POTQ_DQ_NT
 #define POTQ_DQ_NT 1
 #endif
-constexpr int kOctetsPerLane = POTQ_DQ_OCTETS;            // U: stores per lane
-constexpr int kDequantBlock = POTQ_DQ_BLOCK;              // threads per workgroup
-constexpr int kOctetsPerWave = kWave * kOctetsPerLane;    // 256 octets = 2048 weights
+// Shape of the launch by code width: octets (16-byte stores) per lane and threads per
+// workgroup.  Chosen by measurement with code buffers that are not resident in the
+// last-level cache (a rotating set of layers): three octets per lane and 1024 threads are
+// 8-12 % faster than two and 512 at 2 and 3 bits, and 12 % slower at 4 bits.
+#if defined(POTQ_DQ_OCTETS) && defined(POTQ_DQ_BLOCK)
+template <int BITS> struct DequantShape { static constexpr int octets = POTQ_DQ_OCTETS, block = POTQ_DQ_BLOCK; };
+#else
+template <int BITS> struct DequantShape { static constexpr int octets = (BITS == 4) ? 2 : 3, block = (BITS == 4) ? 512 : 1024; };
+#endif
 
 // 32 (bits=4), 24 (bits=3) or 16 (bits=2) code bits of octet `o`, from aligned 32-bit words.
 template <int BITS>
@@ -102,6 +102,9 @@ __device__ __forceinline__ void dequant_block(const uint32_t *__restrict__ codes
                                               int64_t n_octets, int group_shift, int64_t block)
 {
     const int lane = threadIdx.x & (kWave - 1);
+    constexpr int kOctetsPerLane = DequantShape<BITS>::octets;
+    constexpr int kDequantBlock = DequantShape<BITS>::block;
+    constexpr int kOctetsPerWave = kWave * kOctetsPerLane;
     const int64_t wave = block * (kDequantBlock / kWave) + (threadIdx.x >> 6);
     const int64_t base = wave * kOctetsPerWave;
     if (base >= n_octets) return;
@@ -134,7 +137,7 @@ __device__ __forceinline__ void dequant_block(const uint32_t *__restrict__ codes
 }
 
 template <int BITS, bool IS_INT>
-__global__ __launch_bounds__(kDequantBlock) void dequant_kernel(
+__global__ __launch_bounds__(DequantShape<BITS>::block) void dequant_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales,
     const uint16_t *__restrict__ zeros, u32x4 *__restrict__ out, int64_t n_octets, int group_shift)
 {
@@ -156,7 +159,7 @@ struct DequantBatch {
 };
 
 template <int BITS, bool IS_INT>
-__global__ __launch_bounds__(kDequantBlock) void dequant_batch_kernel(const DequantBatch batch, int group_shift)
+__global__ __launch_bounds__(DequantShape<BITS>::block) void dequant_batch_kernel(const DequantBatch batch, int group_shift)
 {
     int i = 0;
     while (i + 1 < batch.count && blockIdx.x >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
@@ -164,10 +167,16 @@ __global__ __launch_bounds__(kDequantBlock) void dequant_batch_kernel(const Dequ
                                 group_shift, blockIdx.x - batch.first_block[i]);
 }
 
-static int64_t dequant_blocks(int64_t n_octets)
+static int dequant_block_threads(int bits) { return bits == 4 ? DequantShape<4>::block : DequantShape<2>::block; }
+
+static int64_t dequant_blocks(int64_t n_octets, int bits)
 {
-    const int64_t waves = (n_octets + kOctetsPerWave - 1) / kOctetsPerWave;
-    return (waves + (kDequantBlock / kWave) - 1) / (kDequantBlock / kWave);
+    static_assert(DequantShape<2>::octets == DequantShape<3>::octets && DequantShape<2>::block == DequantShape<3>::block,
+                  "2- and 3-bit launches share one shape");
+    const int64_t per_wave = kWave * (bits == 4 ? DequantShape<4>::octets : DequantShape<2>::octets);
+    const int64_t waves_per_block = dequant_block_threads(bits) / kWave;
+    const int64_t waves = (n_octets + per_wave - 1) / per_wave;
+    return (waves + waves_per_block - 1) / waves_per_block;
 }
 
 template <int BITS, bool IS_INT>
@@ -176,7 +185,7 @@ static hipError_t launch_dequant(const void *codes, const void *scales, const vo
 {
     const int64_t n_octets = N * K / 8;
     const int group_shift = (group == 128) ? 7 : 6;
-    hipLaunchKernelGGL((dequant_kernel<BITS, IS_INT>), dim3((unsigned)dequant_blocks(n_octets)), dim3(kDequantBlock),
+    hipLaunchKernelGGL((dequant_kernel<BITS, IS_INT>), dim3((unsigned)dequant_blocks(n_octets, BITS)), dim3(DequantShape<BITS>::block),
                        0, stream, (const uint32_t *)codes, (const uint16_t *)scales, (const uint16_t *)zeros,
                        (u32x4 *)out, n_octets, group_shift);
     return hipGetLastError();
@@ -221,14 +230,14 @@ hipError_t run_dequant_batch(bool is_int, int count, const void *const *codes, c
         b.out[i] = live ? (u32x4 *)out[k] : nullptr;
         b.n_octets[i] = live ? N[k] * K[k] / 8 : 0;
         b.first_block[i] = (uint32_t)blocks;
-        if (live) blocks += (uint64_t)dequant_blocks(b.n_octets[i]);
+        if (live) blocks += (uint64_t)dequant_blocks(b.n_octets[i], bits);
     }
     b.first_block[kMaxBatch] = (uint32_t)blocks;
     b.count = count;
     if (blocks == 0) return hipSuccess;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const int group_shift = (group == 128) ? 7 : 6;
-    const dim3 grid((unsigned)blocks), block(kDequantBlock);
+    const dim3 grid((unsigned)blocks), block((unsigned)dequant_block_threads(bits));
     if (is_int) {
         if (bits == 4) hipLaunchKernelGGL((dequant_batch_kernel<4, true>), grid, block, 0, stream, b, group_shift);
         else if (bits == 3) hipLaunchKernelGGL((dequant_batch_kernel<3, true>), grid, block, 0, stream, b, group_shift);
