@@ -28,8 +28,11 @@ namespace potq {
 #ifndef POTQ_GEMM_WPE
 #define POTQ_GEMM_WPE 2
 #endif
+#ifndef POTQ_GEMM_KSPLIT
+#define POTQ_GEMM_KSPLIT 1
+#endif
 
-template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC>
+template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC, int KS>
 __global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu((RM * CN == 16) ? POTQ_GEMM_WPE : 1, 8)))
 void gemm_tile16_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
@@ -37,11 +40,17 @@ void gemm_tile16_kernel(
     int groups_per_split, int gs)
 {
     // gs = 0: one scale per 128 columns; gs = 1: one per 64 (lane (r, q) then uses scale column 2g + q/2)
+    // KS wavefronts share a set of row tiles and split every chunk of K between them: a chunk is
+    // CW = GC * KS scale groups wide, wavefront part `kpart` takes groups kpart*GC .. kpart*GC+GC-1 of
+    // it, and the KS partial tiles are added through LDS at the end, in a fixed order.
     constexpr int MT = 16 * CN;                       // tokens per workgroup
     constexpr int THREADS = WAVES * kWave;
-    constexpr int PPT = (MT * 16) / THREADS;          // 16-byte pieces of an X chunk per thread
-    static_assert((MT * 16) % THREADS == 0, "X chunk must divide evenly over the workgroup");
-    extern __shared__ u32x4 smem[];                   // [2 buffers][GC groups][16 k-slot groups][MT tokens]
+    constexpr int CW = GC * KS;                       // scale groups per chunk
+    constexpr int RS = WAVES / KS;                    // row-tile slots per workgroup
+    constexpr int PPT = (CW * MT * 16) / THREADS;     // 16-byte pieces of an X chunk per thread
+    static_assert(WAVES % KS == 0, "wavefronts must divide evenly over the K parts");
+    static_assert((CW * MT * 16) % THREADS == 0, "X chunk must divide evenly over the workgroup");
+    extern __shared__ u32x4 smem[];                   // [2 buffers][CW groups][16 k-slot groups][MT tokens]
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -50,7 +59,8 @@ void gemm_tile16_kernel(
     const int q = lane >> 4;
     const int G = K / kTileCols;
     const int64_t rowtiles = N / kTileRows;
-    const int64_t rt0 = ((int64_t)blockIdx.x * WAVES + wave) * RM;
+    const int kpart = wave % KS;
+    const int64_t rt0 = ((int64_t)blockIdx.x * RS + wave / KS) * RM;
     const int m0 = blockIdx.y * MT;
     // split-K: blockIdx.z owns scale groups [g_begin, g_end); its fp32 sums go to partial[z] when gridDim.z > 1
     const int g_begin = blockIdx.z * groups_per_split;
@@ -76,11 +86,13 @@ void gemm_tile16_kernel(
 
     // X side: this thread's pieces of a chunk (16 tokens x 4 consecutive 8-value runs per wavefront)
     const uint16_t *xsrc[PPT];
-    int xslot[PPT];
+    int xslot[PPT], xgrp[PPT];
     bool xok[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
-        const int p = tid + THREADS * i;
+        const int pc = tid + THREADS * i;             // piece index inside the chunk
+        xgrp[i] = pc / (MT * 16);                     // scale group inside the chunk
+        const int p = pc % (MT * 16);
         const int st = p & 3;                         // run inside a 32-column block = MFMA step
         const int blk = p >> 6;
         const int m = ((p >> 2) & 15) + 16 * (blk % CN);   // four consecutive lanes read 64 contiguous bytes
@@ -89,7 +101,7 @@ void gemm_tile16_kernel(
         xsrc[i] = X + (int64_t)(xok[i] ? m0 + m : 0) * K + 32 * qq + 8 * st;
         // rotate the token index inside its 16-token tile by 4*st: the four lanes of a quad (same
         // token, st = 0..3) then write to four different LDS bank groups
-        xslot[i] = (st * 4 + qq) * MT + (m & ~15) + ((m + 4 * st) & 15);
+        xslot[i] = xgrp[i] * 16 * MT + (st * 4 + qq) * MT + (m & ~15) + ((m + 4 * st) & 15);
     }
 
     // with few output tiles per wavefront the MFMAs of one tile form a dependent chain:
@@ -108,25 +120,24 @@ void gemm_tile16_kernel(
     // zero afterwards) and every iteration issues the same loads in the same order.
     constexpr bool kAlignedChunks = (GC % 4 == 0);     // chunks start on multiples of four groups (see launch)
     // register stages of X (the LDS buffer is one more stage); the big tiles keep one to stay at two wavefronts per SIMD
-    constexpr int kXStages = (GC * PPT <= 4 && RM * CN < POTQ_GEMM_XS_LIMIT) ? 2 : 1;
+    constexpr int kXStages = (PPT <= 4 && RM * CN < POTQ_GEMM_XS_LIMIT) ? 2 : 1;
     uint32_t wr[2][GC][RM][BITS], sr[2][GC][RM], zr[2][GC][RM];
-    u32x4 xreg[kXStages][GC][PPT];
+    u32x4 xreg[kXStages][PPT];
     uint32_t xmask[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) xmask[i] = xok[i] ? 0xFFFFFFFFu : 0u;
 
     auto fetch_x = [&](int stage, int g0) {
 #pragma unroll
-        for (int gi = 0; gi < GC; ++gi) {
-            const int gc = g0 + gi < g_end ? g0 + gi : g_end - 1;   // past the end: re-read the last group
-#pragma unroll
-            for (int i = 0; i < PPT; ++i) xreg[stage][gi][i] = *(const u32x4 *)(xsrc[i] + gc * kTileCols);
+        for (int i = 0; i < PPT; ++i) {
+            const int gc = min(g0 + xgrp[i], g_end - 1);            // past the end: re-read the last group
+            xreg[stage][i] = *(const u32x4 *)(xsrc[i] + gc * kTileCols);
         }
     };
     auto fetch_w = [&](int stage, int g0) {
 #pragma unroll
         for (int gi = 0; gi < GC; ++gi) {
-            const int gc = g0 + gi < g_end ? g0 + gi : g_end - 1;
+            const int gc = min(g0 + kpart * GC + gi, g_end - 1);
 #pragma unroll
             for (int rm = 0; rm < RM; ++rm) {
 #pragma unroll
@@ -146,21 +157,16 @@ void gemm_tile16_kernel(
     };
 
     auto process = [&](int stage, int g0) {
-        u32x4 *buf = smem + stage * (GC * 16 * MT);
-        constexpr int xs = kXStages == 2 ? 1 : 0;
+        u32x4 *buf = smem + stage * (CW * 16 * MT);
 #pragma unroll
-        for (int gi = 0; gi < GC; ++gi)
-#pragma unroll
-            for (int i = 0; i < PPT; ++i)
-                buf[gi * 16 * MT + xslot[i]] = xreg[kXStages == 2 ? stage : 0][gi][i] & xmask[i];
-        (void)xs;
+        for (int i = 0; i < PPT; ++i) buf[xslot[i]] = xreg[kXStages == 2 ? stage : 0][i] & xmask[i];
         __syncthreads();    // this buffer was last read two chunks ago, before the previous barrier
-        fetch_x(kXStages == 2 ? stage : 0, g0 + kXStages * GC);
+        fetch_x(kXStages == 2 ? stage : 0, g0 + kXStages * CW);
 
         uint32_t w[GC][RM][BITS], s[GC][RM], z[GC][RM];
 #pragma unroll
         for (int gi = 0; gi < GC; ++gi) {
-            const int gc = g0 + gi < g_end ? g0 + gi : g_end - 1;
+            const int gc = min(g0 + kpart * GC + gi, g_end - 1);
             const int scale_owner = (4 * r + (((gc << gs) + ((q >> 1) & -gs)) & 3)) * 4;
 #pragma unroll
             for (int rm = 0; rm < RM; ++rm) {
@@ -171,12 +177,12 @@ void gemm_tile16_kernel(
                 z[gi][rm] = IS_INT ? (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)zr[stage][gi][rm]) : 0u;
             }
         }
-        fetch_w(stage, g0 + 2 * GC);
+        fetch_w(stage, g0 + 2 * CW);
 
 #pragma unroll
         for (int gi = 0; gi < GC; ++gi) {
-            if (g0 + gi >= g_end) break;              // uniform: only the last chunk of a split can be short
-            const u32x4 *xb = buf + gi * 16 * MT;
+            if (g0 + kpart * GC + gi >= g_end) break; // wavefront-uniform: only the last chunk of a split can be short
+            const u32x4 *xb = buf + (kpart * GC + gi) * 16 * MT;
             Decoder<BITS, IS_INT> dec[RM];
 #pragma unroll
             for (int rm = 0; rm < RM; ++rm) {
@@ -205,15 +211,41 @@ void gemm_tile16_kernel(
     };
 
     fetch_x(0, g_begin);
-    if (kXStages == 2) fetch_x(1, g_begin + GC);
+    if (kXStages == 2) fetch_x(1, g_begin + CW);
     fetch_w(0, g_begin);
-    fetch_w(1, g_begin + GC);
+    fetch_w(1, g_begin + CW);
     int g = g_begin;
-    for (; g + GC < g_end; g += 2 * GC) {
+    for (; g + CW < g_end; g += 2 * CW) {
         process(0, g);
-        process(1, g + GC);
+        process(1, g + CW);
     }
     if (g < g_end) process(0, g);
+
+    // K parts of a row-tile slot: every wavefront leaves its tiles in LDS, part 0 adds them in
+    // ascending part order (reproducible) and goes on to the store
+    if constexpr (KS > 1) {
+        float4_t *red = (float4_t *)smem;             // [wave][rm][c][lane]
+        __syncthreads();                              // every wavefront is done reading X from LDS
+#pragma unroll
+        for (int rm = 0; rm < RM; ++rm)
+#pragma unroll
+            for (int c = 0; c < CN; ++c) {
+                const float4_t mine = ACCS == 2 ? acc[0][rm][c] + acc[ACCS - 1][rm][c] : acc[0][rm][c];
+                red[((wave * RM + rm) * CN + c) * kWave + lane] = mine;
+            }
+        __syncthreads();
+        if (kpart != 0) return;
+#pragma unroll
+        for (int rm = 0; rm < RM; ++rm)
+#pragma unroll
+            for (int c = 0; c < CN; ++c) {
+                float4_t sum = red[((wave * RM + rm) * CN + c) * kWave + lane];
+#pragma unroll
+                for (int p = 1; p < KS; ++p) sum += red[(((wave + p) * RM + rm) * CN + c) * kWave + lane];
+                acc[0][rm][c] = sum;
+                if (ACCS == 2) acc[ACCS - 1][rm][c] = float4_t{0.f, 0.f, 0.f, 0.f};
+            }
+    }
 
     // D: lane holds token m0 + 16c + (lane % 16), weight rows 4*(lane / 16) + i of each row tile
     typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
@@ -264,34 +296,41 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4_t *__rest
 
 // Number of K splits: enough workgroups to occupy the chip about three times over,
 // at least four scale groups per split, and only as many as the workspace holds.
-static int choose_splits(int64_t workgroups, int64_t G, int64_t M, int64_t N, size_t workspace_bytes, bool big)
+static int choose_splits(int64_t workgroups, int waves, int ks, int64_t G, int64_t M, int64_t N,
+                         size_t workspace_bytes, bool big)
 {
     // the many-token configuration moves M*N*4 bytes per split through the workspace: split only when
-    // fewer than ~60 % of the CUs would have a workgroup, and then just enough to cover them
+    // fewer than ~60 % of the CUs would have a workgroup, and then just enough to cover them; the
+    // others aim at POTQ_GEMM_TARGET_WGS four-wavefront workgroups' worth of wavefronts
+    const int64_t units = workgroups * waves / 4;
     int64_t want = big ? (workgroups < 160 ? (320 + workgroups - 1) / workgroups : 1)
-                       : (POTQ_GEMM_TARGET_WGS + workgroups - 1) / workgroups;
-    if (want > G / POTQ_GEMM_MIN_GROUPS) want = G / POTQ_GEMM_MIN_GROUPS;
+                       : (POTQ_GEMM_TARGET_WGS + units - 1) / units;
+    if (want > G / (POTQ_GEMM_MIN_GROUPS * ks)) want = G / (POTQ_GEMM_MIN_GROUPS * ks);
     if (want > 16) want = 16;
     const int64_t fit = (int64_t)(workspace_bytes / ((size_t)M * (size_t)N * sizeof(float)));
     if (want > fit) want = fit;
     return want < 2 ? 1 : (int)want;
 }
 
-template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC>
+template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC, int KS = 1>
 static void launch_gemm_cfg(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                             int64_t M, int64_t N, int64_t K, int group, void *workspace, size_t workspace_bytes,
                             hipStream_t stream)
 {
     const int64_t rowtiles = N / kTileRows;
     const int64_t G = K / kTileCols;
-    const unsigned gx = (unsigned)((rowtiles + WAVES * RM - 1) / (WAVES * RM));
+    constexpr int RS = WAVES / KS;                    // row-tile slots per workgroup
+    constexpr int CW = GC * KS;                       // scale groups per chunk
+    const unsigned gx = (unsigned)((rowtiles + RS * RM - 1) / (RS * RM));
     const unsigned gy = (unsigned)((M + 16 * CN - 1) / (16 * CN));
-    int splits = workspace ? choose_splits((int64_t)gx * gy, G, M, N, workspace_bytes, CN >= 8) : 1;
+    int splits = workspace ? choose_splits((int64_t)gx * gy, WAVES, KS, G, M, N, workspace_bytes, CN >= 8) : 1;
     int per = (int)((G + splits - 1) / splits);
-    per = (per + GC - 1) / GC * GC;                   // whole chunks
+    per = (per + CW - 1) / CW * CW;                   // whole chunks
     splits = (int)((G + per - 1) / per);              // no empty split
-    const size_t lds = (size_t)2 * GC * 16 * (16 * CN) * sizeof(u32x4);
-    hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN, GC>), dim3(gx, gy, (unsigned)splits),
+    size_t lds = (size_t)2 * CW * 16 * (16 * CN) * sizeof(u32x4);
+    const size_t red = KS > 1 ? (size_t)WAVES * RM * CN * kWave * sizeof(float4_t) : 0;
+    if (red > lds) lds = red;
+    hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN, GC, KS>), dim3(gx, gy, (unsigned)splits),
                        dim3(WAVES * kWave), lds, stream, (const uint32_t *)codes, (const uint16_t *)scales,
                        (const uint16_t *)zeros, (const uint16_t *)X, (uint16_t *)Y, (float *)workspace, (int)M, N,
                        (int)K, per, group == 64 ? 1 : 0);
@@ -333,12 +372,26 @@ template <int BITS, bool IS_INT>
 static void launch_gemm(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                         int64_t M, int64_t N, int64_t K, int group, void *ws, size_t ws_bytes, hipStream_t stream)
 {
+    // Few tokens: not enough output tiles for the chip.  With short rows (K <= 8192) the eight
+    // wavefronts of a workgroup split K between them (no second kernel, no workspace traffic:
+    // 5-16 % faster at K = 5120); with long rows every workgroup would re-read too much of X, and
+    // K is split over workgroups instead, through the caller's workspace.
+    const bool in_group_split = POTQ_GEMM_KSPLIT && K <= 8192;
     if (M <= 16) {
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        if (in_group_split)
+            launch_gemm_cfg<BITS, IS_INT, 8, 1, 1, 2, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else
+            launch_gemm_cfg<BITS, IS_INT, 4, 1, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else if (M <= 32) {
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 2, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        if (in_group_split)
+            launch_gemm_cfg<BITS, IS_INT, 8, 1, 2, 2, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else
+            launch_gemm_cfg<BITS, IS_INT, 4, 1, 2, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else if (M <= 64) {
-        launch_gemm_cfg<BITS, IS_INT, 4, 1, 4, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        if (in_group_split)
+            launch_gemm_cfg<BITS, IS_INT, 8, 1, 4, 1, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else
+            launch_gemm_cfg<BITS, IS_INT, 4, 1, 4, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
         int rm, cn;
         big_tile(M, N, &rm, &cn);
