@@ -363,6 +363,7 @@ static int64_t big_workgroups(int64_t M, int64_t N)
 // Workspace that lets every supported shape use its preferred number of splits.
 size_t gemm_workspace_bytes(int64_t M, int64_t N)
 {
+    if (M <= 16) return 0;                            // the few-token kernel splits K inside the workgroup
     if (M <= 64) return (size_t)16 * M * N * sizeof(float);
     const int64_t workgroups = big_workgroups(M, N);
     return workgroups < 160 ? (size_t)((320 + workgroups - 1) / workgroups) * M * N * sizeof(float) : 0;
@@ -377,12 +378,7 @@ static void launch_gemm(const void *codes, const void *scales, const void *zeros
     // 5-16 % faster at K = 5120); with long rows every workgroup would re-read too much of X, and
     // K is split over workgroups instead, through the caller's workspace.
     const bool in_group_split = POTQ_GEMM_KSPLIT && K <= 8192;
-    if (M <= 16) {
-        if (in_group_split)
-            launch_gemm_cfg<BITS, IS_INT, 8, 1, 1, 2, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
-        else
-            launch_gemm_cfg<BITS, IS_INT, 4, 1, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
-    } else if (M <= 32) {
+    if (M <= 32) {
         if (in_group_split)
             launch_gemm_cfg<BITS, IS_INT, 8, 1, 2, 2, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else
@@ -404,10 +400,16 @@ static void launch_gemm(const void *codes, const void *scales, const void *zeros
     }
 }
 
+hipError_t run_gemm_fewtok(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
+                           void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
+
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, void *ws, size_t ws_bytes,
                            hipStream_t stream)
 {
+    // up to 16 tokens: the kernel built like the GEMV (one table per 128 weights, no cross-lane code traffic)
+    if (M <= 16)
+        return run_gemm_fewtok(is_int, codes, scales, zeros, X, Y, M, N, K, bits, group, stream);
     if (is_int) {
         if (bits == 4) launch_gemm<4, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else if (bits == 3) launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);

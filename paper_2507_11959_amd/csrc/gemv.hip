@@ -19,10 +19,10 @@ namespace potq {
 // values, the same in all 16 columns, so every column of the 16x16 result holds
 // the partial products of the 16 rows.  Products are exact, sums fp32.
 // `s`/`z` serve columns 0..63, `s_hi`/`z_hi` columns 64..127 (the same values for group size 128).
-template <int BITS, bool IS_INT>
+// `bfrag(j)` returns the B operand of step j (j = 0..15: columns 8j .. 8j+7 of the group).
+template <int BITS, bool IS_INT, typename BFrag>
 __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, uint32_t z, uint32_t s_hi,
-                                           uint32_t z_hi, bool two_scales, const u32x4 *__restrict__ xg,
-                                           float4_t (&acc)[4])
+                                           uint32_t z_hi, bool two_scales, BFrag bfrag, float4_t (&acc)[4])
 {
     Decoder<BITS, IS_INT> dec;
 #pragma unroll
@@ -35,7 +35,7 @@ __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, u
         dec.set_block(w);
 #pragma unroll
         for (int m = 0; m < 8; m += 2) {
-            const u32x4 xv = xg[b * 4 + m / 2];     // columns 32b + 4m .. + 7
+            const u32x4 xv = bfrag(b * 4 + m / 2);  // columns 32b + 4m .. + 7
             uint32_t e0, o0, e1, o1;
             dec.get(m, e0, o0);
             dec.get(m + 1, e1, o1);
@@ -162,7 +162,8 @@ __device__ __forceinline__ void gemv_tile16_body(
             so = so_hi = 0x3C00u;
             zo = zo_hi = 0u;
         }
-        gemv_group<BITS, IS_INT>(L, so, zo, so_hi, zo_hi, gs != 0, g < G ? xs + g * kXRun : zero_block, acc);
+        const u32x4 *xg = g < G ? xs + g * kXRun : zero_block;
+        gemv_group<BITS, IS_INT>(L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xg[j]; }, acc);
         g = gn;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
@@ -226,6 +227,209 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_batch_kernel(
     while (i + 1 < batch.count && blockIdx.x >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
     gemv_tile16_body<BITS, IS_INT, S, G64>(batch.codes[i], batch.scales[i], batch.zeros[i], x, batch.y[i],
                                            batch.rowtiles[i], K, blockIdx.x - batch.first_block[i]);
+}
+
+// ---------------------------------------------------------------------------
+// Fused GEMM for at most 16 tokens (batched decoding), built like the GEMV:
+// lane (r, t) owns row r of one scale group (16-byte code loads, one table per
+// 128 weights, no cross-lane traffic for the codes), and the B operand of the
+// MFMA holds the 16 tokens instead of 16 copies of x, so all 256 results of
+// v_mfma_f32_16x16x32_f16 are used: D[row][token].
+//
+// A workgroup of 8 (16) wavefronts serves 2 (4) row tiles; the 4 wavefronts of a
+// tile take 4 consecutive groups each, so a round of the workgroup covers 16
+// groups (2048 columns).  The X chunk of a round (16 tokens x 2048 columns, 64 KB) sits
+// in LDS as [group][step][token] 16-byte runs, the token index rotated by
+// 4 * (step % 4) so that the staging writes (a quad of lanes holds four
+// consecutive runs of one token) spread over the banks.  The chunk of the next
+// round travels through registers while the current one is consumed.
+// ---------------------------------------------------------------------------
+constexpr int kFewSplit = 4;                          // wavefronts per row tile
+constexpr int kFewChunk = 4 * kFewSplit;              // scale groups per round
+constexpr int kFewDepth = 1;                          // rounds of codes requested ahead (two or three measured no better)
+
+template <int BITS, bool IS_INT, bool G64, int kFewWaves>
+__global__ __launch_bounds__(kFewWaves * kWave) void gemm_fewtok_kernel(
+    const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
+    const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, int M, int64_t N, int K)
+{
+    constexpr int gs = G64 ? 1 : 0;
+    constexpr int R = kFewWaves / kFewSplit;
+    constexpr int kFewPieces = kFewChunk * 256 / (kFewWaves * kWave);   // 16-byte X pieces per thread and round
+    extern __shared__ u32x4 smem[];                     // [16 groups][16 steps][16 tokens]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int r = lane & 15;
+    const int t = lane >> 4;
+    const int G = K / kTileCols;
+    const int64_t rowtiles = N / kTileRows;
+    const int part = wave % kFewSplit;
+    int64_t rowtile = (int64_t)blockIdx.x * R + wave / kFewSplit;
+    const bool live = rowtile < rowtiles;
+    if (!live) rowtile = rowtiles - 1;                  // surplus wavefronts redo the last tile, store nothing
+    const int64_t row = rowtile * kTileRows + r;
+    const u32x4 *tile0 = codes + rowtile * G * (BITS * 16) + r;
+    const uint16_t *srow = scales + (rowtile * kTileRows + (lane >> 2)) * G;
+    const uint16_t *zrow = IS_INT ? zeros + (rowtile * kTileRows + (lane >> 2)) * G : nullptr;
+    const int scale_owner = (4 * r + t) * 4;
+    const uint32_t *srow2 = (const uint32_t *)(scales + row * (int64_t)(2 * G));
+    const uint32_t *zrow2 = IS_INT ? (const uint32_t *)(zeros + row * (int64_t)(2 * G)) : nullptr;
+    const int rounds = (G + kFewChunk - 1) / kFewChunk;
+
+    struct Fetched {
+        u32x4 L[BITS];
+        uint32_t s, z;
+    };
+    auto fetch = [&](int rnd, Fetched &f) {             // indices clamped into the matrix, as in the GEMV
+        const int gc = min(rnd * kFewChunk + part * 4 + t, G - 1);
+#pragma unroll
+        for (int j = 0; j < BITS; ++j)
+            f.L[j] = __builtin_nontemporal_load(tile0 + (int64_t)gc * (BITS * 16) + 16 * j);
+        f.z = 0;
+        if (gs) {
+            f.s = srow2[gc];
+            if (IS_INT) f.z = zrow2[gc];
+        } else {
+            const int gq = min(rnd * kFewChunk + part * 4 + (lane & 3), G - 1);
+            f.s = srow[gq];
+            if (IS_INT) f.z = zrow[gq];
+        }
+    };
+
+    // X pieces of this thread: piece p = tid + (threads) i is run (p % 4) + 4 (p/64 % 4) of group p/256
+    // for token (p/4) % 16 -- four consecutive lanes read 64 contiguous bytes of one token
+    const uint16_t *xsrc[kFewPieces];
+    int xslot[kFewPieces], xgrp[kFewPieces];
+    bool xtok[kFewPieces];
+#pragma unroll
+    for (int i = 0; i < kFewPieces; ++i) {
+        const int p = tid + kFewWaves * kWave * i;
+        const int jl = p & 3, c = (p >> 2) & 15, blk = p >> 6;
+        const int j = (blk & 3) * 4 + jl;
+        xgrp[i] = blk >> 2;
+        xtok[i] = c < M;
+        xsrc[i] = X + (int64_t)(xtok[i] ? c : 0) * K + 8 * j;
+        xslot[i] = (xgrp[i] * 16 + j) * 16 + ((c + 4 * jl) & 15);
+    }
+    u32x4 xr[kFewPieces];
+    auto fetch_x = [&](int rnd) {
+#pragma unroll
+        for (int i = 0; i < kFewPieces; ++i) {
+            const int g = rnd * kFewChunk + xgrp[i];
+            const u32x4 v = *(const u32x4 *)(xsrc[i] + (int64_t)min(g, G - 1) * kTileCols);
+            xr[i] = (xtok[i] && g < G) ? v : u32x4{0u, 0u, 0u, 0u};   // tokens past M and groups past K count as zero
+        }
+    };
+    // B operand of step j for lane (token r, k-slice t): group 4*part + t of the chunk
+    const u32x4 *xq[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) xq[k] = smem + (part * 4 + t) * 256 + ((r + 4 * k) & 15);
+
+    Fetched q[kFewDepth];                               // rounds of codes in flight ahead of the arithmetic
+#pragma unroll
+    for (int d = 0; d < kFewDepth; ++d) fetch(d, q[d]);
+    fetch_x(0);
+
+    float4_t acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int round = 0; round < rounds; ++round) {
+        if (round) __syncthreads();                     // the previous chunk has been consumed
+#pragma unroll
+        for (int i = 0; i < kFewPieces; ++i) smem[xslot[i]] = xr[i];
+        __syncthreads();
+        Fetched nx;
+        fetch(round + kFewDepth, nx);
+        fetch_x(round + 1);                             // past the end: clamped addresses, zeros, never used
+        const Fetched &cur = q[0];
+
+        const int g = round * kFewChunk + part * 4 + t;
+        uint32_t so, zo = 0u, so_hi, zo_hi = 0u;
+        if (gs) {
+            so = cur.s & 0xFFFFu;
+            so_hi = cur.s >> 16;
+            if (IS_INT) {
+                zo = cur.z & 0xFFFFu;
+                zo_hi = cur.z >> 16;
+            }
+        } else {
+            so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)cur.s);
+            if (IS_INT) zo = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)cur.z);
+            so_hi = so;
+            zo_hi = zo;
+        }
+        if (g >= G) {                                   // finite weights against a zero B operand
+            so = so_hi = 0x3C00u;
+            zo = zo_hi = 0u;
+        }
+        gemv_group<BITS, IS_INT>(cur.L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xq[j & 3][j * 16]; }, acc);
+#pragma unroll
+        for (int d = 0; d + 1 < kFewDepth; ++d) q[d] = q[d + 1];
+        q[kFewDepth - 1] = nx;
+    }
+
+    // D: lane (c, q) holds token c, rows 4q .. 4q+3.  Add the four wavefronts of a tile in a fixed order.
+    float4_t *red = (float4_t *)smem;
+    const float4_t part_sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    __syncthreads();                                    // every wavefront is done with the X chunk
+    red[wave * kWave + lane] = part_sum;
+    __syncthreads();
+    if (part != 0 || !live || r >= M) return;
+    float4_t sum = red[wave * kWave + lane];
+#pragma unroll
+    for (int p = 1; p < kFewSplit; ++p) sum += red[(wave + p) * kWave + lane];
+    typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+    half4_t h;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) h[i] = (_Float16)sum[i];
+    *(half4_t *)(Y + (int64_t)r * N + rowtile * kTileRows + 4 * t) = h;
+}
+
+template <int BITS, bool IS_INT, bool G64, int WAVES>
+static void launch_gemm_fewtok_cfg(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
+                                   int64_t M, int64_t N, int64_t K, hipStream_t stream)
+{
+    const int64_t rowtiles = N / kTileRows;
+    constexpr int R = WAVES / kFewSplit;
+    const dim3 grid((unsigned)((rowtiles + R - 1) / R)), block(WAVES * kWave);
+    const size_t lds = (size_t)kFewChunk * 256 * sizeof(u32x4);
+    hipLaunchKernelGGL((gemm_fewtok_kernel<BITS, IS_INT, G64, WAVES>), grid, block, lds, stream, (const u32x4 *)codes,
+                       (const uint16_t *)scales, (const uint16_t *)zeros, (const uint16_t *)X, (uint16_t *)Y, (int)M, N,
+                       (int)K);
+}
+
+// Tall matrices take 16 wavefronts per workgroup (four row tiles share every X chunk: 13.3 us
+// against 15.8 us on 13824 x 5120), the others 8 (more workgroups: 9.2 us against 12.2 us on 5120 x 5120).
+template <int BITS, bool IS_INT>
+static void launch_gemm_fewtok(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
+                               int64_t M, int64_t N, int64_t K, int group, hipStream_t stream)
+{
+    const bool tall = N / kTileRows >= 768;
+    if (group == 64) {
+        if (tall) launch_gemm_fewtok_cfg<BITS, IS_INT, true, 16>(codes, scales, zeros, X, Y, M, N, K, stream);
+        else launch_gemm_fewtok_cfg<BITS, IS_INT, true, 8>(codes, scales, zeros, X, Y, M, N, K, stream);
+    } else {
+        if (tall) launch_gemm_fewtok_cfg<BITS, IS_INT, false, 16>(codes, scales, zeros, X, Y, M, N, K, stream);
+        else launch_gemm_fewtok_cfg<BITS, IS_INT, false, 8>(codes, scales, zeros, X, Y, M, N, K, stream);
+    }
+}
+
+// M <= 16 tokens, tiled layout.
+hipError_t run_gemm_fewtok(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
+                           void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, hipStream_t stream)
+{
+    if (is_int) {
+        if (bits == 4) launch_gemm_fewtok<4, true>(codes, scales, zeros, X, Y, M, N, K, group, stream);
+        else if (bits == 3) launch_gemm_fewtok<3, true>(codes, scales, zeros, X, Y, M, N, K, group, stream);
+        else launch_gemm_fewtok<2, true>(codes, scales, zeros, X, Y, M, N, K, group, stream);
+    } else {
+        if (bits == 4) launch_gemm_fewtok<4, false>(codes, scales, zeros, X, Y, M, N, K, group, stream);
+        else if (bits == 3) launch_gemm_fewtok<3, false>(codes, scales, zeros, X, Y, M, N, K, group, stream);
+        else launch_gemm_fewtok<2, false>(codes, scales, zeros, X, Y, M, N, K, group, stream);
+    }
+    return hipGetLastError();
 }
 
 size_t gemv_lds_bytes(int64_t K)
