@@ -78,7 +78,8 @@ def test_host_side_validation(lib):
     assert m(None, None, None, None, 0, 16, 128, 3, 128, 1, None, 0, None) == OK
     assert m(A, A, A, A, 4, 16, 128, 3, 128, 1, MIS, 1 << 20, None) == ALIGN
     assert lib.int_gemm(A, A, None, A, A, 4, 16, 128, 3, 128, 1, None, 0, None) == NULL
-    assert lib.potq_gemm_workspace_bytes(16, 4096, 4096, 3) == 16 * 16 * 4096 * 4
+    assert lib.potq_gemm_workspace_bytes(16, 4096, 4096, 3) == 0          # up to 16 tokens: no workspace is used
+    assert lib.potq_gemm_workspace_bytes(32, 4096, 4096, 3) == 16 * 32 * 4096 * 4
     assert lib.potq_gemm_workspace_bytes(256, 13824, 5120, 3) == 0      # enough output tiles: no split
     assert lib.potq_gemm_workspace_bytes(256, 4096, 4096, 3) == 5 * 256 * 4096 * 4   # 64 tiles of 128x128
     assert lib.potq_gemm_workspace_bytes(0, 4096, 4096, 3) == 0
