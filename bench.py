@@ -349,7 +349,7 @@ def main() -> int:
             del tiled
             torch.cuda.empty_cache()
         extras["pot_gemm_3bit_13b_shapes"] = gemm
-        del tiled, sc, Sd, Zd
+        del sc, Sd, Zd
         torch.cuda.empty_cache()
 
         # Step 1 scale search (Algorithm 1) on one 4096x4096 fp16 matrix, 3-bit, group 128: plain vector-ALU
