@@ -99,10 +99,11 @@ int pot_dequant(const void *codes, const void *scales, void *out_f16,
 /*
  * int_dequant -- the uniform baseline (Sec. 4.1 Eq. (9)):
  *   out[n,k] = fp16_rne( (q[n,k] + zeros[n,k/group]) * scales[n,k/group] )
- * q is the unsigned `bits`-bit code (same canonical stream).  `zeros` holds
- * integer-valued fp16 numbers in [-(2^bits - 1), 0]; for those the result is
- * the exact product rounded once.  (For other zero-points q + Z is itself
- * rounded to fp16 first.)
+ * q is the unsigned `bits`-bit code (same canonical stream).  `zeros` must hold
+ * integer-valued fp16 numbers in [-(2^bits - 1), 0]; for those q + Z is exact
+ * and the result is the exact product rounded once, identically in int_dequant,
+ * int_gemv and int_gemm.  Other zero-points are outside the contract: the sum
+ * q + Z is then rounded at a point that differs between the entry points.
  */
 int int_dequant(const void *codes, const void *scales, const void *zeros, void *out_f16,
                 int64_t N, int64_t K, int bits, int group, void *hip_stream);
@@ -145,7 +146,9 @@ int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits,
  *   y[n] = fp16( sum_k W~[n,k] * x[k] ),  W~ as defined by pot_dequant,
  * products exact, accumulation in fp32, one rounding to fp16 at the end.
  *   x_f16 in  K fp16;   y_f16 out  N fp16
- * `layout` names the layout `codes` is in.
+ * `layout` names the layout `codes` is in; only POTQ_LAYOUT_TILE16 is accepted
+ * (POTQ_ERR_LAYOUT otherwise; potq_repack converts), which needs N % 16 == 0.
+ * The whole of x is held in on-chip memory: K <= 30464 (POTQ_ERR_SHAPE beyond).
  */
 int pot_gemv(const void *codes, const void *scales, const void *x_f16, void *y_f16,
              int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
@@ -189,7 +192,9 @@ int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f1
  * in a fixed order in a second small kernel (results stay reproducible).
  * potq_gemm_workspace_bytes() returns the size that allows the preferred split
  * (0 when no split would be used); a NULL or smaller workspace is valid and
- * only means fewer splits.  The workspace may be reused by the next call on the
+ * only means fewer splits; with at most 16 tokens, and with at most 64 tokens
+ * and K <= 8192, K is split inside the workgroups and no workspace is used.
+ * The workspace may be reused by the next call on the
  * same stream; concurrent calls on different streams need separate workspaces.
  */
 size_t potq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
