@@ -294,16 +294,20 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4_t *__rest
 #define POTQ_GEMM_MIN_GROUPS 4
 #endif
 
+constexpr int64_t kBigSplitBelow = 120, kBigSplitTarget = 160;
+
 // Number of K splits: enough workgroups to occupy the chip about three times over,
 // at least four scale groups per split, and only as many as the workspace holds.
 static int choose_splits(int64_t workgroups, int waves, int ks, int64_t G, int64_t M, int64_t N,
                          size_t workspace_bytes, bool big)
 {
-    // the many-token configuration moves M*N*4 bytes per split through the workspace: split only when
-    // fewer than ~60 % of the CUs would have a workgroup, and then just enough to cover them; the
-    // others aim at POTQ_GEMM_TARGET_WGS four-wavefront workgroups' worth of wavefronts
+    // the many-token configurations move M*N*4 bytes per split through the workspace: split only when
+    // fewer than about half of the CUs would have a workgroup (of eight wavefronts), and then just
+    // enough for 160 workgroups (more splits measured slower: 40.3 us with 8 against 30.0 us with 4
+    // on 5120 x 5120 at 256 tokens); the others aim at POTQ_GEMM_TARGET_WGS four-wavefront
+    // workgroups' worth of wavefronts
     const int64_t units = workgroups * waves / 4;
-    int64_t want = big ? (workgroups < 160 ? (320 + workgroups - 1) / workgroups : 1)
+    int64_t want = big ? (workgroups < kBigSplitBelow ? (kBigSplitTarget + workgroups - 1) / workgroups : 1)
                        : (POTQ_GEMM_TARGET_WGS + units - 1) / units;
     if (want > G / (POTQ_GEMM_MIN_GROUPS * ks)) want = G / (POTQ_GEMM_MIN_GROUPS * ks);
     if (want > 16) want = 16;
@@ -323,7 +327,7 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
     constexpr int CW = GC * KS;                       // scale groups per chunk
     const unsigned gx = (unsigned)((rowtiles + RS * RM - 1) / (RS * RM));
     const unsigned gy = (unsigned)((M + 16 * CN - 1) / (16 * CN));
-    int splits = workspace ? choose_splits((int64_t)gx * gy, WAVES, KS, G, M, N, workspace_bytes, CN >= 8) : 1;
+    int splits = workspace ? choose_splits((int64_t)gx * gy, WAVES, KS, G, M, N, workspace_bytes, M > 64) : 1;
     int per = (int)((G + splits - 1) / splits);
     per = (per + CW - 1) / CW * CW;                   // whole chunks
     splits = (int)((G + per - 1) / per);              // no empty split
@@ -342,22 +346,21 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
 }
 
 
-// Tile shapes for more than 64 tokens: (row tiles per wavefront, 16-token tiles per workgroup).
-// More row tiles per wavefront reuse each X fragment read from LDS more often (two row
-// tiles leave LDS as busy as the matrix pipe), more token tiles amortise the decode; both
-// cost output tiles, so the large shapes are only used where enough of them remain.
-static void big_tile(int64_t M, int64_t N, int *rm, int *cn)
+// More than 64 tokens: eight wavefronts per workgroup, two row tiles each (256 weight rows), and
+// either 128 tokens (the decode of a weight serves eight token tiles) or 64 (twice the workgroups).
+// Measured on the 13B shapes with 128 to 512 tokens: the wide tile wins when there are few tiles
+// (K is then split over workgroups anyway) or at least about one per compute unit; in between, the
+// narrow one does (e.g. 13824 x 5120 at 256 tokens: 51.6 us against 73.2 us; 5120 x 5120: 37.1 against 30.0).
+static bool wide_tile(int64_t M, int64_t N)
 {
-    if (M >= 512 && N >= 8192) { *rm = 4; *cn = 8; }
-    else if (M >= 512 || (M >= 256 && N >= 8192)) { *rm = 4; *cn = 4; }
-    else { *rm = 2; *cn = 8; }
+    const int64_t tiles = ((N + 255) / 256) * ((M + 127) / 128);
+    return tiles <= 64 || tiles >= 200;
 }
 
 static int64_t big_workgroups(int64_t M, int64_t N)
 {
-    int rm, cn;
-    big_tile(M, N, &rm, &cn);
-    return ((N / kTileRows + 4 * rm - 1) / (4 * rm)) * ((M + 16 * cn - 1) / (16 * cn));
+    const int64_t tokens = wide_tile(M, N) ? 128 : 64;
+    return ((N + 255) / 256) * ((M + tokens - 1) / tokens);
 }
 
 // Workspace that lets every supported shape use its preferred number of splits.
@@ -366,7 +369,9 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N)
     if (M <= 16) return 0;                            // the few-token kernel splits K inside the workgroup
     if (M <= 64) return (size_t)16 * M * N * sizeof(float);
     const int64_t workgroups = big_workgroups(M, N);
-    return workgroups < 160 ? (size_t)((320 + workgroups - 1) / workgroups) * M * N * sizeof(float) : 0;
+    return workgroups < kBigSplitBelow
+               ? (size_t)((kBigSplitTarget + workgroups - 1) / workgroups) * M * N * sizeof(float)
+               : 0;
 }
 
 template <int BITS, bool IS_INT>
@@ -389,14 +394,10 @@ static void launch_gemm(const void *codes, const void *scales, const void *zeros
         else
             launch_gemm_cfg<BITS, IS_INT, 4, 1, 4, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
-        int rm, cn;
-        big_tile(M, N, &rm, &cn);
-        if (rm == 4 && cn == 8)
-            launch_gemm_cfg<BITS, IS_INT, 4, 4, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
-        else if (rm == 4)
-            launch_gemm_cfg<BITS, IS_INT, 4, 4, 4, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        if (wide_tile(M, N))
+            launch_gemm_cfg<BITS, IS_INT, 8, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else
-            launch_gemm_cfg<BITS, IS_INT, 4, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     }
 }
 
