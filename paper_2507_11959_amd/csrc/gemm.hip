@@ -28,9 +28,6 @@ namespace potq {
 #ifndef POTQ_GEMM_WPE
 #define POTQ_GEMM_WPE 2
 #endif
-#ifndef POTQ_GEMM_KSPLIT
-#define POTQ_GEMM_KSPLIT 1
-#endif
 
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC, int KS>
 __global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu((RM * CN == 16) ? POTQ_GEMM_WPE : 1, 8)))
@@ -378,21 +375,22 @@ template <int BITS, bool IS_INT>
 static void launch_gemm(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                         int64_t M, int64_t N, int64_t K, int group, void *ws, size_t ws_bytes, hipStream_t stream)
 {
-    // Few tokens: not enough output tiles for the chip.  With short rows (K <= 8192) the eight
-    // wavefronts of a workgroup split K between them (no second kernel, no workspace traffic:
-    // 5-16 % faster at K = 5120); with long rows every workgroup would re-read too much of X, and
-    // K is split over workgroups instead, through the caller's workspace.
-    const bool in_group_split = POTQ_GEMM_KSPLIT && K <= 8192;
+    // 17 to 64 tokens: not enough output tiles for the chip; eight wavefronts per workgroup.
+    // Small, short matrices (K <= 8192, N <= 8192) let pairs of wavefronts split K inside the
+    // workgroup and add their tiles through LDS (no second kernel, no workspace traffic: 16.3 us
+    // against 19.3 us on 5120 x 5120 at 64 tokens); the others give every wavefront one row tile
+    // and split K over workgroups through the caller's workspace (25.8 against 29.8 us on 13824 x 5120).
+    const bool in_group_split = K <= 8192 && N <= 8192;
     if (M <= 32) {
         if (in_group_split)
-            launch_gemm_cfg<BITS, IS_INT, 8, 1, 2, 2, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            launch_gemm_cfg<BITS, IS_INT, 8, 2, 2, 1, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else
-            launch_gemm_cfg<BITS, IS_INT, 4, 1, 2, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            launch_gemm_cfg<BITS, IS_INT, 8, 1, 2, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else if (M <= 64) {
         if (in_group_split)
-            launch_gemm_cfg<BITS, IS_INT, 8, 1, 4, 1, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else
-            launch_gemm_cfg<BITS, IS_INT, 4, 1, 4, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            launch_gemm_cfg<BITS, IS_INT, 8, 1, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
         if (wide_tile(M, N))
             launch_gemm_cfg<BITS, IS_INT, 8, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
