@@ -315,3 +315,28 @@ def test_empty_inputs_are_accepted(potq):
     torch.cuda.synchronize()
     assert torch.all(y == 0)
     assert e8.numel() == 0 and e16.numel() == 0
+
+
+# One case per kernel configuration the GEMM dispatcher can choose (token count x matrix size),
+# each with and without a workspace, PoT and uniform, so that no template instance goes untested.
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("M,N,K", [
+    (9, 1024, 2304),       # few-token kernel, 8 wavefronts, ragged last round (18 groups)
+    (16, 12304, 384),      # few-token kernel, 16 wavefronts (tall matrix), surplus wavefronts in the last workgroup
+    (24, 80, 1280),        # 17-32 tokens, K split inside the workgroup
+    (24, 32, 11008),       # 17-32 tokens, long rows: one row tile per wavefront, K split over workgroups
+    (30, 8208, 256),       # 17-32 tokens, tall matrix
+    (48, 8208, 384),       # 33-64 tokens, tall matrix
+    (64, 48, 9216),        # 33-64 tokens, long rows
+    (100, 16640, 128),     # narrow 256x64 tile (65 tiles)
+    (130, 4112, 256),      # wide 256x128 tile, ragged token tile
+])
+def test_gemm_every_dispatch_configuration(potq, M, N, K, is_int):
+    bits = 3
+    packed, S, Z = _gemv_inputs(2000 + M + N, N, K, bits, is_int)
+    X = workloads.activations(2100 + M, M, K)
+    want = oracle.gemm(packed, S, Z, X, K, bits, 128, nthreads=8)
+    for use_ws in (True, False):
+        got = _run_gemm(potq, packed, S, Z, X, K, bits, use_workspace=use_ws)
+        e, nw, nfloor = rel_err(got, want, K)
+        assert e <= REL_TOL, (use_ws, e, nw, nfloor)
