@@ -20,28 +20,44 @@ namespace potq {
 // the partial products of the 16 rows.  Products are exact, sums fp32.
 // `s`/`z` serve columns 0..63, `s_hi`/`z_hi` columns 64..127 (the same values for group size 128).
 // `bfrag(j)` returns the B operand of step j (j = 0..15: columns 8j .. 8j+7 of the group).
-template <int BITS, bool IS_INT, typename BFrag>
+template <int BITS, bool IS_INT, bool COL0, typename BFrag>
 __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, uint32_t z, uint32_t s_hi,
                                            uint32_t z_hi, bool two_scales, BFrag bfrag, float4_t (&acc)[4])
 {
     Decoder<BITS, IS_INT> dec;
+    // The B operand of a block's four steps.  With COL0 only column 0 of the result is used (the
+    // GEMV: x in every column), so only the lanes of column 0 fetch it -- an LDS read returns 16
+    // bytes per active lane, and the other 60 lanes' share is wasted bandwidth.  The fetch of the
+    // next block is issued before the current block is expanded.
+    const bool fetches = !COL0 || (threadIdx.x & 15) == 0;
+    u32x4 xq[4], xn[4];
+    if (fetches) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xq[i] = bfrag(i);
+    }
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         if (b == 0 || (b == 2 && two_scales))       // wave-uniform: the second table exists only for group size 64
             dec.set_group(b ? s_hi : s, b ? z_hi : z);
+        if (b < 3 && fetches) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xn[i] = bfrag((b + 1) * 4 + i);
+        }
         uint32_t w[BITS];
 #pragma unroll
         for (int j = 0; j < BITS; ++j) w[j] = L[j][b];
         dec.set_block(w);
 #pragma unroll
         for (int m = 0; m < 8; m += 2) {
-            const u32x4 xv = bfrag(b * 4 + m / 2);  // columns 32b + 4m .. + 7
+            const u32x4 xv = xq[m / 2];             // columns 32b + 4m .. + 7
             uint32_t e0, o0, e1, o1;
             dec.get(m, e0, o0);
             dec.get(m + 1, e1, o1);
             const half8_t av = __builtin_bit_cast(half8_t, (u32x4{e0, o0, e1, o1}));
             acc[m / 2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, __builtin_bit_cast(half8_t, xv), acc[m / 2], 0, 0, 0);
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xq[i] = xn[i];
     }
 }
 
@@ -57,7 +73,7 @@ constexpr int kGemvWaves = POTQ_GEMV_WAVES;
 // of K in flight at once), tall matrices want S = 1 or 2 (long-lived wavefronts,
 // no cross-wavefront sums).  The codes of the next round are requested before
 // the current one is expanded, and the first request goes out before x is staged.
-template <int BITS, bool IS_INT, int S, bool G64>
+template <int BITS, bool IS_INT, int S, bool G64, bool COL0>
 __device__ __forceinline__ void gemv_tile16_body(
     const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
     const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K, int64_t block)
@@ -163,7 +179,7 @@ __device__ __forceinline__ void gemv_tile16_body(
             zo = zo_hi = 0u;
         }
         const u32x4 *xg = g < G ? xs + g * kXRun : zero_block;
-        gemv_group<BITS, IS_INT>(L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xg[j]; }, acc);
+        gemv_group<BITS, IS_INT, COL0>(L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xg[j]; }, acc);
         g = gn;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
@@ -197,12 +213,12 @@ __device__ __forceinline__ void gemv_tile16_body(
     }
 }
 
-template <int BITS, bool IS_INT, int S, bool G64>
+template <int BITS, bool IS_INT, int S, bool G64, bool COL0>
 __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
     const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K)
 {
-    gemv_tile16_body<BITS, IS_INT, S, G64>(codes, scales, zeros, x, y, rowtiles, K, blockIdx.x);
+    gemv_tile16_body<BITS, IS_INT, S, G64, COL0>(codes, scales, zeros, x, y, rowtiles, K, blockIdx.x);
 }
 
 // Several matrices that consume the same activation vector (q/k/v, gate/up) in one launch:
@@ -219,13 +235,13 @@ struct GemvBatch {
     int count;
 };
 
-template <int BITS, bool IS_INT, int S, bool G64>
+template <int BITS, bool IS_INT, int S, bool G64, bool COL0>
 __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_batch_kernel(
     const GemvBatch batch, const u32x4 *__restrict__ x, int K)
 {
     int i = 0;
     while (i + 1 < batch.count && blockIdx.x >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
-    gemv_tile16_body<BITS, IS_INT, S, G64>(batch.codes[i], batch.scales[i], batch.zeros[i], x, batch.y[i],
+    gemv_tile16_body<BITS, IS_INT, S, G64, COL0>(batch.codes[i], batch.scales[i], batch.zeros[i], x, batch.y[i],
                                            batch.rowtiles[i], K, blockIdx.x - batch.first_block[i]);
 }
 
@@ -364,7 +380,7 @@ __global__ __launch_bounds__(kFewWaves * kWave) void gemm_fewtok_kernel(
             so = so_hi = 0x3C00u;
             zo = zo_hi = 0u;
         }
-        gemv_group<BITS, IS_INT>(cur.L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xq[j & 3][j * 16]; }, acc);
+        gemv_group<BITS, IS_INT, false>(cur.L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xq[j & 3][j * 16]; }, acc);
 #pragma unroll
         for (int d = 0; d + 1 < kFewDepth; ++d) q[d] = q[d + 1];
         q[kFewDepth - 1] = nx;
@@ -437,6 +453,11 @@ size_t gemv_lds_bytes(int64_t K)
     return (size_t)(K / kTileCols) * kXRun * 16 + 256 + kGemvWaves * kTileRows * sizeof(float);
 }
 
+// Long rows (several rounds per wavefront) let only the lanes of result column 0 read x from
+// LDS (4096 x 11008: 7.7 -> 7.0 us, 8192 x 28672: 23.4 -> 20.4 us); with one or two rounds per
+// wavefront the masked reads measured slower (11008 x 4096: 6.8 -> 8.0 us) and all lanes read.
+static bool gemv_col0_fetch(int64_t K) { return K > 8192; }
+
 // Eight wavefronts per tile measured best or equal on every decoder shape (all of a row's
 // groups in flight at once); short rows take fewer so that no wavefront idles.
 static int gemv_split(int64_t G)
@@ -453,29 +474,29 @@ static void launch_gemv(const void *codes, const void *scales, const void *zeros
     const int64_t rowtiles = N / kTileRows;
     const size_t lds = gemv_lds_bytes(K);
     const int64_t G = K / kTileCols;
-#define POTQ_LAUNCH_GEMV(SPLIT)                                                                                    \
+#define POTQ_LAUNCH_GEMV(SPLIT, COL0)                                                                              \
     do {                                                                                                           \
         const dim3 grid((unsigned)((rowtiles + (kGemvWaves / SPLIT) - 1) / (kGemvWaves / SPLIT)));                 \
         if (group == 64)                                                                                           \
-            hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT, true>), grid, dim3(kGemvWaves * kWave),    \
-                               lds, stream, (const u32x4 *)codes, (const uint16_t *)scales,                        \
-                               (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K);        \
+            hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT, true, COL0>), grid,                        \
+                               dim3(kGemvWaves * kWave), lds, stream, (const u32x4 *)codes,                        \
+                               (const uint16_t *)scales, (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, \
+                               rowtiles, (int)K);                                                                  \
         else                                                                                                       \
-            hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT, false>), grid, dim3(kGemvWaves * kWave),   \
-                               lds, stream, (const u32x4 *)codes, (const uint16_t *)scales,                        \
-                               (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K);        \
+            hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT, false, COL0>), grid,                       \
+                               dim3(kGemvWaves * kWave), lds, stream, (const u32x4 *)codes,                        \
+                               (const uint16_t *)scales, (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, \
+                               rowtiles, (int)K);                                                                  \
     } while (0)
     // Eight wavefronts per tile measured best or equal on every decoder shape (all of a
     // row's groups in flight at once); short rows take fewer so that no wavefront idles.
-#ifdef POTQ_GEMV_SPLIT
-    POTQ_LAUNCH_GEMV(POTQ_GEMV_SPLIT);
-#else
     const int split = gemv_split(G);
-    if (split == 8 && kGemvWaves >= 8) POTQ_LAUNCH_GEMV((kGemvWaves >= 8 ? 8 : 1));
-    else if (split == 4) POTQ_LAUNCH_GEMV(4);
-    else if (split == 2) POTQ_LAUNCH_GEMV(2);
-    else POTQ_LAUNCH_GEMV(1);
-#endif
+    if (split == 8 && kGemvWaves >= 8) {
+        if (gemv_col0_fetch(K)) POTQ_LAUNCH_GEMV((kGemvWaves >= 8 ? 8 : 1), true);
+        else POTQ_LAUNCH_GEMV((kGemvWaves >= 8 ? 8 : 1), false);
+    } else if (split == 4) POTQ_LAUNCH_GEMV(4, false);
+    else if (split == 2) POTQ_LAUNCH_GEMV(2, false);
+    else POTQ_LAUNCH_GEMV(1, false);
 #undef POTQ_LAUNCH_GEMV
 }
 
@@ -486,19 +507,21 @@ static void launch_gemv_batch(const GemvBatch &b, unsigned blocks, const void *x
                               hipStream_t stream)
 {
     const size_t lds = gemv_lds_bytes(K);
-#define POTQ_LAUNCH_GEMVB(SPLIT)                                                                                   \
+#define POTQ_LAUNCH_GEMVB(SPLIT, COL0)                                                                             \
     do {                                                                                                           \
         if (group == 64)                                                                                           \
-            hipLaunchKernelGGL((gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, true>), dim3(blocks),                \
+            hipLaunchKernelGGL((gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, true, COL0>), dim3(blocks),          \
                                dim3(kGemvWaves * kWave), lds, stream, b, (const u32x4 *)x, (int)K);                \
         else                                                                                                       \
-            hipLaunchKernelGGL((gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, false>), dim3(blocks),               \
+            hipLaunchKernelGGL((gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, false, COL0>), dim3(blocks),         \
                                dim3(kGemvWaves * kWave), lds, stream, b, (const u32x4 *)x, (int)K);                \
     } while (0)
-    if (split == 8 && kGemvWaves >= 8) POTQ_LAUNCH_GEMVB((kGemvWaves >= 8 ? 8 : 1));
-    else if (split == 4) POTQ_LAUNCH_GEMVB(4);
-    else if (split == 2) POTQ_LAUNCH_GEMVB(2);
-    else POTQ_LAUNCH_GEMVB(1);
+    if (split == 8 && kGemvWaves >= 8) {
+        if (gemv_col0_fetch(K)) POTQ_LAUNCH_GEMVB((kGemvWaves >= 8 ? 8 : 1), true);
+        else POTQ_LAUNCH_GEMVB((kGemvWaves >= 8 ? 8 : 1), false);
+    } else if (split == 4) POTQ_LAUNCH_GEMVB(4, false);
+    else if (split == 2) POTQ_LAUNCH_GEMVB(2, false);
+    else POTQ_LAUNCH_GEMVB(1, false);
 #undef POTQ_LAUNCH_GEMVB
 }
 
