@@ -192,8 +192,8 @@ int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f1
  * in a fixed order in a second small kernel (results stay reproducible).
  * potq_gemm_workspace_bytes() returns the size that allows the preferred split
  * (0 when no split would be used); a NULL or smaller workspace is valid and
- * only means fewer splits; with at most 16 tokens, and with at most 64 tokens
- * and K <= 8192, K is split inside the workgroups and no workspace is used.
+ * only means fewer splits.  With at most 16 tokens K is always split inside the
+ * workgroups and the workspace is never touched (the size query returns 0).
  * The workspace may be reused by the next call on the
  * same stream; concurrent calls on different streams need separate workspaces.
  */
