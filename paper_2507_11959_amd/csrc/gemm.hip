@@ -345,13 +345,14 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
 
 // More than 64 tokens: eight wavefronts per workgroup, two row tiles each (256 weight rows), and
 // either 128 tokens (the decode of a weight serves eight token tiles) or 64 (twice the workgroups).
-// Measured on the 13B shapes with 128 to 512 tokens: the wide tile wins when there are few tiles
-// (K is then split over workgroups anyway) or at least about one per compute unit; in between, the
-// narrow one does (e.g. 13824 x 5120 at 256 tokens: 51.6 us against 73.2 us; 5120 x 5120: 37.1 against 30.0).
+// Measured on the 13B shapes with 128 to 2048 tokens: the wide tile wins when there are few tiles
+// (K is then split over workgroups, which is cheap while M*N is small) or enough of them to do
+// without a split; in between, the narrow one does (13824 x 5120 at 256 tokens, 108 wide tiles:
+// 51.6 us against 73.2 us; 5120 x 5120 at 1024 tokens, 160 wide tiles: 97.2 us against 72.1 us).
 static bool wide_tile(int64_t M, int64_t N)
 {
     const int64_t tiles = ((N + 255) / 256) * ((M + 127) / 128);
-    return tiles <= 64 || tiles >= 200;
+    return tiles <= 64 || tiles >= kBigSplitBelow;
 }
 
 static int64_t big_workgroups(int64_t M, int64_t N)
