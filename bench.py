@@ -348,6 +348,63 @@ def main() -> int:
         del keep, steps_
         torch.cuda.empty_cache()
 
+        # Llama-2-70B layer (GQA shapes): stand-alone dequant of all seven matrices in one launch at 2 and 3
+        # bits (four rotating code sets: 0.9 / 1.3 GB of codes), and the batch-1 GEMV of its four distinct shapes
+        big = {}
+        outs70 = [torch.empty((N, K), dtype=torch.float16, device=dev) for _, N, K in workloads.LLAMA2_70B_LAYER]
+        for bb in (2, 3):
+            nb = sum(workloads.algorithmic_bytes_dequant(N, K, bb, G) for _, N, K in workloads.LLAMA2_70B_LAYER)
+            sets70, keep70 = [], []
+            for _ in range(4):
+                ms_ = []
+                for j, (_, N, K) in enumerate(workloads.LLAMA2_70B_LAYER):
+                    c = torch.randint(0, 256, (N, K * bb // 8), dtype=torch.uint8, device=dev, generator=gen)
+                    ms_.append((c, to_dev(workloads.pot_scales(workloads.seed_of(3, j, 1), N, K, G)), None, outs70[j], K, bb))
+                keep70.append(ms_)
+                sets70.append(binding.make_batch(ms_))
+
+            def step70():
+                turn[0] += 1
+                check(lib.pot_dequant_batch(sets70[turn[0] % 4], 7, bb, G, stream))
+
+            ms70 = _time_steps(torch, step70, 24, 4)
+            big[f"dequant_{bb}bit"] = {"us": round(ms70 * 1e3, 1), "GBps": round(nb / ms70 / 1e6, 1),
+                                       "pct_hbm_peak": round(nb / ms70 / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+            del sets70, keep70
+            torch.cuda.empty_cache()
+        del outs70
+        torch.cuda.empty_cache()
+        g70 = []
+        for (N, K) in ((8192, 8192), (1024, 8192), (28672, 8192), (8192, 28672)):
+            nbytes = workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
+            R = rotate(nbytes)
+            cs = [torch.randint(0, 256, (N, K * b3 // 8), dtype=torch.uint8, device=dev, generator=gen) for _ in range(R)]
+            sc_ = to_dev(workloads.pot_scales(workloads.seed_of(3, 0, 1), N, K, G))
+            S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(3, 0, 3), N, K, b3, G)
+            Sd_, Zd_ = to_dev(S_h), to_dev(Z_h)
+            x = to_dev(workloads.activations(workloads.seed_of(3, 0, 2), 1, K)[0])
+            y = torch.empty((N,), dtype=torch.float16, device=dev)
+
+            def pot70():
+                for c in cs:
+                    check(lib.pot_gemv(c.data_ptr(), sc_.data_ptr(), x.data_ptr(), y.data_ptr(), N, K, b3, G, 1, stream))
+
+            def int70():
+                for c in cs:
+                    check(lib.int_gemv(c.data_ptr(), Sd_.data_ptr(), Zd_.data_ptr(), x.data_ptr(), y.data_ptr(), N, K,
+                                       b3, G, 1, stream))
+
+            reps = max(2, 64 // R)
+            us_p = _time_steps(torch, pot70, reps, 1) * 1e3 / R
+            us_i = _time_steps(torch, int70, reps, 1) * 1e3 / R
+            g70.append({"shape": f"{N}x{K}", "us": round(us_p, 2), "GBps": round(nbytes / us_p / 1e3, 1),
+                        "pct_hbm_peak": round(nbytes / us_p / 1e3 / HBM_PEAK_GBPS * 100, 1), "int_us": round(us_i, 2),
+                        "pot_speedup_vs_int": round(us_i / us_p, 3), "buffers_rotated": R})
+            del cs
+            torch.cuda.empty_cache()
+        big["gemv_3bit"] = g70
+        extras["llama2_70b_layer"] = big
+
         # fused MFMA GEMM, 3-bit, 13B shapes; the calls rotate through enough copies of the weight codes
         # (random bytes are valid codes) that they are read from HBM, not from the 256 MB last-level cache
         gemm = []
