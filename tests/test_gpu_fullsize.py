@@ -177,3 +177,26 @@ def test_second_workload_llama30b_layer(potq, bits):
             want = oracle.gemm(host[i][0], host[i][1], None, x, K, bits, G, nthreads=_threads())[0]
             e, nw, nfloor = rel_err(host_bits(y), want, K)
             assert e <= REL_TOL, (layer[i][0], e, nw, nfloor)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_dequant_output_beyond_four_gibibytes(potq, bits):
+    # 36864 x 65536 = 2.4 G weights: element indices pass 2^31 and output byte offsets pass 2^32, so any
+    # 32-bit index arithmetic in the kernel or its launch would show here.  Sampled rows (first, last, around the
+    # 2^31-element and 2^32-byte marks) against the oracle; codes are random bytes drawn on the device.
+    N, K = 36864, 65536
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(77 + bits)
+    codes = torch.randint(0, 256, (N, K * bits // 8), dtype=torch.uint8, device="cuda:0", generator=gen)
+    scales_h = workloads.pot_scales(workloads.seed_of(9, bits, 1), N, K, G)
+    scales = dev(scales_h)
+    out = potq.pot_dequant(codes, scales, K, bits, G)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 1, N - 2, N - 1], [32766, 32767, 32768, 32769],      # 2^31 elements, 2^32 bytes
+                                     [16383, 16384], np.random.default_rng(bits).integers(0, N, 24)]))
+    idx = torch.from_numpy(rows).to("cuda:0")
+    want = oracle.pot_dequant(codes[idx].cpu().numpy(), scales_h[rows], K, bits, G, nthreads=_threads())
+    assert np.array_equal(host_bits(out[idx]), want)
+    # every row obeys the format invariants (checked on the GPU in slices to bound memory)
+    for r0 in range(0, N, 4096):
+        _invariants(out[r0:r0 + 4096], scales[r0:r0 + 4096], True, bits)
