@@ -1,8 +1,11 @@
 // Fused de-quantise + GEMM on the matrix cores (tiled layout), gfx950.
 //
-// Y[m,n] = sum_k X[m,k] W~[n,k].  A workgroup of WAVES wavefronts owns
-// WAVES*RM 16-row tiles of W and a strip of 16*CN tokens, and walks K in chunks
-// of GC scale groups (128 columns each), one workgroup barrier per chunk.
+// Y[m,n] = sum_k X[m,k] W~[n,k], for more than 16 tokens (up to 16 tokens take
+// the kernel in gemv.hip that is built like the GEMV).  A workgroup of WAVES
+// wavefronts owns (WAVES/KS)*RM 16-row tiles of W and a strip of 16*CN tokens,
+// and walks K in chunks of GC*KS scale groups (128 columns each), one workgroup
+// barrier per chunk; the KS wavefronts that share row tiles take GC groups of
+// every chunk each and add their tiles through LDS at the end.
 //
 //  - Weights never touch LDS.  Lane (r = lane % 16, q = lane / 16) fetches the
 //    32 codes of row r, column block q of the group (`bits` dwords), builds the
@@ -15,9 +18,10 @@
 //    B fragment is one conflict-free ds_read_b128 per lane and is reused by all
 //    RM row tiles of the wavefront.
 //  - Accumulation is fp32 in the MFMA accumulators; one rounding to fp16 at the end.
-//  - Few-token shapes do not have enough output tiles to occupy 256 CUs, so K is
-//    split over blockIdx.z: every split writes its fp32 sums to the caller's
-//    workspace and a small second kernel adds them in a fixed order.
+//  - Shapes without enough output tiles to occupy 256 CUs split K: inside the
+//    workgroup (KS > 1), and/or over blockIdx.z, where every split writes its
+//    fp32 sums to the caller's workspace and a small second kernel adds them in
+//    a fixed order.
 #include "potq_device.hpp"
 
 namespace potq {

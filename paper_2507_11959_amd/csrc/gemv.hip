@@ -9,6 +9,9 @@
 // run on the otherwise idle matrix pipe (the vector ALU is the scarce resource
 // of this kernel): x, held in LDS, is the B operand replicated in all columns.
 // Partial sums are combined in a fixed order, so results are reproducible.
+//
+// The same file holds the fused GEMM for up to 16 tokens (gemm_fewtok_kernel),
+// which keeps this lane-owns-a-group scheme and makes the tokens the B operand.
 #include "potq_device.hpp"
 
 namespace potq {
