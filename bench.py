@@ -196,7 +196,7 @@ def main() -> int:
             "us_per_launch": round(ms * 1e3 / launches, 3),
             # HBM bytes per launch from rocprofv3 FETCH_SIZE (x2.000) + WRITE_SIZE (x1.000), factors calibrated
             # on a 256 MiB copy; figures and commands in profiles/pot_dequant_batch_b2_llama7b_layer.md
-            "traffic": 458579364,
+            "traffic": 458576323,
         },
     }
 
