@@ -466,13 +466,13 @@ def main() -> int:
         torch.cuda.empty_cache()
 
         # Step 1 scale search (Algorithm 1) on one 4096x4096 fp16 matrix, 3-bit, group 128: plain vector-ALU
-        # work, about ten lane operations per weight and multiplier (200 multipliers)
+        # work, about eight lane operations per weight and multiplier (200 multipliers)
         Wq = to_dev(workloads.weights_f16(workloads.seed_of(0, 0, 4), 4096, 4096))
         qc = torch.empty((4096, 4096 * b3 // 8), dtype=torch.uint8, device=dev)
         qs = torch.empty((4096, 4096 // G), dtype=torch.float16, device=dev)
         qa = (Wq.data_ptr(), qc.data_ptr(), qs.data_ptr(), 4096, 4096, b3, G, stream)
         ms_q = _time_steps(torch, lambda: check(lib.pot_quantize(*qa)), 10, 2)
-        lane_ops = 4096.0 * 4096 * 200 * 10
+        lane_ops = 4096.0 * 4096 * 200 * 8
         extras["pot_quantize_3bit_4096x4096"] = {
             "ms": round(ms_q, 4), "Mweights_per_s": round(4096 * 4096 / ms_q / 1e3, 1),
             "bound": "alu", "T_lane_ops_per_s": round(lane_ops / ms_q / 1e9, 2),

@@ -74,12 +74,12 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
         }
         float q = 0.f;
         for (int k = 0; k < group; ++k) {
-            const float x = w[gi][k];
-            const float a = fabsf(x);
+            const float a = fabsf(w[gi][k]);
             float mag = mag_of[0];
 #pragma unroll
             for (int e = 1; e <= qmax; ++e) mag = a >= thr[e] ? mag_of[e] : mag;
-            const float d = x - (x < 0.f ? -mag : mag);
+            // (w - sign(w) mag)^2 = (|w| - mag)^2 exactly: the two differences are negatives of each other
+            const float d = a - mag;
             q = __builtin_fmaf(d, d, q);
         }
         qs[gi][i - 1] = q;
