@@ -407,11 +407,17 @@ static void launch_gemm(const void *codes, const void *scales, const void *zeros
 hipError_t run_gemm_fewtok(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 
+bool gemv_multi_ok(int64_t M, int64_t N, int64_t K, int group);
+hipError_t run_gemv_multi(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
+                          void *Y, int64_t M, int64_t N, int64_t K, int bits, hipStream_t stream);
+
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, void *ws, size_t ws_bytes,
                            hipStream_t stream)
 {
     // up to 16 tokens: the kernel built like the GEMV (one table per 128 weights, no cross-lane code traffic)
+    // two to four tokens: the GEMV kernel with one activation vector per result column
+    if (gemv_multi_ok(M, N, K, group)) return run_gemv_multi(is_int, codes, scales, zeros, X, Y, M, N, K, bits, stream);
     if (M <= 16)
         return run_gemm_fewtok(is_int, codes, scales, zeros, X, Y, M, N, K, bits, group, stream);
     if (is_int) {

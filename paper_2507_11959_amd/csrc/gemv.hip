@@ -23,16 +23,16 @@ namespace potq {
 // the partial products of the 16 rows.  Products are exact, sums fp32.
 // `s`/`z` serve columns 0..63, `s_hi`/`z_hi` columns 64..127 (the same values for group size 128).
 // `bfrag(j)` returns the B operand of step j (j = 0..15: columns 8j .. 8j+7 of the group).
-template <int BITS, bool IS_INT, bool COL0, typename BFrag>
+template <int BITS, bool IS_INT, int NCOL, typename BFrag>
 __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, uint32_t z, uint32_t s_hi,
                                            uint32_t z_hi, bool two_scales, BFrag bfrag, float4_t (&acc)[4])
 {
     Decoder<BITS, IS_INT> dec;
-    // The B operand of a block's four steps.  With COL0 only column 0 of the result is used (the
-    // GEMV: x in every column), so only the lanes of column 0 fetch it -- an LDS read returns 16
-    // bytes per active lane, and the other 60 lanes' share is wasted bandwidth.  The fetch of the
+    // The B operand of a block's four steps.  With NCOL > 0 only the first NCOL columns of the
+    // result are used (the GEMV: column 0), so only the lanes of those columns fetch it -- an LDS
+    // read returns 16 bytes per active lane, and the other lanes' share is wasted bandwidth.  The fetch of the
     // next block is issued before the current block is expanded.
-    const bool fetches = !COL0 || (threadIdx.x & 15) == 0;
+    const bool fetches = NCOL == 0 || (int)(threadIdx.x & 15) < NCOL;
     u32x4 xq[4], xn[4];
     if (fetches) {
 #pragma unroll
@@ -76,10 +76,14 @@ constexpr int kGemvWaves = POTQ_GEMV_WAVES;
 // of K in flight at once), tall matrices want S = 1 or 2 (long-lived wavefronts,
 // no cross-wavefront sums).  The codes of the next round are requested before
 // the current one is expanded, and the first request goes out before x is staged.
-template <int BITS, bool IS_INT, int S, bool G64, bool COL0>
+// MT > 1: the same kernel for MT activation vectors at once (a GEMM with two to four tokens: rows
+// m < tokens of x, K apart; results y[m * ystride + n]).  Vector m is the B operand of column m, so the
+// matrix is decoded once and every vector costs only LDS space: column m of the MFMA result is its y.
+template <int BITS, bool IS_INT, int S, bool G64, bool COL0, int MT = 1>
 __device__ __forceinline__ void gemv_tile16_body(
     const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
-    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K, int64_t block)
+    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K, int64_t block, int tokens = 1,
+    int64_t ystride = 0)
 {
     constexpr int gs = G64 ? 1 : 0;
     // gs = 0: one scale per 128 columns; gs = 1: one per 64 (two per tile row)
@@ -118,8 +122,8 @@ __device__ __forceinline__ void gemv_tile16_body(
     // re-reads the last group (valid memory), takes the scale 1.0 (finite
     // weights) and multiplies by a block of zeros instead of x.
     const int rounds = (G + kStep - 1) / kStep;
-    u32x4 *zero_block = smem + (K / kTileCols) * kXRun; // 16 uint4 of zeros
-    float *red = (float *)(zero_block + 16);            // 8 wavefronts x 16 partial sums
+    u32x4 *zero_block = smem + MT * (K / kTileCols) * kXRun;   // 16 uint4 of zeros
+    float *red = (float *)(zero_block + 16);            // 8 wavefronts x MT x 16 partial sums
 
     int g = part * 4 + t;
     u32x4 L[BITS];
@@ -138,7 +142,16 @@ __device__ __forceinline__ void gemv_tile16_body(
         }
     }
 
-    for (int i = tid; i < K / 8; i += kGemvWaves * kWave) xs[(i >> 4) * kXRun + (i & 15)] = x[i];
+    if (MT == 1) {
+        for (int i = tid; i < K / 8; i += kGemvWaves * kWave) xs[(i >> 4) * kXRun + (i & 15)] = x[i];
+    } else {
+        // vector m occupies runs m*G .. m*G + G-1; vectors past `tokens` count as zero
+        const int per = K / 8;
+        for (int i = tid; i < MT * per; i += kGemvWaves * kWave) {
+            const int m = i / per, o = i - m * per;
+            xs[(m * G + (o >> 4)) * kXRun + (o & 15)] = m < tokens ? x[i] : u32x4{0u, 0u, 0u, 0u};
+        }
+    }
     if (tid < 16) zero_block[tid] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
@@ -146,6 +159,9 @@ __device__ __forceinline__ void gemv_tile16_body(
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = float4_t{0.f, 0.f, 0.f, 0.f};
     for (int round = 0; round < rounds; ++round) {
+        // a wavefront whose four groups of this round all lie past the end of the row is done
+        // (wave-uniform; K = 5120 has 40 groups for 64 slots of two rounds)
+        if (round * kStep + part * 4 >= G) break;
         const int gn = g + kStep;
         u32x4 Ln[BITS];
         uint32_t sn = 0, zn = 0;
@@ -181,8 +197,11 @@ __device__ __forceinline__ void gemv_tile16_body(
             so = so_hi = 0x3C00u;
             zo = zo_hi = 0u;
         }
-        const u32x4 *xg = g < G ? xs + g * kXRun : zero_block;
-        gemv_group<BITS, IS_INT, COL0>(L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xg[j]; }, acc);
+        // column c of the B operand: vector c (vector 0 in the columns that are not used)
+        const int vec = (MT > 1 && r < MT) ? r : 0;
+        const u32x4 *xg = g < G ? xs + (vec * G + g) * kXRun : zero_block;
+        gemv_group<BITS, IS_INT, (MT > 1 ? MT : (COL0 ? 1 : 0))>(L, so, zo, so_hi, zo_hi, gs != 0,
+                                                               [&](int j) { return xg[j]; }, acc);
         g = gn;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
@@ -203,16 +222,16 @@ __device__ __forceinline__ void gemv_tile16_body(
         }
         return;
     }
-    if (r == 0) *(float4_t *)(red + wave * kTileRows + 4 * t) = part_sum;
+    if (r < MT) *(float4_t *)(red + (wave * MT + r) * kTileRows + 4 * t) = part_sum;
     __syncthreads();
-    if (tid < R * kTileRows) {
-        const int tile = tid / kTileRows, rr = tid % kTileRows;
+    if (tid < R * MT * kTileRows) {
+        const int tile = tid / (MT * kTileRows), m = (tid / kTileRows) % MT, rr = tid % kTileRows;
         const int64_t rt = block * R + tile;
         float sum = 0.f;
 #pragma unroll
-        for (int p = 0; p < S; ++p) sum += red[(tile * S + p) * kTileRows + rr];
+        for (int p = 0; p < S; ++p) sum += red[((tile * S + p) * MT + m) * kTileRows + rr];
         const _Float16 h = (_Float16)sum;
-        if (rt < rowtiles) y[rt * kTileRows + rr] = __builtin_bit_cast(uint16_t, h);
+        if (rt < rowtiles && m < tokens) y[m * ystride + rt * kTileRows + rr] = __builtin_bit_cast(uint16_t, h);
     }
 }
 
@@ -383,7 +402,7 @@ __global__ __launch_bounds__(kFewWaves * kWave) void gemm_fewtok_kernel(
             so = so_hi = 0x3C00u;
             zo = zo_hi = 0u;
         }
-        gemv_group<BITS, IS_INT, false>(cur.L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xq[j & 3][j * 16]; }, acc);
+        gemv_group<BITS, IS_INT, 0>(cur.L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xq[j & 3][j * 16]; }, acc);
 #pragma unroll
         for (int d = 0; d + 1 < kFewDepth; ++d) q[d] = q[d + 1];
         q[kFewDepth - 1] = nx;
@@ -447,6 +466,63 @@ hipError_t run_gemm_fewtok(bool is_int, const void *codes, const void *scales, c
         if (bits == 4) launch_gemm_fewtok<4, false>(codes, scales, zeros, X, Y, M, N, K, group, stream);
         else if (bits == 3) launch_gemm_fewtok<3, false>(codes, scales, zeros, X, Y, M, N, K, group, stream);
         else launch_gemm_fewtok<2, false>(codes, scales, zeros, X, Y, M, N, K, group, stream);
+    }
+    return hipGetLastError();
+}
+
+// Two to four tokens through the GEMV kernel (eight wavefronts per tile, group size 128).
+template <int BITS, bool IS_INT, int MT>
+__global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_multi_kernel(
+    const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
+    const u32x4 *__restrict__ X, uint16_t *__restrict__ Y, int64_t rowtiles, int K, int tokens, int64_t N)
+{
+    gemv_tile16_body<BITS, IS_INT, 8, false, false, MT>(codes, scales, zeros, X, Y, rowtiles, K, blockIdx.x, tokens, N);
+}
+
+static size_t gemv_multi_lds_bytes(int64_t K, int mt)
+{
+    return (size_t)mt * (K / kTileCols) * kXRun * 16 + 256 + (size_t)kGemvWaves * mt * kTileRows * sizeof(float);
+}
+
+// Whether run_gemv_multi serves this shape: 2..4 tokens, group 128, rows long enough for eight
+// wavefronts per tile, the padded vectors within 64 KB of LDS, and not four vectors on a tall
+// matrix (13824 x 5120: 13.7 us against 12.3 us for the few-token kernel; elsewhere the GEMV
+// kernel measured 1.1-1.45x faster than the few-token kernel at two to four tokens).
+bool gemv_multi_ok(int64_t M, int64_t N, int64_t K, int group)
+{
+    const int64_t G = K / kTileCols;
+    if (M < 2 || M > 4 || group != 128 || kGemvWaves != 8 || G < 32) return false;
+    if (M > 2 && N / kTileRows >= 768) return false;
+    return gemv_multi_lds_bytes(K, M <= 2 ? 2 : 4) <= 64 * 1024;
+}
+
+template <int BITS, bool IS_INT>
+static void launch_gemv_multi(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
+                              int64_t M, int64_t N, int64_t K, hipStream_t stream)
+{
+    const int64_t rowtiles = N / kTileRows;
+    const dim3 grid((unsigned)rowtiles), block(kGemvWaves * kWave);
+    if (M <= 2)
+        hipLaunchKernelGGL((gemv_tile16_multi_kernel<BITS, IS_INT, 2>), grid, block, gemv_multi_lds_bytes(K, 2), stream,
+                           (const u32x4 *)codes, (const uint16_t *)scales, (const uint16_t *)zeros, (const u32x4 *)X,
+                           (uint16_t *)Y, rowtiles, (int)K, (int)M, N);
+    else
+        hipLaunchKernelGGL((gemv_tile16_multi_kernel<BITS, IS_INT, 4>), grid, block, gemv_multi_lds_bytes(K, 4), stream,
+                           (const u32x4 *)codes, (const uint16_t *)scales, (const uint16_t *)zeros, (const u32x4 *)X,
+                           (uint16_t *)Y, rowtiles, (int)K, (int)M, N);
+}
+
+hipError_t run_gemv_multi(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
+                          void *Y, int64_t M, int64_t N, int64_t K, int bits, hipStream_t stream)
+{
+    if (is_int) {
+        if (bits == 4) launch_gemv_multi<4, true>(codes, scales, zeros, X, Y, M, N, K, stream);
+        else if (bits == 3) launch_gemv_multi<3, true>(codes, scales, zeros, X, Y, M, N, K, stream);
+        else launch_gemv_multi<2, true>(codes, scales, zeros, X, Y, M, N, K, stream);
+    } else {
+        if (bits == 4) launch_gemv_multi<4, false>(codes, scales, zeros, X, Y, M, N, K, stream);
+        else if (bits == 3) launch_gemv_multi<3, false>(codes, scales, zeros, X, Y, M, N, K, stream);
+        else launch_gemv_multi<2, false>(codes, scales, zeros, X, Y, M, N, K, stream);
     }
     return hipGetLastError();
 }

@@ -321,6 +321,11 @@ def test_empty_inputs_are_accepted(potq):
 # each with and without a workspace, PoT and uniform, so that no template instance goes untested.
 @pytest.mark.parametrize("is_int", [False, True])
 @pytest.mark.parametrize("M,N,K", [
+    (2, 272, 4096),        # two tokens: the GEMV kernel with one vector per result column
+    (3, 64, 5120),         # three tokens in the four-vector instance (fourth vector zero, not stored)
+    (4, 48, 4096),         # four tokens
+    (2, 32, 11008),        # two tokens, long rows
+    (4, 32, 8192),         # four tokens whose vectors do not fit LDS: few-token kernel
     (9, 1024, 2304),       # few-token kernel, 8 wavefronts, ragged last round (18 groups)
     (16, 12304, 384),      # few-token kernel, 16 wavefronts (tall matrix), surplus wavefronts in the last workgroup
     (24, 80, 1280),        # 17-32 tokens, K split inside the workgroup
