@@ -408,6 +408,9 @@ hipError_t run_gemm_fewtok(bool is_int, const void *codes, const void *scales, c
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 
 bool gemv_multi_ok(int64_t M, int64_t N, int64_t K, int group);
+size_t gemv_lds_bytes(int64_t K);
+hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
+                           void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 hipError_t run_gemv_multi(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
                           void *Y, int64_t M, int64_t N, int64_t K, int bits, hipStream_t stream);
 
@@ -416,6 +419,9 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
                            hipStream_t stream)
 {
     // up to 16 tokens: the kernel built like the GEMV (one table per 128 weights, no cross-lane code traffic)
+    // one token is a GEMV
+    if (M == 1 && gemv_lds_bytes(K) <= 64 * 1024)
+        return run_gemv_tile16(is_int, codes, scales, zeros, X, Y, N, K, bits, group, stream);
     // two to four tokens: the GEMV kernel with one activation vector per result column
     if (gemv_multi_ok(M, N, K, group)) return run_gemv_multi(is_int, codes, scales, zeros, X, Y, M, N, K, bits, stream);
     if (M <= 16)
