@@ -149,6 +149,17 @@ int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits,
  * `layout` names the layout `codes` is in; only POTQ_LAYOUT_TILE16 is accepted
  * (POTQ_ERR_LAYOUT otherwise; potq_repack converts), which needs N % 16 == 0.
  * The whole of x is held in on-chip memory: K <= 30464 (POTQ_ERR_SHAPE beyond).
+ *
+ * Large 2- and 3-bit matrices (potq_gemv_exponent_form() tells which) are served
+ * in the exponent form of the product (Sec. 4.2, additivity of exponents):
+ *   y[n] = sum_g scale[n,g] * sum_{k in g} (+-2^E[n,k]) x[k],
+ * the inner sums in exact integer arithmetic on x in 32-bit fixed point (exact
+ * for every x[k] within 2^19 of the largest |x|, rounded to 2^-30 of it below),
+ * one fp32 rounding per group.  For scales inside the domain of pot_dequant
+ * this is the same sum; for scales outside it (pot_check_scales() finds them,
+ * pot_quantize() never produces them) this form multiplies by 2^E where the
+ * other adds into the exponent field, and the results differ.  An infinity or
+ * NaN anywhere in x makes every y[n] NaN in this form.
  */
 int pot_gemv(const void *codes, const void *scales, const void *x_f16, void *y_f16,
              int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
@@ -156,6 +167,13 @@ int pot_gemv(const void *codes, const void *scales, const void *x_f16, void *y_f
 /* int_gemv -- the same with W~ as defined by int_dequant. */
 int int_gemv(const void *codes, const void *scales, const void *zeros, const void *x_f16, void *y_f16,
              int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
+
+/*
+ * 1 if pot_gemv (and pot_gemm with one token) serves an N x K matrix of this
+ * width in the exponent form described above, else 0.  For pot_gemv_batch pass
+ * the total number of rows of the matrices that share the launch.
+ */
+int potq_gemv_exponent_form(int64_t N, int64_t K, int bits);
 
 /*
  * pot_gemv_batch / int_gemv_batch -- up to POTQ_MAX_BATCH matrices that consume

@@ -42,6 +42,7 @@ EXPORTS = {
     "pot_gemv": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
     "int_gemv": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
     "potq_gemm_workspace_bytes": (ctypes.c_size_t, [_i64, _i64, _i64, _int]),
+    "potq_gemv_exponent_form": (_int, [_i64, _i64, _int]),
     "pot_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
     "int_gemm": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
     "pot_check_scales": (_int, [_vp, _i64, _int, _vp, _vp]),
@@ -219,6 +220,11 @@ def make_gemv_batch(mats, K: int, bits: int, is_int: bool = False):
         arr[i].y_f16 = _dev(y, torch.float16, "y")
         arr[i].N = _shape_codes(codes, K, bits)
     return arr
+
+
+def potq_gemv_exponent_form(N: int, K: int, bits: int) -> bool:
+    """Whether pot_gemv serves an N x K matrix in the exponent form (N: total rows for a batch)."""
+    return bool(_lib.potq_gemv_exponent_form(N, K, bits))
 
 
 def pot_gemv_batch(mats, x, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16):

@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB_PATH = os.path.join(_HERE, "libpotq.so")
-SOURCES = ["api.hip", "dequant.hip", "repack.hip", "gemv.hip", "gemm.hip", "quantize.hip", "fakequant.hip"]
+SOURCES = ["api.hip", "dequant.hip", "repack.hip", "gemv.hip", "gemv_exp.hip", "gemm.hip", "quantize.hip", "fakequant.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -19,6 +19,7 @@ size_t gemv_lds_bytes(int64_t K);
 hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
                            void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 int gemv_max_batch();
+bool gemv_exp_ok(int64_t N, int64_t K, int bits);
 hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *codes, const void *const *scales,
                                  const void *const *zeros, void *const *y, const int64_t *N, const void *x,
                                  int64_t K, int bits, int group, hipStream_t stream);
@@ -255,6 +256,12 @@ int int_gemv(const void *codes, const void *scales, const void *zeros, const voi
              int64_t K, int bits, int group, int layout, void *hip_stream)
 {
     return gemv_entry(true, codes, scales, zeros, x_f16, y_f16, N, K, bits, group, layout, hip_stream);
+}
+
+int potq_gemv_exponent_form(int64_t N, int64_t K, int bits)
+{
+    if (N <= 0 || K <= 0 || (K % 128) != 0 || (N % 16) != 0) return 0;
+    return potq::gemv_exp_ok(N, K, bits) ? 1 : 0;
 }
 
 int pot_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f16, int64_t K, int bits, int group,

@@ -604,11 +604,28 @@ static void launch_gemv_batch(const GemvBatch &b, unsigned blocks, const void *x
 #undef POTQ_LAUNCH_GEMVB
 }
 
+// The exponent form of the PoT GEMV (gemv_exp.hip).
+bool gemv_exp_ok(int64_t N, int64_t K, int bits);
+bool gemv_exp_batch_ok(int count, int64_t rows_total, int64_t K, int bits);
+hipError_t run_gemv_exp(const void *codes, const void *scales, const void *x, void *y, int64_t N, int64_t K, int bits,
+                        int group, hipStream_t stream);
+hipError_t run_gemv_exp_batch(int count, const void *const *codes, const void *const *scales, void *const *y,
+                              const int64_t *N, const void *x, int64_t K, int bits, int group, hipStream_t stream);
+#ifndef POTQ_GEMV_EXP
+#define POTQ_GEMV_EXP 1
+#endif
+
 // `count` non-empty matrices (count <= kMaxGemvBatch), validated by the caller; all share x, K, bits, group.
 hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *codes, const void *const *scales,
                                  const void *const *zeros, void *const *y, const int64_t *N, const void *x,
                                  int64_t K, int bits, int group, hipStream_t stream)
 {
+    if (POTQ_GEMV_EXP && !is_int) {
+        int64_t rows = 0;
+        for (int i = 0; i < count; ++i) rows += N[i];
+        if (gemv_exp_batch_ok(count, rows, K, bits))
+            return run_gemv_exp_batch(count, codes, scales, y, N, x, K, bits, group, stream);
+    }
     const int split = gemv_split(K / kTileCols);
     const int R = kGemvWaves / split;
     GemvBatch b;
@@ -639,9 +656,12 @@ hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *code
     return hipGetLastError();
 }
 
+
 hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
                            void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream)
 {
+    // large PoT matrices at 2 and 3 bits: the exponent form (scale applied per group, integer inner sums)
+    if (POTQ_GEMV_EXP && !is_int && gemv_exp_ok(N, K, bits)) return run_gemv_exp(codes, scales, x, y, N, K, bits, group, stream);
     if (is_int) {
         if (bits == 4) launch_gemv<4, true>(codes, scales, zeros, x, y, N, K, group, stream);
         else if (bits == 3) launch_gemv<3, true>(codes, scales, zeros, x, y, N, K, group, stream);

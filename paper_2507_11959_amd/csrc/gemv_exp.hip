@@ -1,0 +1,475 @@
+// Fused de-quantise + GEMV in the exponent form of the PoT product, gfx950.
+//
+// A power-of-two weight only shifts the exponent of the activation it meets
+// (Sec. 4.2, the additivity of exponents), so the group's scale can stay out
+// of the inner loop and be applied once per group to the partial sum:
+//     y[n] = sum_g s[n,g] * sum_{k in g} (+-2^E[n,k]) x[k].
+// The inner sums are integer work.  +-2^E is a signed byte, one v_perm_b32
+// look-up per four codes in a table that is the same for every group (no
+// per-group table, no merge with the scale's low byte: the vector ALU, the
+// scarce unit of the fp16 GEMV, does about 40 % less).  The activations are
+// turned, once per workgroup, into 32-bit fixed point against the largest
+// exponent in x and cut into four signed 8-bit digits, x = 2^-k sum_p 256^p d_p;
+// digit sums run on the matrix pipe (v_mfma_i32_16x16x64_i8, exact).  The
+// digits of the four groups a wavefront works on sit block-diagonally in the A
+// operand -- row 4q + p holds digit p of the group of lane group q in k-slice q
+// and zeros elsewhere -- so lane (r, q) receives the four digit sums of row r
+// of its own group, recombines them and multiplies by its own scale.
+//
+// Exactness: every fp16 activation within 2^19 of the largest one is
+// represented exactly (smaller ones are rounded to 2^-30 of the largest); the
+// digit sums are exact; one fp32 rounding per group in the recombination and
+// one in the accumulation, as many as the fp16 form has per four MFMA steps.
+// The scale must lie in the domain on which the integer add of Sec. 4.2 is the
+// multiplication by 2^E (every scale pot_quantize produces does).
+#include "potq_device.hpp"
+
+namespace potq {
+
+constexpr int kExpSplit = 8;          // wavefronts that share one 16-row tile and split its scale groups
+constexpr int kPieceRun = 9;          // uint4 per (group, digit) in LDS: 128 bytes + 16 of padding
+constexpr int kExpOctetsPerThread = 4;   // x octets a thread stages: K <= 4 * 8 * (threads of the workgroup)
+
+typedef int int4_t __attribute__((ext_vector_type(4)));
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+template <int BITS>
+struct ExpDecoder {
+    static_assert(BITS == 2 || BITS == 3, "+-2^E must fit a signed byte");
+    // the signed bytes +-2^E by code (sign in the code's top bit)
+    static constexpr uint32_t lo = BITS == 2 ? 0xFEFF0201u : 0x08040201u;
+    static constexpr uint32_t hi = BITS == 2 ? 0xFEFF0201u : 0xF8FCFEFFu;
+    uint32_t sel[8];
+    __device__ __forceinline__ void set_block(const uint32_t (&w)[BITS])
+    {
+        if constexpr (BITS == 3)
+            selectors3(w[0], w[1], w[2], sel);
+        else
+            selectors2(w[0], w[1], sel);
+    }
+    // selector m -> the four weights of columns 4m + (0, 2, 1, 3) of the block
+    __device__ __forceinline__ uint32_t get(int m) const { return byte_perm(hi, lo, sel[m]); }
+};
+
+// Eight 16-byte LDS reads by the lanes of `lanes` only, which leave the registers of the other
+// lanes untouched: the off-diagonal lanes of the A operand hold zeros, written once, and never
+// read LDS.  The compiler does not count these reads, so lds_wait() stands between them and
+// their first use.
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+__device__ __forceinline__ void lds_read_keep(u32x4 (&xa)[8], uint32_t lds_byte_address, uint64_t lanes)
+{
+    uint64_t saved;
+    asm volatile("s_mov_b64 %[saved], exec\n\t"
+                 "s_and_b64 exec, exec, %[lanes]\n\t"
+                 "ds_read_b128 %[x0], %[at]\n\t"
+                 "ds_read_b128 %[x1], %[at] offset:16\n\t"
+                 "ds_read_b128 %[x2], %[at] offset:32\n\t"
+                 "ds_read_b128 %[x3], %[at] offset:48\n\t"
+                 "ds_read_b128 %[x4], %[at] offset:64\n\t"
+                 "ds_read_b128 %[x5], %[at] offset:80\n\t"
+                 "ds_read_b128 %[x6], %[at] offset:96\n\t"
+                 "ds_read_b128 %[x7], %[at] offset:112\n\t"
+                 "s_mov_b64 exec, %[saved]"
+                 : [x0] "+v"(xa[0]), [x1] "+v"(xa[1]), [x2] "+v"(xa[2]), [x3] "+v"(xa[3]), [x4] "+v"(xa[4]),
+                   [x5] "+v"(xa[5]), [x6] "+v"(xa[6]), [x7] "+v"(xa[7]), [saved] "=&s"(saved)
+                 : [at] "v"(lds_byte_address), [lanes] "s"(lanes));
+}
+__device__ __forceinline__ void lds_wait(u32x4 (&xa)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(xa[0]), "+v"(xa[1]), "+v"(xa[2]), "+v"(xa[3]), "+v"(xa[4]), "+v"(xa[5]), "+v"(xa[6]), "+v"(xa[7]));
+}
+
+// Blocks b0 .. b1-1 (32 columns each) of one group of one row against the lane's A operand
+// (xa[2b + h]: digit bytes of columns 32b + 16h .. + 15, in selector order).
+template <int BITS>
+__device__ __forceinline__ void exp_blocks(const u32x4 (&L)[BITS], const u32x4 (&xa)[8], int b0, int b1, int4_t &d)
+{
+    ExpDecoder<BITS> dec;
+#pragma unroll
+    for (int b = b0; b < b1; ++b) {
+        uint32_t w[BITS];
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) w[j] = L[j][b];
+        dec.set_block(w);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const u32x4 wt{dec.get(4 * h), dec.get(4 * h + 1), dec.get(4 * h + 2), dec.get(4 * h + 3)};
+            d = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(int4_t, xa[2 * b + h]),
+                                                      __builtin_bit_cast(int4_t, wt), d, 0, 0, 0);
+        }
+    }
+}
+
+// The four digit sums of a group -> the group's sum in units of 2^-k, as fp32.
+__device__ __forceinline__ float exp_recombine(const int4_t d)
+{
+    const int hi = d[3] * 256 + d[2];               // |d_p| <= 128 * 8 * 128
+    const int lo = d[1] * 256 + d[0];
+    return __builtin_fmaf((float)hi, 65536.f, (float)lo);
+}
+
+// Eight fp16 activations (columns 8i .. 8i+7) -> fixed point m = rne(x * 2^k), each m cut into
+// four signed digits (m + 0x00808080 makes the three low bytes excess-128), the digits stored
+// per digit plane in the order the selectors deliver the weights: (c0, c2, c1, c3, c4, c6, c5, c7).
+__device__ __forceinline__ void stage_digits(const u32x4 xv, u32x4 *__restrict__ pieces, int i, float two_k)
+{
+    const int g = i >> 4, at = i & 15;              // group, octet inside the group
+    uint32_t u[8];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const half2_t h = as_half2(xv[w]);
+        u[2 * w] = (uint32_t)(int)__builtin_rintf((float)h[0] * two_k) + 0x00808080u;
+        u[2 * w + 1] = (uint32_t)(int)__builtin_rintf((float)h[1] * two_k) + 0x00808080u;
+    }
+    uint32_t plane[4][2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const uint32_t a = u[4 * q], b = u[4 * q + 1], c = u[4 * q + 2], d = u[4 * q + 3];
+        const uint32_t ac_lo = byte_perm(c, a, 0x05010400u);     // a.0 c.0 a.1 c.1
+        const uint32_t ac_hi = byte_perm(c, a, 0x07030602u);     // a.2 c.2 a.3 c.3
+        const uint32_t bd_lo = byte_perm(d, b, 0x05010400u);
+        const uint32_t bd_hi = byte_perm(d, b, 0x07030602u);
+        plane[0][q] = byte_perm(bd_lo, ac_lo, 0x05040100u) ^ 0x80808080u;   // a.0 c.0 b.0 d.0
+        plane[1][q] = byte_perm(bd_lo, ac_lo, 0x07060302u) ^ 0x80808080u;
+        plane[2][q] = byte_perm(bd_hi, ac_hi, 0x05040100u) ^ 0x80808080u;
+        plane[3][q] = byte_perm(bd_hi, ac_hi, 0x07060302u);                 // top digit: two's complement as is
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) ((u32x2 *)(pieces + (g * 4 + p) * kPieceRun))[at] = u32x2{plane[p][0], plane[p][1]};
+}
+
+// A workgroup of WAVES wavefronts stages the digits of x once and serves, WAVES / 8 at a time,
+// the row tiles (first + i * stride) * (WAVES / 8) + slot below rowtiles.  The eight wavefronts
+// of a slot split the scale groups of its tile (wavefront p, lane group t: groups 4p + t,
+// 4p + t + 32, ...).  The codes of the next step -- the next round of the tile or the first round
+// of the next tile -- are requested before the current ones are expanded (requests two or three
+// steps ahead measured slower), and the very first request goes out before x is staged.
+template <int BITS, bool G64, int WAVES>
+__device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales,
+                                              const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int K,
+                                              int64_t rowtiles, int64_t first, int64_t stride)
+{
+    constexpr int gs = G64 ? 1 : 0;
+    constexpr int kStep = 4 * kExpSplit;                // groups per round of a slot
+    constexpr int SLOTS = WAVES / kExpSplit;
+    static_assert(WAVES % kExpSplit == 0, "whole slots");
+    extern __shared__ u32x4 smem[];
+    const int G = K / kTileCols;
+    u32x4 *pieces = smem;                               // [group][digit] runs of kPieceRun uint4
+    u32x4 *zero_block = smem + G * 4 * kPieceRun;       // 8 uint4 of zeros
+    float *red = (float *)(zero_block + 8);             // 2 x WAVES x 16 partial sums
+    uint32_t *amax_part = (uint32_t *)(red + 2 * WAVES * kTileRows);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, kept in a scalar
+    const int part = wave % kExpSplit;
+    const int slot = wave / kExpSplit;
+    const int r = lane & 15;
+    const int t = lane >> 4;
+    const int scale_owner = (4 * r + t) * 4;            // ds_bpermute byte address
+    // rounds in which this wavefront has a group (G >= 32: at least one)
+    const int my_rounds = (G - part * 4 + kStep - 1) / kStep;
+    // tile of this slot in tile set q; a slot past the last tile works on the last one and stores nothing
+    auto tile_of = [&](int64_t q) { return min(q * SLOTS + slot, rowtiles - 1); };
+
+    // Codes of (tile, round) for lane (r, t); scales in memory order (lane l: row l/4, group
+    // first + l%4; handed to their owners by a permute) or, for group size 64, the lane's own pair.
+    // Indices past the end of the row are clamped into it: valid memory, multiplied by zeros.
+    auto fetch = [&](int64_t tile, int round, u32x4 (&Lx)[BITS], uint32_t &sx) {
+        const int g0 = round * kStep + part * 4;                        // uniform
+        const int gc = min(g0 + t, G - 1);
+        const u32x4 *tile_codes = codes + tile * G * (BITS * 16);       // uniform
+        const uint32_t at = (uint32_t)(gc * (BITS * 16) + r);
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) Lx[j] = __builtin_nontemporal_load(tile_codes + at + 16 * j);
+        if (gs) {
+            const uint32_t *tile_scales = (const uint32_t *)(scales + tile * kTileRows * (int64_t)(2 * G));
+            sx = tile_scales[(uint32_t)(r * G + gc)];
+        } else {
+            const uint16_t *tile_scales = scales + tile * kTileRows * (int64_t)G;
+            sx = tile_scales[(uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1))];
+        }
+    };
+
+    // The steps of a wavefront are its (tile set, round) pairs in order.  `fq`/`fround` is the
+    // step of the next request; past the last step the last one is requested again (valid
+    // memory, never used).
+    int64_t fq = first;
+    int fround = 0;
+    auto advance = [&]() {
+        if (fround + 1 < my_rounds) {
+            ++fround;
+        } else if ((fq + stride) * SLOTS < rowtiles) {
+            fq += stride;
+            fround = 0;
+        }
+    };
+    u32x4 L[BITS];
+    uint32_t s;
+    fetch(tile_of(fq), fround, L, s);
+    advance();
+
+    // --- activations: largest exponent, then fixed point digits into LDS ---
+    const int octets = K / 8;
+    u32x4 xv[kExpOctetsPerThread];
+    uint32_t am = 0u;
+#pragma unroll
+    for (int n = 0; n < kExpOctetsPerThread; ++n) {
+        const int i = tid + n * (WAVES * kWave);
+        xv[n] = i < octets ? x[i] : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            am = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, am),
+                                                                        __builtin_bit_cast(ushort2_t, xv[n][w] & 0x7FFF7FFFu)));
+    }
+    am = max(am & 0xFFFFu, am >> 16);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) am = max(am, (uint32_t)__shfl_xor((int)am, off, kWave));
+    if (lane == 0) amax_part[wave] = am;
+    if (tid < 8) zero_block[tid] = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < WAVES; ++p) am = max(am, amax_part[p]);
+    // |x| < 2^(e-14) with e = max(exponent field, 1): k = 44 - e puts every |m| below 2^30
+    const int e = max((int)(am >> 10), 1);
+    const int k = 44 - e;
+    const float two_k = __builtin_bit_cast(float, (uint32_t)(k + 127) << 23);
+    // an infinity or NaN among the activations makes every result NaN
+    const float two_mk = e == 31 ? __builtin_nanf("") : __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
+#pragma unroll
+    for (int n = 0; n < kExpOctetsPerThread; ++n) {
+        const int i = tid + n * (WAVES * kWave);
+        if (i < octets) stage_digits(xv[n], pieces, i, two_k);
+    }
+    __syncthreads();
+
+    // The A operand: lanes on the block diagonal carry digit (lane % 4) of their own group; the
+    // others hold zeros from here on (lds_read_keep never writes them).
+    const uint64_t diagonal_lanes = __builtin_amdgcn_ballot_w64((r >> 2) == t);
+    u32x4 xa[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xa[j] = u32x4{0u, 0u, 0u, 0u};
+    const uint32_t pieces_at = (uint32_t)(uintptr_t)(lds_u32x4 *)pieces;
+    const uint32_t zeros_at = (uint32_t)(uintptr_t)(lds_u32x4 *)zero_block;
+
+    int it = 0;
+    for (int64_t q = first; q * SLOTS < rowtiles; q += stride, ++it) {
+        float row_sum = 0.f;
+        for (int round = 0; round < my_rounds; ++round) {
+            u32x4 Ln[BITS];
+            uint32_t sn;
+            fetch(tile_of(fq), fround, Ln, sn);
+            advance();
+            const int g = round * kStep + part * 4 + t;
+            // a lane past the end of the row multiplies the (valid) last group by zeros
+            lds_read_keep(xa, g < G ? pieces_at + (uint32_t)((g * 4 + (lane & 3)) * (kPieceRun * 16)) : zeros_at,
+                          diagonal_lanes);
+            if (gs) {
+                lds_wait(xa);
+                int4_t d0{0, 0, 0, 0}, d1{0, 0, 0, 0};
+                exp_blocks<BITS>(L, xa, 0, 2, d0);
+                exp_blocks<BITS>(L, xa, 2, 4, d1);
+                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s & 0xFFFFu)), exp_recombine(d0),
+                                         row_sum);
+                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s >> 16)), exp_recombine(d1),
+                                         row_sum);
+            } else {
+                const uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)s);
+                lds_wait(xa);
+                int4_t d{0, 0, 0, 0};
+                exp_blocks<BITS>(L, xa, 0, 4, d);
+                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)so), exp_recombine(d), row_sum);
+            }
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
+            s = sn;
+        }
+
+        // lane (r, t) holds the groups of lane group t of row r: add the lane groups, then the
+        // wavefronts of the slot, in a fixed order.  The buffer alternates between tile sets, so one
+        // barrier per set separates the writes of set i + 2 from the reads of set i.
+        float *red_it = red + (it & 1) * (WAVES * kTileRows);
+        row_sum *= two_mk;
+        row_sum += __shfl_xor(row_sum, 16, kWave);
+        row_sum += __shfl_xor(row_sum, 32, kWave);
+        if (t == 0) red_it[wave * kTileRows + r] = row_sum;
+        __syncthreads();
+        if (tid < SLOTS * kTileRows) {
+            const int of_slot = tid / kTileRows, row = tid % kTileRows;
+            const int64_t tile = q * SLOTS + of_slot;
+            float sum = 0.f;
+#pragma unroll
+            for (int p = 0; p < kExpSplit; ++p) sum += red_it[(of_slot * kExpSplit + p) * kTileRows + row];
+            const _Float16 h = (_Float16)sum;
+            if (tile < rowtiles) y[tile * kTileRows + row] = __builtin_bit_cast(uint16_t, h);
+        }
+    }
+}
+
+template <int BITS, bool G64, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void gemv_exp_kernel(
+    const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const u32x4 *__restrict__ x,
+    uint16_t *__restrict__ y, int K, int64_t rowtiles)
+{
+    gemv_exp_body<BITS, G64, WAVES>(codes, scales, x, y, K, rowtiles, blockIdx.x, gridDim.x);
+}
+
+// Several matrices that consume the same activation vector in one launch: a workgroup belongs
+// to one matrix and walks that matrix's tiles as in the single launch.
+constexpr int kMaxExpBatch = 16;
+struct ExpBatch {
+    const u32x4 *codes[kMaxExpBatch];
+    const uint16_t *scales[kMaxExpBatch];
+    uint16_t *y[kMaxExpBatch];
+    int64_t rowtiles[kMaxExpBatch];
+    uint32_t first_block[kMaxExpBatch + 1];   // workgroups first_block[i] .. first_block[i+1]-1 serve matrix i
+    int count;
+};
+
+template <int BITS, bool G64, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void gemv_exp_batch_kernel(const ExpBatch batch,
+                                                                       const u32x4 *__restrict__ x, int K)
+{
+    int i = 0;
+    while (i + 1 < batch.count && blockIdx.x >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
+    gemv_exp_body<BITS, G64, WAVES>(batch.codes[i], batch.scales[i], x, batch.y[i], K, batch.rowtiles[i],
+                                    blockIdx.x - batch.first_block[i],
+                                    batch.first_block[i + 1] - batch.first_block[i]);
+}
+
+static size_t exp_lds_bytes(int64_t K, int waves)
+{
+    return (size_t)(K / kTileCols) * 4 * kPieceRun * 16 + 8 * 16 + 2 * (size_t)waves * kTileRows * sizeof(float) +
+           (size_t)waves * sizeof(uint32_t);
+}
+
+#ifndef POTQ_EXP_GROUPS
+#define POTQ_EXP_GROUPS 512
+#endif
+#ifndef POTQ_EXP_MIN_WEIGHTS
+#define POTQ_EXP_MIN_WEIGHTS (60ll << 20)
+#endif
+// Workgroups per launch: what the chip holds at once (two per compute unit at this register
+// and LDS footprint), each with an equal share of the row tiles, so that x is staged as few
+// times as possible and nobody waits for a second wave of workgroups.
+constexpr int kExpGroups = POTQ_EXP_GROUPS;
+constexpr size_t kExpLdsSmall = 64 * 1024, kExpLdsLarge = 160 * 1024;
+
+// Wavefronts per workgroup: eight while two workgroups' digits of x fit the LDS of a compute
+// unit together, else sixteen (two tiles at a time) for one workgroup per compute unit.
+static int exp_waves(int64_t K) { return exp_lds_bytes(K, 8) <= kExpLdsSmall ? 8 : 16; }
+
+// Whether the exponent form serves this PoT GEMV: signed-byte weights (2 or 3 bits), rows long
+// enough for eight wavefronts per tile, the digits of x within LDS and within the staging
+// registers of a thread, and a matrix large enough for the conversion of x to pay: below
+// about 60 M weights the fp16 form measured equal or faster (4096 x 11008, 3 bits: 7.2 us
+// against 7.5 us), above slower (28672 x 8192: 22 us against 17 us).
+bool gemv_exp_ok(int64_t N, int64_t K, int bits)
+{
+    const int64_t G = K / kTileCols;
+    if (bits != 2 && bits != 3) return false;
+    if (G < 32 || N * K < POTQ_EXP_MIN_WEIGHTS) return false;
+    const int waves = exp_waves(K);
+    if (K > (int64_t)kExpOctetsPerThread * waves * kWave * 8) return false;
+    return exp_lds_bytes(K, waves) <= kExpLdsLarge;
+}
+
+// The same question for `count` matrices that share x (N = the sum of their rows).
+bool gemv_exp_batch_ok(int count, int64_t rows_total, int64_t K, int bits)
+{
+    return count <= kMaxExpBatch && gemv_exp_ok(rows_total, K, bits);
+}
+
+template <typename Kernel>
+static hipError_t exp_allow_lds(Kernel kernel, size_t lds)
+{
+    // more dynamic LDS than the default limit: raise the kernel's limit (cheap and idempotent,
+    // so it is simply repeated on every such launch)
+    if (lds <= kExpLdsSmall) return hipSuccess;
+    return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kExpLdsLarge);
+}
+
+// Workgroups for a matrix of `sets` tile sets when it may use `cap` of them: equal shares of sets.
+static int64_t exp_groups(int64_t sets, int64_t cap)
+{
+    if (cap < 1) cap = 1;
+    const int64_t per_group = (sets + cap - 1) / cap;
+    return (sets + per_group - 1) / per_group;
+}
+
+template <int BITS, bool G64, int WAVES>
+static hipError_t launch_exp(const void *codes, const void *scales, const void *x, void *y, int64_t N, int64_t K,
+                             hipStream_t stream)
+{
+    const size_t lds = exp_lds_bytes(K, WAVES);
+    const hipError_t e = exp_allow_lds(gemv_exp_kernel<BITS, G64, WAVES>, lds);
+    if (e != hipSuccess) return e;
+    constexpr int SLOTS = WAVES / kExpSplit;
+    const int64_t rowtiles = N / kTileRows;
+    const dim3 grid((unsigned)exp_groups((rowtiles + SLOTS - 1) / SLOTS, kExpGroups / SLOTS)), block(WAVES * kWave);
+    hipLaunchKernelGGL((gemv_exp_kernel<BITS, G64, WAVES>), grid, block, lds, stream, (const u32x4 *)codes,
+                       (const uint16_t *)scales, (const u32x4 *)x, (uint16_t *)y, (int)K, rowtiles);
+    return hipGetLastError();
+}
+
+hipError_t run_gemv_exp(const void *codes, const void *scales, const void *x, void *y, int64_t N, int64_t K, int bits,
+                        int group, hipStream_t stream)
+{
+    const bool g64 = group == 64;
+#define POTQ_LAUNCH_EXP(BITS, WAVES)                                                              \
+    (g64 ? launch_exp<BITS, true, WAVES>(codes, scales, x, y, N, K, stream)                       \
+         : launch_exp<BITS, false, WAVES>(codes, scales, x, y, N, K, stream))
+    if (exp_waves(K) == 8) return bits == 3 ? POTQ_LAUNCH_EXP(3, 8) : POTQ_LAUNCH_EXP(2, 8);
+    return bits == 3 ? POTQ_LAUNCH_EXP(3, 16) : POTQ_LAUNCH_EXP(2, 16);
+#undef POTQ_LAUNCH_EXP
+}
+
+
+template <int BITS, bool G64, int WAVES>
+static hipError_t launch_exp_batch(int count, const void *const *codes, const void *const *scales, void *const *y,
+                                   const int64_t *N, const void *x, int64_t K, hipStream_t stream)
+{
+    const size_t lds = exp_lds_bytes(K, WAVES);
+    const hipError_t e = exp_allow_lds(gemv_exp_batch_kernel<BITS, G64, WAVES>, lds);
+    if (e != hipSuccess) return e;
+    constexpr int SLOTS = WAVES / kExpSplit;
+    int64_t sets_total = 0;
+    for (int i = 0; i < count; ++i) sets_total += (N[i] / kTileRows + SLOTS - 1) / SLOTS;
+    ExpBatch b;
+    uint64_t blocks = 0;
+    for (int i = 0; i < kMaxExpBatch; ++i) {
+        const bool live = i < count;
+        b.codes[i] = live ? (const u32x4 *)codes[i] : nullptr;
+        b.scales[i] = live ? (const uint16_t *)scales[i] : nullptr;
+        b.y[i] = live ? (uint16_t *)y[i] : nullptr;
+        b.rowtiles[i] = live ? N[i] / kTileRows : 0;
+        b.first_block[i] = (uint32_t)blocks;
+        if (live) {
+            // each matrix gets the share of the resident workgroups that its share of the tiles asks for
+            const int64_t sets = (b.rowtiles[i] + SLOTS - 1) / SLOTS;
+            blocks += (uint64_t)exp_groups(sets, (kExpGroups / SLOTS) * sets / sets_total);
+        }
+    }
+    b.first_block[kMaxExpBatch] = (uint32_t)blocks;
+    b.count = count;
+    hipLaunchKernelGGL((gemv_exp_batch_kernel<BITS, G64, WAVES>), dim3((unsigned)blocks), dim3(WAVES * kWave), lds,
+                       stream, b, (const u32x4 *)x, (int)K);
+    return hipGetLastError();
+}
+
+// `count` non-empty matrices (count <= kMaxExpBatch) that share x, K, bits and group.
+hipError_t run_gemv_exp_batch(int count, const void *const *codes, const void *const *scales, void *const *y,
+                              const int64_t *N, const void *x, int64_t K, int bits, int group, hipStream_t stream)
+{
+    const bool g64 = group == 64;
+#define POTQ_LAUNCH_EXPB(BITS, WAVES)                                                             \
+    (g64 ? launch_exp_batch<BITS, true, WAVES>(count, codes, scales, y, N, x, K, stream)          \
+         : launch_exp_batch<BITS, false, WAVES>(count, codes, scales, y, N, x, K, stream))
+    if (exp_waves(K) == 8) return bits == 3 ? POTQ_LAUNCH_EXPB(3, 8) : POTQ_LAUNCH_EXPB(2, 8);
+    return bits == 3 ? POTQ_LAUNCH_EXPB(3, 16) : POTQ_LAUNCH_EXPB(2, 16);
+#undef POTQ_LAUNCH_EXPB
+}
+
+}  // namespace potq

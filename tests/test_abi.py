@@ -83,6 +83,12 @@ def test_host_side_validation(lib):
     assert lib.potq_gemm_workspace_bytes(256, 13824, 5120, 3) == 0      # enough output tiles: no split
     assert lib.potq_gemm_workspace_bytes(256, 4096, 4096, 3) == 5 * 256 * 4096 * 4   # 64 tiles of 128x128
     assert lib.potq_gemm_workspace_bytes(0, 4096, 4096, 3) == 0
+    # the exponent form of the GEMV: large 2- and 3-bit matrices with at least 32 groups per row
+    assert lib.potq_gemv_exponent_form(28672, 8192, 3) == 1 and lib.potq_gemv_exponent_form(8192, 28672, 2) == 1
+    assert lib.potq_gemv_exponent_form(4096, 4096, 3) == 0        # too small for the conversion of x to pay
+    assert lib.potq_gemv_exponent_form(28672, 8192, 4) == 0       # +-2^7 does not fit a signed byte
+    assert lib.potq_gemv_exponent_form(1 << 20, 2048, 3) == 0     # fewer than 32 groups per row
+    assert lib.potq_gemv_exponent_form(0, 8192, 3) == 0 and lib.potq_gemv_exponent_form(28672, 8200, 3) == 0
     assert lib.int_gemv(A, A, A, MIS, A, 16, 128, 3, 128, 1, None) == ALIGN
     r = lib.potq_repack
     assert r(A, A, 24, 128, 3, 1, None) == SHAPE
@@ -113,3 +119,13 @@ def test_driver_entry_points_exist():
     import importlib
     entry = importlib.import_module("__graft_entry__")
     assert callable(entry.build) and callable(entry.smoke)
+
+
+def test_build_step_loads_without_the_built_library():
+    """build() must work in a tree that has no libpotq.so yet: it may not import the package, which needs it."""
+    import subprocess
+    import sys
+    code = ("import sys, __graft_entry__ as g; m = g._build_module(); "
+            "assert m.LIB_PATH.endswith('libpotq.so') and callable(m.build); "
+            "assert not any(k.startswith('paper_2507_11959_amd') for k in sys.modules)")
+    subprocess.run([sys.executable, "-c", code], check=True, cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))

@@ -1,0 +1,111 @@
+"""GPU parity of the exponent form of the PoT GEMV (Sec. 4.2, additivity of exponents: the
+scale applied once per group, integer inner sums) against the oracle, through pot_gemv and
+pot_gemv_batch on shapes large enough to be served by it: ragged group counts, several row
+tiles per workgroup, the sixteen-wavefront variant for long rows, both group sizes, and
+activation vectors that stress the fixed-point conversion of x."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_util import REL_TOL, dev, host_bits, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def potq():
+    import paper_2507_11959_amd as p
+    return p
+
+
+def _threads():
+    import os
+    return min(16, len(os.sched_getaffinity(0)))
+
+
+def _x(kind: str, K: int, seed: int) -> np.ndarray:
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal(K).astype(np.float32)
+    if kind == "outlier":            # a few channels 200x the rest, as activation outliers are
+        x[rng.choice(K, 8, replace=False)] *= 200.0
+    elif kind == "tiny":
+        x *= 1e-4
+    elif kind == "wide":             # 30 binades of dynamic range: small entries fall off the fixed-point grid
+        x *= np.exp2(rng.integers(-20, 10, K)).astype(np.float32)
+    elif kind == "subnormal":
+        x *= 3e-7
+    elif kind == "zero":
+        x[:] = 0.0
+    elif kind == "largest":          # the largest finite fp16 among ordinary entries
+        x[rng.choice(K, 4, replace=False)] = 65504.0
+    return x.astype(np.float16)
+
+
+def _check(potq, N, K, bits, group, kind="normal", seed=0):
+    assert potq.potq_gemv_exponent_form(N, K, bits), "shape is meant to take the exponent form"
+    packed, S = workloads.pot_matrix(6, seed, N, K, bits, group)
+    x = _x(kind, K, seed)
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    got = host_bits(potq.pot_gemv(tiled, dev(S), dev(x), K, bits, group))
+    want = oracle.gemm(packed, S, None, x[None, :], K, bits, group, nthreads=_threads())[0]
+    finite = np.isfinite(want.view(np.float16))      # sums beyond the fp16 range: the same infinity on both sides
+    assert np.array_equal(got[~finite], want[~finite])
+    e, nw, nfloor = rel_err(got[finite], want[finite], K)
+    assert e <= REL_TOL, (N, K, bits, group, kind, e, nw, nfloor)
+    return got, want
+
+
+@pytest.mark.parametrize("N,K,bits,group", [
+    (15904, 4224, 3, 128),     # 33 groups: one wavefront has a second round; 994 tiles over 497 workgroups
+    (8208, 8192, 2, 128),      # 513 tiles: the last workgroup has one tile fewer
+    (9600, 7040, 3, 64),       # group size 64, 55 groups
+    (4112, 16384, 2, 64),      # long rows: sixteen wavefronts, two tiles at a time, odd number of tiles
+    (2320, 30464, 3, 128),     # the longest row pot_gemv accepts
+])
+def test_shapes(potq, N, K, bits, group):
+    _check(potq, N, K, bits, group)
+
+
+@pytest.mark.parametrize("kind", ["outlier", "tiny", "wide", "subnormal", "zero", "largest"])
+def test_activation_ranges(potq, kind):
+    got, want = _check(potq, 8192, 8192, 3, 128, kind, seed=3)
+    if kind == "zero":
+        assert not got.any()
+
+
+def test_non_finite_activation_gives_nan(potq):
+    N, K, bits = 8192, 8192, 3
+    packed, S = workloads.pot_matrix(6, 9, N, K, bits, 128)
+    x = _x("normal", K, 9)
+    x[17] = np.float16(np.inf)
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    y = potq.pot_gemv(tiled, dev(S), dev(x), K, bits)
+    assert bool(torch.isnan(y).all())
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_batch_sharing_x(potq, bits):
+    K, rows = 4096, (11008, 5504, 16)          # 16 528 rows together: served in the exponent form
+    assert potq.potq_gemv_exponent_form(sum(rows), K, bits)
+    x = _x("outlier", K, 11)
+    mats, refs = [], []
+    for i, N in enumerate(rows):
+        packed, S = workloads.pot_matrix(6, 20 + i, N, K, bits, 128)
+        mats.append((potq.potq_repack(dev(packed), K, bits), dev(S)))
+        refs.append(oracle.gemm(packed, S, None, x[None, :], K, bits, 128, nthreads=_threads())[0])
+    ys = potq.pot_gemv_batch(mats, dev(x), K, bits)
+    for y, want in zip(ys, refs):
+        e, nw, nfloor = rel_err(host_bits(y), want, K)
+        assert e <= REL_TOL, (bits, e, nw, nfloor)
+
+
+def test_gemm_with_one_token_takes_the_same_path(potq):
+    N, K, bits = 8192, 8192, 3
+    packed, S = workloads.pot_matrix(6, 30, N, K, bits, 128)
+    x = _x("normal", K, 30)
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    y1 = host_bits(potq.pot_gemv(tiled, dev(S), dev(x), K, bits))
+    y2 = host_bits(potq.pot_gemm(tiled, dev(S), dev(x[None, :]), K, bits))[0]
+    assert np.array_equal(y1, y2)
