@@ -24,6 +24,8 @@
 // multiplication by 2^E (every scale pot_quantize produces does).
 #include "potq_device.hpp"
 
+#include <atomic>
+
 namespace potq {
 
 constexpr int kExpSplit = 8;          // wavefronts that share one 16-row tile and split its scale groups
@@ -382,13 +384,23 @@ bool gemv_exp_batch_ok(int count, int64_t rows_total, int64_t K, int bits)
     return count <= kMaxExpBatch && gemv_exp_ok(rows_total, K, bits);
 }
 
-template <typename Kernel>
-static hipError_t exp_allow_lds(Kernel kernel, size_t lds)
+// More dynamic LDS than the default limit of a kernel: raise that kernel's limit, once per
+// device and process (the call is not stream work, so it is also legal while a stream is
+// being captured into a graph).
+template <int BITS, bool G64, int WAVES, bool BATCH>
+static hipError_t exp_allow_lds(size_t lds)
 {
-    // more dynamic LDS than the default limit: raise the kernel's limit (cheap and idempotent,
-    // so it is simply repeated on every such launch)
     if (lds <= kExpLdsSmall) return hipSuccess;
-    return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kExpLdsLarge);
+    static std::atomic<uint64_t> raised{0};           // bit d: done on device d (devices past 63: every call)
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 64 && ((raised.load(std::memory_order_acquire) >> device) & 1u)) return hipSuccess;
+    const void *kernel = BATCH ? (const void *)gemv_exp_batch_kernel<BITS, G64, WAVES>
+                               : (const void *)gemv_exp_kernel<BITS, G64, WAVES>;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kExpLdsLarge);
+    if (e == hipSuccess && device < 64) raised.fetch_or(uint64_t{1} << device, std::memory_order_release);
+    return e;
 }
 
 // Workgroups for a matrix of `sets` tile sets when it may use `cap` of them: equal shares of sets.
@@ -404,7 +416,7 @@ static hipError_t launch_exp(const void *codes, const void *scales, const void *
                              hipStream_t stream)
 {
     const size_t lds = exp_lds_bytes(K, WAVES);
-    const hipError_t e = exp_allow_lds(gemv_exp_kernel<BITS, G64, WAVES>, lds);
+    const hipError_t e = exp_allow_lds<BITS, G64, WAVES, false>(lds);
     if (e != hipSuccess) return e;
     constexpr int SLOTS = WAVES / kExpSplit;
     const int64_t rowtiles = N / kTileRows;
@@ -432,7 +444,7 @@ static hipError_t launch_exp_batch(int count, const void *const *codes, const vo
                                    const int64_t *N, const void *x, int64_t K, hipStream_t stream)
 {
     const size_t lds = exp_lds_bytes(K, WAVES);
-    const hipError_t e = exp_allow_lds(gemv_exp_batch_kernel<BITS, G64, WAVES>, lds);
+    const hipError_t e = exp_allow_lds<BITS, G64, WAVES, true>(lds);
     if (e != hipSuccess) return e;
     constexpr int SLOTS = WAVES / kExpSplit;
     int64_t sets_total = 0;

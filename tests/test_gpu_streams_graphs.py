@@ -83,3 +83,27 @@ def test_graph_capture_and_replay(potq, bits):
             assert np.array_equal(host_bits(m["out"]), oracle.pot_dequant(m["packed"], m["scales"], K, bits, 128))
             assert torch.equal(y, ey), replay
         assert torch.equal(Y_g, eager_Y), replay
+
+
+def test_graph_capture_of_the_exponent_form_with_long_rows(potq):
+    """The 16-wavefront exponent-form GEMV needs more LDS than a kernel's default limit; raising
+    the limit is not stream work and must not disturb a capture."""
+    N, K, bits = 4112, 16384, 3
+    assert potq.potq_gemv_exponent_form(N, K, bits)
+    packed, scales = workloads.pot_matrix(9, 40, N, K, bits, 128)
+    tiled, s = potq.potq_repack(dev(packed), K, bits), dev(scales)
+    x = dev(workloads.activations(8, 1, K)[0])
+    y_g = torch.empty((N,), dtype=torch.float16, device="cuda:0")
+    from paper_2507_11959_amd import binding
+    lib = binding.raw()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        st = torch.cuda.current_stream().cuda_stream
+        assert lib.pot_gemv(tiled.data_ptr(), s.data_ptr(), x.data_ptr(), y_g.data_ptr(), N, K, bits, 128, 1, st) == 0
+    eager = potq.pot_gemv(tiled, s, x, K, bits)
+    for replay in range(3):
+        y_g.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_g, eager), replay
