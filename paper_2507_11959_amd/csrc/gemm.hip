@@ -23,6 +23,7 @@
 //    fp32 sums to the caller's workspace and a small second kernel adds them in
 //    a fixed order.
 #include "potq_device.hpp"
+#include "potq_launch.hpp"
 
 namespace potq {
 
@@ -335,6 +336,10 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
     size_t lds = (size_t)2 * CW * 16 * (16 * CN) * sizeof(u32x4);
     const size_t red = KS > 1 ? (size_t)WAVES * RM * CN * kWave * sizeof(float4_t) : 0;
     if (red > lds) lds = red;
+    static std::atomic<uint64_t> lds_raised{0};       // per instantiation of this launcher, i.e. per kernel
+    if (allow_large_lds((const void *)gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN, GC, KS>, lds, lds_raised) !=
+        hipSuccess)
+        return;                                       // the error stays pending for the caller's hipGetLastError()
     hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN, GC, KS>), dim3(gx, gy, (unsigned)splits),
                        dim3(WAVES * kWave), lds, stream, (const uint32_t *)codes, (const uint16_t *)scales,
                        (const uint16_t *)zeros, (const uint16_t *)X, (uint16_t *)Y, (float *)workspace, (int)M, N,
@@ -386,6 +391,27 @@ static void launch_gemm(const void *codes, const void *scales, const void *zeros
     // against 19.3 us on 5120 x 5120 at 64 tokens); the others give every wavefront one row tile
     // and split K over workgroups through the caller's workspace (25.8 against 29.8 us on 13824 x 5120).
     const bool in_group_split = K <= 8192 && N <= 8192;
+    // Large matrices with few row tiles (N <= 8192: the 70B / 30B q, o and down projections) give
+    // every wavefront four row tiles, so that a token fragment read from LDS serves four MFMAs
+    // instead of one or two: with K <= 8192 four wavefronts split K inside the workgroup
+    // (8192 x 8192: 16.6 against 20.5 us at 32 tokens, 24.2 against 30.4 us at 64), longer rows
+    // split K over workgroups (8192 x 28672: 39 against 48 us, 49 against 69 us).  Smaller or
+    // taller matrices measured equal or slower with four row tiles.
+    const bool short_and_big = N <= 8192 && N * K >= (40ll << 20);
+    if (M <= 64 && short_and_big && (K <= 8192 || N * K >= (100ll << 20))) {
+        if (M <= 32) {
+            if (K <= 8192)
+                launch_gemm_cfg<BITS, IS_INT, 8, 4, 2, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            else
+                launch_gemm_cfg<BITS, IS_INT, 8, 4, 2, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        } else {
+            if (K <= 8192)
+                launch_gemm_cfg<BITS, IS_INT, 8, 4, 4, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            else
+                launch_gemm_cfg<BITS, IS_INT, 8, 4, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        }
+        return;
+    }
     if (M <= 32) {
         if (in_group_split)
             launch_gemm_cfg<BITS, IS_INT, 8, 2, 2, 1, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);

@@ -23,8 +23,7 @@
 // The scale must lie in the domain on which the integer add of Sec. 4.2 is the
 // multiplication by 2^E (every scale pot_quantize produces does).
 #include "potq_device.hpp"
-
-#include <atomic>
+#include "potq_launch.hpp"
 
 namespace potq {
 
@@ -357,7 +356,7 @@ static size_t exp_lds_bytes(int64_t K, int waves)
 // and LDS footprint), each with an equal share of the row tiles, so that x is staged as few
 // times as possible and nobody waits for a second wave of workgroups.
 constexpr int kExpGroups = POTQ_EXP_GROUPS;
-constexpr size_t kExpLdsSmall = 64 * 1024, kExpLdsLarge = 160 * 1024;
+constexpr size_t kExpLdsSmall = kLdsDefaultLimit, kExpLdsLarge = kLdsPerWorkgroup;
 
 // Wavefronts per workgroup: eight while two workgroups' digits of x fit the LDS of a compute
 // unit together, else sixteen (two tiles at a time) for one workgroup per compute unit.
@@ -384,23 +383,13 @@ bool gemv_exp_batch_ok(int count, int64_t rows_total, int64_t K, int bits)
     return count <= kMaxExpBatch && gemv_exp_ok(rows_total, K, bits);
 }
 
-// More dynamic LDS than the default limit of a kernel: raise that kernel's limit, once per
-// device and process (the call is not stream work, so it is also legal while a stream is
-// being captured into a graph).
 template <int BITS, bool G64, int WAVES, bool BATCH>
 static hipError_t exp_allow_lds(size_t lds)
 {
-    if (lds <= kExpLdsSmall) return hipSuccess;
-    static std::atomic<uint64_t> raised{0};           // bit d: done on device d (devices past 63: every call)
-    int device = 0;
-    hipError_t e = hipGetDevice(&device);
-    if (e != hipSuccess) return e;
-    if (device < 64 && ((raised.load(std::memory_order_acquire) >> device) & 1u)) return hipSuccess;
+    static std::atomic<uint64_t> raised{0};           // one flag word per kernel instantiation
     const void *kernel = BATCH ? (const void *)gemv_exp_batch_kernel<BITS, G64, WAVES>
                                : (const void *)gemv_exp_kernel<BITS, G64, WAVES>;
-    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kExpLdsLarge);
-    if (e == hipSuccess && device < 64) raised.fetch_or(uint64_t{1} << device, std::memory_order_release);
-    return e;
+    return allow_large_lds(kernel, lds, raised);
 }
 
 // Workgroups for a matrix of `sets` tile sets when it may use `cap` of them: equal shares of sets.

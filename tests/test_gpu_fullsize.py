@@ -149,6 +149,34 @@ def test_config4_gemm_3bit_13b_shapes_sampled_rows(potq, M, is_int):
         assert bool(torch.isfinite(Y).all())
 
 
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("M", [24, 32, 64])
+def test_gemm_few_row_tiles_large_matrices_sampled_rows(potq, M, is_int):
+    """17 to 64 tokens on large matrices with N <= 8192 (four row tiles per wavefront; K split inside
+    the workgroup for K <= 8192, over workgroups for longer rows)."""
+    bits = 3
+    rng = np.random.default_rng(70 + M)
+    for i, (N, K) in enumerate([(8192, 8192), (6656, 6656), (8192, 28672), (6656, 17920)]):
+        packed = workloads.packed_codes(workloads.seed_of(7, i, 0), N, K, bits)
+        X = workloads.activations(workloads.seed_of(7, i, 2) + M, M, K)
+        tiled = potq.potq_repack(dev(packed), K, bits)
+        if is_int:
+            S, Z = workloads.int_scales_zeros(workloads.seed_of(7, i, 3), N, K, bits, G)
+            Y = potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits, workspace=potq.gemm_workspace(M, N, K, bits))
+        else:
+            S, Z = workloads.pot_scales(workloads.seed_of(7, i, 1), N, K, G), None
+            Y = potq.pot_gemm(tiled, dev(S), dev(X), K, bits, workspace=potq.gemm_workspace(M, N, K, bits))
+        rows = np.unique(np.concatenate([[0, 15, 16, 63, 64, N - 1], rng.integers(0, N, 120)]))
+        want = oracle.gemm(packed[rows], S[rows], None if Z is None else Z[rows], X, K, bits, G,
+                           nthreads=_threads())
+        got = host_bits(Y[:, torch.from_numpy(rows).to("cuda:0")].contiguous())
+        e, nw, nfloor = rel_err(got, want, K)
+        assert e <= REL_TOL, ((N, K), M, e, nw, nfloor)
+        assert bool(torch.isfinite(Y).all())
+        del tiled, Y
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("bits", [2, 3])
 def test_second_workload_llama30b_layer(potq, bits):
     """LLaMA-30B-shaped layer: batched dequant (sampled rows + invariants) and the q/k/v and gate/up
