@@ -434,6 +434,9 @@ hipError_t run_gemm_fewtok(bool is_int, const void *codes, const void *scales, c
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 
 bool gemv_multi_ok(int64_t M, int64_t N, int64_t K, int group);
+bool gemv_exp_multi_ok(int64_t M, int64_t N, int64_t K, int bits, int group);
+hipError_t run_gemv_exp_multi(const void *codes, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
+                              int64_t K, int bits, hipStream_t stream);
 size_t gemv_lds_bytes(int64_t K);
 hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
                            void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
@@ -448,6 +451,12 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
     // one token is a GEMV
     if (M == 1 && gemv_lds_bytes(K) <= 64 * 1024)
         return run_gemv_tile16(is_int, codes, scales, zeros, X, Y, N, K, bits, group, stream);
+#ifndef POTQ_GEMV_EXP_MULTI
+#define POTQ_GEMV_EXP_MULTI 1
+#endif
+    // two to four tokens on a large PoT matrix: the exponent form of the GEMV with one MFMA per vector and step
+    if (POTQ_GEMV_EXP_MULTI && !is_int && gemv_exp_multi_ok(M, N, K, bits, group))
+        return run_gemv_exp_multi(codes, scales, X, Y, M, N, K, bits, stream);
     // two to four tokens: the GEMV kernel with one activation vector per result column
     if (gemv_multi_ok(M, N, K, group)) return run_gemv_multi(is_int, codes, scales, zeros, X, Y, M, N, K, bits, stream);
     if (M <= 16)

@@ -317,6 +317,183 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_kernel(
     gemv_exp_body<BITS, G64, WAVES>(codes, scales, x, y, K, rowtiles, blockIdx.x, gridDim.x);
 }
 
+// ---------------------------------------------------------------------------
+// Two to four activation vectors at once (a GEMM with two to four tokens), group size 128:
+// the matrix is decoded once per step and every vector costs one more MFMA per step and its
+// own digit planes in LDS (each vector has its own fixed-point exponent).  Here all lanes read
+// LDS -- the off-diagonal ones a block of zeros -- so the A operands need no registers of their
+// own between steps.  Vectors past `tokens` count as zero.  Results y[m * ystride + n].
+// ---------------------------------------------------------------------------
+template <int BITS, int WAVES, int MT>
+__global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
+    const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const u32x4 *__restrict__ x,
+    uint16_t *__restrict__ y, int K, int64_t rowtiles, int tokens, int64_t ystride)
+{
+    constexpr int kStep = 4 * kExpSplit;
+    constexpr int SLOTS = WAVES / kExpSplit;
+    constexpr int THREADS = WAVES * kWave;
+    extern __shared__ u32x4 smem[];
+    const int G = K / kTileCols;
+    u32x4 *pieces = smem;                               // [vector][group][digit] runs of kPieceRun uint4
+    u32x4 *zero_block = smem + MT * G * 4 * kPieceRun;  // 8 uint4 of zeros
+    float *red = (float *)(zero_block + 8);             // 2 x WAVES x MT x 16 partial sums
+    uint32_t *amax_part = (uint32_t *)(red + 2 * WAVES * MT * kTileRows);   // WAVES x MT
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int part = wave % kExpSplit;
+    const int slot = wave / kExpSplit;
+    const int r = lane & 15;
+    const int t = lane >> 4;
+    const int scale_owner = (4 * r + t) * 4;
+    const int my_rounds = (G - part * 4 + kStep - 1) / kStep;
+    const int64_t first = blockIdx.x, stride = gridDim.x;
+    auto tile_of = [&](int64_t q) { return min(q * SLOTS + slot, rowtiles - 1); };
+
+    auto fetch = [&](int64_t tile, int round, u32x4 (&Lx)[BITS], uint32_t &sx) {
+        const int g0 = round * kStep + part * 4;
+        const int gc = min(g0 + t, G - 1);
+        const u32x4 *tile_codes = codes + tile * G * (BITS * 16);
+        const uint32_t at = (uint32_t)(gc * (BITS * 16) + r);
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) Lx[j] = __builtin_nontemporal_load(tile_codes + at + 16 * j);
+        const uint16_t *tile_scales = scales + tile * kTileRows * (int64_t)G;
+        sx = tile_scales[(uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1))];
+    };
+    int64_t fq = first;
+    int fround = 0;
+    auto advance = [&]() {
+        if (fround + 1 < my_rounds) {
+            ++fround;
+        } else if ((fq + stride) * SLOTS < rowtiles) {
+            fq += stride;
+            fround = 0;
+        }
+    };
+    u32x4 L[BITS];
+    uint32_t s;
+    fetch(tile_of(fq), fround, L, s);
+    advance();
+
+    // --- activations: per vector the largest exponent, then fixed point digits into LDS ---
+    const int per = K / 8;                              // octets per vector
+    const int octets = MT * per;
+    u32x4 xv[kExpOctetsPerThread];
+    int vec[kExpOctetsPerThread];
+    uint32_t am[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) am[m] = 0u;
+#pragma unroll
+    for (int n = 0; n < kExpOctetsPerThread; ++n) {
+        const int i = tid + n * THREADS;
+        vec[n] = i / per;
+        xv[n] = (i < octets && vec[n] < tokens) ? x[i] : u32x4{0u, 0u, 0u, 0u};
+        uint32_t a = 0u;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            a = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a),
+                                                                       __builtin_bit_cast(ushort2_t, xv[n][w] & 0x7FFF7FFFu)));
+        a = max(a & 0xFFFFu, a >> 16);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) am[m] = vec[n] == m ? max(am[m], a) : am[m];
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) am[m] = max(am[m], (uint32_t)__shfl_xor((int)am[m], off, kWave));
+        if (lane == 0) amax_part[wave * MT + m] = am[m];
+    }
+    if (tid < 8) zero_block[tid] = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
+    float two_k[MT], two_mk[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+#pragma unroll
+        for (int p = 0; p < WAVES; ++p) am[m] = max(am[m], amax_part[p * MT + m]);
+        const int e = max((int)(am[m] >> 10), 1);
+        const int k = 44 - e;
+        two_k[m] = __builtin_bit_cast(float, (uint32_t)(k + 127) << 23);
+        two_mk[m] = e == 31 ? __builtin_nanf("") : __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
+    }
+#pragma unroll
+    for (int n = 0; n < kExpOctetsPerThread; ++n) {
+        const int i = tid + n * THREADS;
+        if (i < octets) {
+            float scale = two_k[0];
+#pragma unroll
+            for (int m = 1; m < MT; ++m) scale = vec[n] == m ? two_k[m] : scale;
+            stage_digits(xv[n], pieces + vec[n] * G * 4 * kPieceRun, i - vec[n] * per, scale);
+        }
+    }
+    __syncthreads();
+
+    const bool diagonal = (r >> 2) == t;
+    int it = 0;
+    for (int64_t q = first; q * SLOTS < rowtiles; q += stride, ++it) {
+        float row_sum[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) row_sum[m] = 0.f;
+        for (int round = 0; round < my_rounds; ++round) {
+            u32x4 Ln[BITS];
+            uint32_t sn;
+            fetch(tile_of(fq), fround, Ln, sn);
+            advance();
+            const int g = round * kStep + part * 4 + t;
+            const bool mine = diagonal && g < G;
+            const u32x4 *xq[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                xq[m] = mine ? pieces + ((m * G + g) * 4 + (lane & 3)) * kPieceRun : zero_block;
+            const uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)s);
+            int4_t d[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m) d[m] = int4_t{0, 0, 0, 0};
+            ExpDecoder<BITS> dec;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                uint32_t w[BITS];
+#pragma unroll
+                for (int j = 0; j < BITS; ++j) w[j] = L[j][b];
+                dec.set_block(w);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const u32x4 wt{dec.get(4 * h), dec.get(4 * h + 1), dec.get(4 * h + 2), dec.get(4 * h + 3)};
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+                        d[m] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(int4_t, xq[m][2 * b + h]),
+                                                                     __builtin_bit_cast(int4_t, wt), d[m], 0, 0, 0);
+                }
+            }
+            const float sf = (float)__builtin_bit_cast(_Float16, (uint16_t)so);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) row_sum[m] = __builtin_fmaf(sf, exp_recombine(d[m]), row_sum[m]);
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
+            s = sn;
+        }
+
+        float *red_it = red + (it & 1) * (WAVES * MT * kTileRows);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            float v = row_sum[m] * two_mk[m];
+            v += __shfl_xor(v, 16, kWave);
+            v += __shfl_xor(v, 32, kWave);
+            if (t == 0) red_it[(wave * MT + m) * kTileRows + r] = v;
+        }
+        __syncthreads();
+        if (tid < SLOTS * MT * kTileRows) {
+            const int of_slot = tid / (MT * kTileRows), m = (tid / kTileRows) % MT, row = tid % kTileRows;
+            const int64_t tile = q * SLOTS + of_slot;
+            float sum = 0.f;
+#pragma unroll
+            for (int p = 0; p < kExpSplit; ++p) sum += red_it[((of_slot * kExpSplit + p) * MT + m) * kTileRows + row];
+            const _Float16 h = (_Float16)sum;
+            if (tile < rowtiles && m < tokens) y[m * ystride + tile * kTileRows + row] = __builtin_bit_cast(uint16_t, h);
+        }
+    }
+}
+
 // Several matrices that consume the same activation vector in one launch: a workgroup belongs
 // to one matrix and walks that matrix's tiles as in the single launch.
 constexpr int kMaxExpBatch = 16;
@@ -471,6 +648,64 @@ hipError_t run_gemv_exp_batch(int count, const void *const *codes, const void *c
     if (exp_waves(K) == 8) return bits == 3 ? POTQ_LAUNCH_EXPB(3, 8) : POTQ_LAUNCH_EXPB(2, 8);
     return bits == 3 ? POTQ_LAUNCH_EXPB(3, 16) : POTQ_LAUNCH_EXPB(2, 16);
 #undef POTQ_LAUNCH_EXPB
+}
+
+// ---- two to four tokens ----
+static size_t exp_multi_lds_bytes(int64_t K, int waves, int mt)
+{
+    return (size_t)mt * (K / kTileCols) * 4 * kPieceRun * 16 + 8 * 16 +
+           2 * (size_t)waves * mt * kTileRows * sizeof(float) + (size_t)waves * mt * sizeof(uint32_t);
+}
+
+// eight wavefronts while two workgroups fit the LDS of a compute unit together, else sixteen
+static int exp_multi_waves(int64_t K, int mt) { return 2 * exp_multi_lds_bytes(K, 8, mt) <= kExpLdsLarge ? 8 : 16; }
+
+// Whether a PoT GEMM with M = 2..4 tokens is served in the exponent form: the conditions of the
+// GEMV plus group size 128, room in LDS for the digits of all vectors, and a matrix tall enough
+// for a workgroup to reuse them on several row tiles.  Measured at 3 bits against the kernels
+// that serve the other shapes: two tokens, 28672 x 8192: 20.3 against 26.6 us, 17920 x 6656: 15.3
+// against 17.2 us, 13824 x 5120: 11.3 against 11.9 us, but 8192 x 8192 (one tile per workgroup):
+// 11.0 against 8.8 us; three and four tokens (LDS reads of four vectors' digits weigh more):
+// 17920 x 6656: 21.5 against 26.5 us, 28672 x 8192: 27.7 against 27.9 us, but 13824 x 5120: 15.2
+// against 11.9 us.
+bool gemv_exp_multi_ok(int64_t M, int64_t N, int64_t K, int bits, int group)
+{
+    if (M < 2 || M > 4 || group != 128 || !gemv_exp_ok(N, K, bits)) return false;
+    if (N / kTileRows < (M == 2 ? kExpGroups + 1 : 2 * kExpGroups)) return false;
+    const int mt = M <= 2 ? 2 : 4;
+    const int waves = exp_multi_waves(K, mt);
+    if ((int64_t)mt * K > (int64_t)kExpOctetsPerThread * waves * kWave * 8) return false;
+    return exp_multi_lds_bytes(K, waves, mt) <= kExpLdsLarge;
+}
+
+template <int BITS, int WAVES, int MT>
+static hipError_t launch_exp_multi(const void *codes, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
+                                   int64_t K, hipStream_t stream)
+{
+    static std::atomic<uint64_t> raised{0};
+    const size_t lds = exp_multi_lds_bytes(K, WAVES, MT);
+    const hipError_t e = allow_large_lds((const void *)gemv_exp_multi_kernel<BITS, WAVES, MT>, lds, raised);
+    if (e != hipSuccess) return e;
+    constexpr int SLOTS = WAVES / kExpSplit;
+    const int64_t rowtiles = N / kTileRows;
+    const dim3 grid((unsigned)exp_groups((rowtiles + SLOTS - 1) / SLOTS, kExpGroups / SLOTS)), block(WAVES * kWave);
+    hipLaunchKernelGGL((gemv_exp_multi_kernel<BITS, WAVES, MT>), grid, block, lds, stream, (const u32x4 *)codes,
+                       (const uint16_t *)scales, (const u32x4 *)X, (uint16_t *)Y, (int)K, rowtiles, (int)M, N);
+    return hipGetLastError();
+}
+
+hipError_t run_gemv_exp_multi(const void *codes, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
+                              int64_t K, int bits, hipStream_t stream)
+{
+    const int mt = M <= 2 ? 2 : 4;
+    const int waves = exp_multi_waves(K, mt);
+#define POTQ_LAUNCH_EXPM(BITS)                                                                              \
+    (waves == 8 ? (mt == 2 ? launch_exp_multi<BITS, 8, 2>(codes, scales, X, Y, M, N, K, stream)             \
+                           : launch_exp_multi<BITS, 8, 4>(codes, scales, X, Y, M, N, K, stream))            \
+                : (mt == 2 ? launch_exp_multi<BITS, 16, 2>(codes, scales, X, Y, M, N, K, stream)            \
+                           : launch_exp_multi<BITS, 16, 4>(codes, scales, X, Y, M, N, K, stream)))
+    return bits == 3 ? POTQ_LAUNCH_EXPM(3) : POTQ_LAUNCH_EXPM(2);
+#undef POTQ_LAUNCH_EXPM
 }
 
 }  // namespace potq

@@ -109,3 +109,28 @@ def test_gemm_with_one_token_takes_the_same_path(potq):
     y1 = host_bits(potq.pot_gemv(tiled, dev(S), dev(x), K, bits))
     y2 = host_bits(potq.pot_gemm(tiled, dev(S), dev(x[None, :]), K, bits))[0]
     assert np.array_equal(y1, y2)
+
+
+@pytest.mark.parametrize("M,N,K,bits", [
+    (2, 8208, 8192, 3),        # two tokens: eight wavefronts, two workgroups' digits share a compute unit's LDS
+    (2, 10240, 13824, 2),      # two tokens, long rows: sixteen wavefronts
+    (3, 16400, 8192, 3),       # three tokens in the four-vector kernel (the fourth counts as zero), 1025 row tiles
+    (4, 17920, 6656, 2),       # four tokens, ragged group count (52)
+])
+def test_two_to_four_tokens(potq, M, N, K, bits):
+    """pot_gemm with two to four tokens on tall, large matrices runs the exponent form with one
+    MFMA per vector and step; every vector has its own fixed-point exponent (rows of X differ
+    in scale by up to 2^12 here)."""
+    rng = np.random.default_rng(100 + M)
+    packed, S = workloads.pot_matrix(6, 50 + M, N, K, bits, 128)
+    X = np.stack([_x("outlier" if m % 2 else "normal", K, 60 + m).astype(np.float32) * 2.0 ** (-4 * m)
+                  for m in range(M)]).astype(np.float16)
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    Y = potq.pot_gemm(tiled, dev(S), dev(X), K, bits)
+    rows = np.unique(np.concatenate([[0, 15, 16, N - 17, N - 1], rng.integers(0, N, 400)]))
+    want = oracle.gemm(packed[rows], S[rows], None, X, K, bits, 128, nthreads=_threads())
+    got = host_bits(Y[:, torch.from_numpy(rows).to("cuda:0")].contiguous())
+    for m in range(M):                       # per token: the rows differ in scale, and so does the error floor
+        e, nw, nfloor = rel_err(got[m], want[m], K)
+        assert e <= REL_TOL, (M, N, K, bits, m, e, nw, nfloor)
+    assert bool(torch.isfinite(Y).all())
