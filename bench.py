@@ -329,43 +329,48 @@ def main() -> int:
         torch.cuda.empty_cache()
 
         # the seven projections of one decoder layer at batch 1 as a decoder issues them: q/k/v in one launch,
-        # o, gate/up in one launch, down (four launches), rotating through 16 layers' worth of weights
-        # (0.63 GB of 3-bit codes); random bytes are valid codes, the activations are unrelated vectors
-        LAYERS = 16
-        layer_bytes = sum(workloads.algorithmic_bytes_gemm(1, N, K, b3, G) for _, N, K in workloads.LLAMA2_7B_LAYER)
-        x4k = to_dev(workloads.activations(workloads.seed_of(2, 8, 2), 1, 4096)[0])
-        x11k = to_dev(workloads.activations(workloads.seed_of(2, 9, 2), 1, 11008)[0])
-        keep, steps_ = [], []
-        for _ in range(LAYERS):
-            def mat(N, K):
-                c = torch.randint(0, 256, (N, K * b3 // 8), dtype=torch.uint8, device=dev, generator=gen)
-                sc_ = to_dev(workloads.pot_scales(workloads.seed_of(2, 8, 1), N, K, G))
-                return (c, sc_, None, torch.empty((N,), dtype=torch.float16, device=dev))
-            qkv = [mat(4096, 4096) for _ in range(3)]
-            o = mat(4096, 4096)
-            gu = [mat(11008, 4096) for _ in range(2)]
-            dn = mat(4096, 11008)
-            keep.append((qkv, o, gu, dn))
-            steps_.append((binding.make_gemv_batch(qkv, 4096, b3), binding.make_gemv_batch(gu, 4096, b3),
-                           (o[0].data_ptr(), o[1].data_ptr(), x4k.data_ptr(), o[3].data_ptr(), 4096, 4096, b3, G, 1, stream),
-                           (dn[0].data_ptr(), dn[1].data_ptr(), x11k.data_ptr(), dn[3].data_ptr(), 4096, 11008, b3, G, 1,
-                            stream)))
+        # o, gate/up in one launch, down (four launches), rotating through enough layers' worth of weights to
+        # exceed the last-level cache; random bytes are valid codes, the activations are unrelated vectors
+        def decoder_layer_batch1(hidden, kv_rows, ffn, layers):
+            shapes = [(hidden, hidden), (kv_rows, hidden), (kv_rows, hidden), (hidden, hidden),
+                      (ffn, hidden), (ffn, hidden), (hidden, ffn)]
+            layer_bytes = sum(workloads.algorithmic_bytes_gemm(1, N, K, b3, G) for N, K in shapes)
+            xh = to_dev(workloads.activations(workloads.seed_of(2, 8, 2), 1, hidden)[0])
+            xf = to_dev(workloads.activations(workloads.seed_of(2, 9, 2), 1, ffn)[0])
+            keep, steps_ = [], []
+            for _ in range(layers):
+                def mat(N, K):
+                    c = torch.randint(0, 256, (N, K * b3 // 8), dtype=torch.uint8, device=dev, generator=gen)
+                    sc_ = to_dev(workloads.pot_scales(workloads.seed_of(2, 8, 1), N, K, G))
+                    return (c, sc_, None, torch.empty((N,), dtype=torch.float16, device=dev))
+                qkv = [mat(hidden, hidden), mat(kv_rows, hidden), mat(kv_rows, hidden)]
+                o = mat(hidden, hidden)
+                gu = [mat(ffn, hidden) for _ in range(2)]
+                dn = mat(hidden, ffn)
+                keep.append((qkv, o, gu, dn))
+                steps_.append((binding.make_gemv_batch(qkv, hidden, b3), binding.make_gemv_batch(gu, hidden, b3),
+                               (o[0].data_ptr(), o[1].data_ptr(), xh.data_ptr(), o[3].data_ptr(), hidden, hidden, b3, G,
+                                1, stream),
+                               (dn[0].data_ptr(), dn[1].data_ptr(), xf.data_ptr(), dn[3].data_ptr(), hidden, ffn, b3, G,
+                                1, stream)))
 
-        def layer_rot():
-            for b_qkv, b_gu, c_o, c_dn in steps_:
-                check(lib.pot_gemv_batch(b_qkv, 3, x4k.data_ptr(), 4096, b3, G, 1, stream))
-                check(lib.pot_gemv(*c_o))
-                check(lib.pot_gemv_batch(b_gu, 2, x4k.data_ptr(), 4096, b3, G, 1, stream))
-                check(lib.pot_gemv(*c_dn))
+            def layer_rot():
+                for b_qkv, b_gu, c_o, c_dn in steps_:
+                    check(lib.pot_gemv_batch(b_qkv, 3, xh.data_ptr(), hidden, b3, G, 1, stream))
+                    check(lib.pot_gemv(*c_o))
+                    check(lib.pot_gemv_batch(b_gu, 2, xh.data_ptr(), hidden, b3, G, 1, stream))
+                    check(lib.pot_gemv(*c_dn))
 
-        us_layer = _time_steps(torch, layer_rot, 8, 2) * 1e3 / LAYERS
-        extras["pot_gemv_3bit_7b_decoder_layer_batch1"] = {
-            "us_per_layer": round(us_layer, 2), "launches_per_layer": 4,
-            "GBps": round(layer_bytes / us_layer / 1e3, 1),
-            "pct_hbm_peak": round(layer_bytes / us_layer / 1e3 / HBM_PEAK_GBPS * 100, 1),
-            "layers_rotated": LAYERS}
-        del keep, steps_
-        torch.cuda.empty_cache()
+            us_layer = _time_steps(torch, layer_rot, max(2, 128 // layers), 2) * 1e3 / layers
+            del keep, steps_
+            torch.cuda.empty_cache()
+            return {"us_per_layer": round(us_layer, 2), "launches_per_layer": 4,
+                    "GBps": round(layer_bytes / us_layer / 1e3, 1),
+                    "pct_hbm_peak": round(layer_bytes / us_layer / 1e3 / HBM_PEAK_GBPS * 100, 1),
+                    "layers_rotated": layers}
+
+        extras["pot_gemv_3bit_7b_decoder_layer_batch1"] = decoder_layer_batch1(4096, 4096, 11008, 16)
+        extras["pot_gemv_3bit_70b_decoder_layer_batch1"] = decoder_layer_batch1(8192, 1024, 28672, 3)
 
         # Llama-2-70B layer (GQA shapes): stand-alone dequant of all seven matrices in one launch at 2 and 3
         # bits (four rotating code sets: 0.9 / 1.3 GB of codes), and the batch-1 GEMV of its four distinct shapes
