@@ -171,7 +171,10 @@ int int_gemv(const void *codes, const void *scales, const void *zeros, const voi
 /*
  * 1 if pot_gemv (and pot_gemm with one token) serves an N x K matrix of this
  * width in the exponent form described above, else 0.  For pot_gemv_batch pass
- * the total number of rows of the matrices that share the launch.
+ * the total number of rows of the matrices that share the launch.  pot_gemm
+ * with two to four tokens uses the same form (every token with its own
+ * fixed-point exponent) on a subset of these shapes: group size 128 and more
+ * than 8192 rows (two tokens) or at least 16384 (three, four).
  */
 int potq_gemv_exponent_form(int64_t N, int64_t K, int bits);
 
@@ -202,7 +205,9 @@ int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f1
  * pot_gemm -- fused de-quantise + GEMM on the matrix cores:
  *   Y[m,n] = fp16( sum_k X[m,k] * W~[n,k] ),   X: M x K fp16 row-major,
  *   Y: M x N fp16 row-major (Y = X . W~^T, the nn.Linear convention).
- * fp16 MFMA with fp32 accumulation.  `codes` must be in POTQ_LAYOUT_TILE16.
+ * fp16 MFMA with fp32 accumulation (up to four tokens on large 2-/3-bit PoT
+ * matrices: the exponent form described at pot_gemv, with its conditions on
+ * scales and non-finite activations).  `codes` must be in POTQ_LAYOUT_TILE16.
  *
  * `workspace` is optional device scratch memory (16-byte aligned) owned by the
  * caller.  With few tokens there are too few output tiles to occupy the chip, so
