@@ -55,7 +55,10 @@ struct ExpDecoder {
 // Eight 16-byte LDS reads by the lanes of `lanes` only, which leave the registers of the other
 // lanes untouched: the off-diagonal lanes of the A operand hold zeros, written once, and never
 // read LDS.  The compiler does not count these reads, so lds_wait() stands between them and
-// their first use.
+// their first use.  They overwrite registers that the MFMAs of the previous round read: the
+// caller must have consumed those MFMAs' results (the recombination does) before it issues the
+// next reads -- an MFMA that has been issued but not started may not have read its operands yet
+// (re-reading the registers right after issuing the MFMAs gave wrong results).
 typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 __device__ __forceinline__ void lds_read_keep(u32x4 (&xa)[8], uint32_t lds_byte_address, uint64_t lanes)
 {
