@@ -50,11 +50,28 @@ def _check(potq, N, K, bits, group, kind="normal", seed=0):
     tiled = potq.potq_repack(dev(packed), K, bits)
     got = host_bits(potq.pot_gemv(tiled, dev(S), dev(x), K, bits, group))
     want = oracle.gemm(packed, S, None, x[None, :], K, bits, group, nthreads=_threads())[0]
-    finite = np.isfinite(want.view(np.float16))      # sums beyond the fp16 range: the same infinity on both sides
-    assert np.array_equal(got[~finite], want[~finite])
-    e, nw, nfloor = rel_err(got[finite], want[finite], K)
-    assert e <= REL_TOL, (N, K, bits, group, kind, e, nw, nfloor)
+    _assert_close(got, want, K, (N, K, bits, group, kind))
     return got, want
+
+
+def _assert_close(got, want, K, what):
+    """The fused kernels' gate, |y - ref| <= 2e-3 * max(|ref|, floor), with the two ends of the fp16
+    range treated as what they are: a sum beyond the range is the same infinity on both sides, and
+    an output below the normal range (|ref| < 2^-14, which tiny or subnormal activations produce)
+    is a multiple of 2^-24, so one such quantum is allowed on top -- there it is a relative error
+    far above any tolerance and means nothing."""
+    from gpu_util import floor_fraction
+    w = want.view(np.float16).astype(np.float64)
+    g = got.view(np.float16).astype(np.float64)
+    finite = np.isfinite(w)
+    assert np.array_equal(got[~finite], want[~finite]), what
+    w, g = w[finite], g[finite]
+    if w.size == 0:
+        return
+    floor = np.sqrt(np.mean(w * w)) * floor_fraction(K)
+    allowed = REL_TOL * np.maximum(np.abs(w), floor) + np.where(np.abs(w) < 2.0 ** -14, 2.0 ** -24, 0.0)
+    excess = np.abs(g - w) - allowed
+    assert excess.max() <= 0.0, (what, float((np.abs(g - w) / np.maximum(np.abs(w), max(floor, 1e-300))).max()))
 
 
 @pytest.mark.parametrize("N,K,bits,group", [
