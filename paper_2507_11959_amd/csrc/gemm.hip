@@ -319,7 +319,7 @@ static int choose_splits(int64_t workgroups, int waves, int ks, int64_t G, int64
 }
 
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC, int KS = 1>
-static void launch_gemm_cfg(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
+static hipError_t launch_gemm_cfg(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                             int64_t M, int64_t N, int64_t K, int group, void *workspace, size_t workspace_bytes,
                             hipStream_t stream)
 {
@@ -337,9 +337,9 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
     const size_t red = KS > 1 ? (size_t)WAVES * RM * CN * kWave * sizeof(float4_t) : 0;
     if (red > lds) lds = red;
     static std::atomic<uint64_t> lds_raised{0};       // per instantiation of this launcher, i.e. per kernel
-    if (allow_large_lds((const void *)gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN, GC, KS>, lds, lds_raised) !=
-        hipSuccess)
-        return;                                       // the error stays pending for the caller's hipGetLastError()
+    const hipError_t lds_status =
+        allow_large_lds((const void *)gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN, GC, KS>, lds, lds_raised);
+    if (lds_status != hipSuccess) return lds_status;
     hipLaunchKernelGGL((gemm_tile16_kernel<BITS, IS_INT, WAVES, RM, CN, GC, KS>), dim3(gx, gy, (unsigned)splits),
                        dim3(WAVES * kWave), lds, stream, (const uint32_t *)codes, (const uint16_t *)scales,
                        (const uint16_t *)zeros, (const uint16_t *)X, (uint16_t *)Y, (float *)workspace, (int)M, N,
@@ -349,6 +349,7 @@ static void launch_gemm_cfg(const void *codes, const void *scales, const void *z
         hipLaunchKernelGGL(gemm_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
                            (const float4_t *)workspace, (uint16_t *)Y, quads, splits);
     }
+    return hipGetLastError();
 }
 
 
@@ -382,8 +383,9 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N)
 }
 
 template <int BITS, bool IS_INT>
-static void launch_gemm(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
-                        int64_t M, int64_t N, int64_t K, int group, void *ws, size_t ws_bytes, hipStream_t stream)
+static hipError_t launch_gemm(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
+                              int64_t M, int64_t N, int64_t K, int group, void *ws, size_t ws_bytes,
+                              hipStream_t stream)
 {
     // 17 to 64 tokens: not enough output tiles for the chip; eight wavefronts per workgroup.
     // Small, short matrices (K <= 8192, N <= 8192) let pairs of wavefronts split K inside the
@@ -401,32 +403,31 @@ static void launch_gemm(const void *codes, const void *scales, const void *zeros
     if (M <= 64 && short_and_big && (K <= 8192 || N * K >= (100ll << 20))) {
         if (M <= 32) {
             if (K <= 8192)
-                launch_gemm_cfg<BITS, IS_INT, 8, 4, 2, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+                return launch_gemm_cfg<BITS, IS_INT, 8, 4, 2, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
             else
-                launch_gemm_cfg<BITS, IS_INT, 8, 4, 2, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+                return launch_gemm_cfg<BITS, IS_INT, 8, 4, 2, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         } else {
             if (K <= 8192)
-                launch_gemm_cfg<BITS, IS_INT, 8, 4, 4, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+                return launch_gemm_cfg<BITS, IS_INT, 8, 4, 4, 1, 4>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
             else
-                launch_gemm_cfg<BITS, IS_INT, 8, 4, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+                return launch_gemm_cfg<BITS, IS_INT, 8, 4, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         }
-        return;
     }
     if (M <= 32) {
         if (in_group_split)
-            launch_gemm_cfg<BITS, IS_INT, 8, 2, 2, 1, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 2, 1, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else
-            launch_gemm_cfg<BITS, IS_INT, 8, 1, 2, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            return launch_gemm_cfg<BITS, IS_INT, 8, 1, 2, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else if (M <= 64) {
         if (in_group_split)
-            launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1, 2>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else
-            launch_gemm_cfg<BITS, IS_INT, 8, 1, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            return launch_gemm_cfg<BITS, IS_INT, 8, 1, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
         if (wide_tile(M, N))
-            launch_gemm_cfg<BITS, IS_INT, 8, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
         else
-            launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     }
 }
 
@@ -434,6 +435,9 @@ hipError_t run_gemm_fewtok(bool is_int, const void *codes, const void *scales, c
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 
 bool gemv_multi_ok(int64_t M, int64_t N, int64_t K, int group);
+#ifndef POTQ_GEMV_EXP_MULTI
+#define POTQ_GEMV_EXP_MULTI 1                         // 0: build without the multi-vector exponent form (for A/B timing)
+#endif
 bool gemv_exp_multi_ok(int64_t M, int64_t N, int64_t K, int bits, int group);
 hipError_t run_gemv_exp_multi(const void *codes, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
                               int64_t K, int bits, hipStream_t stream);
@@ -451,9 +455,6 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
     // one token is a GEMV
     if (M == 1 && gemv_lds_bytes(K) <= 64 * 1024)
         return run_gemv_tile16(is_int, codes, scales, zeros, X, Y, N, K, bits, group, stream);
-#ifndef POTQ_GEMV_EXP_MULTI
-#define POTQ_GEMV_EXP_MULTI 1
-#endif
     // two to four tokens on a large PoT matrix: the exponent form of the GEMV with one MFMA per vector and step
     if (POTQ_GEMV_EXP_MULTI && !is_int && gemv_exp_multi_ok(M, N, K, bits, group))
         return run_gemv_exp_multi(codes, scales, X, Y, M, N, K, bits, stream);
@@ -462,15 +463,14 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
     if (M <= 16)
         return run_gemm_fewtok(is_int, codes, scales, zeros, X, Y, M, N, K, bits, group, stream);
     if (is_int) {
-        if (bits == 4) launch_gemm<4, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
-        else if (bits == 3) launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
-        else launch_gemm<2, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        if (bits == 4) return launch_gemm<4, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else if (bits == 3) return launch_gemm<3, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else return launch_gemm<2, true>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
-        if (bits == 4) launch_gemm<4, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
-        else if (bits == 3) launch_gemm<3, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
-        else launch_gemm<2, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        if (bits == 4) return launch_gemm<4, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else if (bits == 3) return launch_gemm<3, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        else return launch_gemm<2, false>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     }
-    return hipGetLastError();
 }
 
 }  // namespace potq
