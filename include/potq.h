@@ -148,7 +148,7 @@ int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits,
  *   x_f16 in  K fp16;   y_f16 out  N fp16
  * `layout` names the layout `codes` is in; only POTQ_LAYOUT_TILE16 is accepted
  * (POTQ_ERR_LAYOUT otherwise; potq_repack converts), which needs N % 16 == 0.
- * The whole of x is held in on-chip memory: K <= 30464 (POTQ_ERR_SHAPE beyond).
+ * The whole of x is held in on-chip memory: K <= 76672 (POTQ_ERR_SHAPE beyond).
  *
  * Large 2- and 3-bit matrices (potq_gemv_exponent_form() tells which) are served
  * in the exponent form of the product (Sec. 4.2, additivity of exponents):

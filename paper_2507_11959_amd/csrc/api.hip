@@ -38,6 +38,7 @@ hipError_t run_quantize(const void *W, void *codes, void *scales, int64_t N, int
 namespace {
 
 constexpr int64_t kMaxDim = (int64_t)1 << 30;
+constexpr size_t kMaxLdsBytes = 160 * 1024;        // LDS a gfx950 workgroup can be given
 
 bool misaligned(const void *p, uintptr_t a = 16) { return ((uintptr_t)p & (a - 1)) != 0; }
 
@@ -111,7 +112,7 @@ int gemv_entry(bool is_int, const void *codes, const void *scales, const void *z
     if (!codes || !scales || !x || (is_int && !zeros)) return POTQ_ERR_NULL;
     if (misaligned(codes) || misaligned(scales) || misaligned(x) || (is_int && misaligned(zeros)))
         return POTQ_ERR_ALIGN;
-    if (potq::gemv_lds_bytes(K) > 64 * 1024) return POTQ_ERR_SHAPE;
+    if (potq::gemv_lds_bytes(K) > kMaxLdsBytes) return POTQ_ERR_SHAPE;
     return finish(potq::run_gemv_tile16(is_int, codes, scales, zeros, x, y, N, K, bits, group, (hipStream_t)stream));
 }
 
@@ -152,7 +153,7 @@ int gemv_batch_entry(bool is_int, const potq_gemv_item *items, int count, const 
     if (live == 0) return POTQ_OK;
     if (!x) return POTQ_ERR_NULL;
     if (misaligned(x)) return POTQ_ERR_ALIGN;
-    if (potq::gemv_lds_bytes(K) > 64 * 1024) return POTQ_ERR_SHAPE;
+    if (potq::gemv_lds_bytes(K) > kMaxLdsBytes) return POTQ_ERR_SHAPE;
     return finish(potq::run_gemv_tile16_batch(is_int, live, codes, scales, zeros, y, N, x, K, bits, group,
                                               (hipStream_t)stream));
 }

@@ -453,7 +453,7 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
 {
     // up to 16 tokens: the kernel built like the GEMV (one table per 128 weights, no cross-lane code traffic)
     // one token is a GEMV
-    if (M == 1 && gemv_lds_bytes(K) <= 64 * 1024)
+    if (M == 1 && gemv_lds_bytes(K) <= kLdsPerWorkgroup)
         return run_gemv_tile16(is_int, codes, scales, zeros, X, Y, N, K, bits, group, stream);
     // two to four tokens on a large PoT matrix: the exponent form of the GEMV with one MFMA per vector and step
     if (POTQ_GEMV_EXP_MULTI && !is_int && gemv_exp_multi_ok(M, N, K, bits, group))

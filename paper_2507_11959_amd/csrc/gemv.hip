@@ -13,6 +13,7 @@
 // The same file holds the fused GEMM for up to 16 tokens (gemm_fewtok_kernel),
 // which keeps this lane-owns-a-group scheme and makes the tokens the B operand.
 #include "potq_device.hpp"
+#include "potq_launch.hpp"
 
 namespace potq {
 
@@ -547,7 +548,7 @@ static int gemv_split(int64_t G)
 }
 
 template <int BITS, bool IS_INT>
-static void launch_gemv(const void *codes, const void *scales, const void *zeros, const void *x, void *y,
+static hipError_t launch_gemv(const void *codes, const void *scales, const void *zeros, const void *x, void *y,
                         int64_t N, int64_t K, int group, hipStream_t stream)
 {
     const int64_t rowtiles = N / kTileRows;
@@ -556,16 +557,21 @@ static void launch_gemv(const void *codes, const void *scales, const void *zeros
 #define POTQ_LAUNCH_GEMV(SPLIT, COL0)                                                                              \
     do {                                                                                                           \
         const dim3 grid((unsigned)((rowtiles + (kGemvWaves / SPLIT) - 1) / (kGemvWaves / SPLIT)));                 \
-        if (group == 64)                                                                                           \
+        if (group == 64) {                                                                                         \
+            if (const hipError_t e_ = allow_large_lds<gemv_tile16_kernel<BITS, IS_INT, SPLIT, true, COL0>>(lds))   \
+                return e_;                                                                                         \
             hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT, true, COL0>), grid,                        \
                                dim3(kGemvWaves * kWave), lds, stream, (const u32x4 *)codes,                        \
                                (const uint16_t *)scales, (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, \
                                rowtiles, (int)K);                                                                  \
-        else                                                                                                       \
+        } else {                                                                                                   \
+            if (const hipError_t e_ = allow_large_lds<gemv_tile16_kernel<BITS, IS_INT, SPLIT, false, COL0>>(lds))  \
+                return e_;                                                                                         \
             hipLaunchKernelGGL((gemv_tile16_kernel<BITS, IS_INT, SPLIT, false, COL0>), grid,                       \
                                dim3(kGemvWaves * kWave), lds, stream, (const u32x4 *)codes,                        \
                                (const uint16_t *)scales, (const uint16_t *)zeros, (const u32x4 *)x, (uint16_t *)y, \
                                rowtiles, (int)K);                                                                  \
+        }                                                                                                          \
     } while (0)
     // Eight wavefronts per tile measured best or equal on every decoder shape (all of a
     // row's groups in flight at once); short rows take fewer so that no wavefront idles.
@@ -577,23 +583,29 @@ static void launch_gemv(const void *codes, const void *scales, const void *zeros
     else if (split == 2) POTQ_LAUNCH_GEMV(2, false);
     else POTQ_LAUNCH_GEMV(1, false);
 #undef POTQ_LAUNCH_GEMV
+    return hipGetLastError();
 }
 
 int gemv_max_batch() { return kMaxGemvBatch; }
 
 template <int BITS, bool IS_INT>
-static void launch_gemv_batch(const GemvBatch &b, unsigned blocks, const void *x, int64_t K, int group, int split,
+static hipError_t launch_gemv_batch(const GemvBatch &b, unsigned blocks, const void *x, int64_t K, int group, int split,
                               hipStream_t stream)
 {
     const size_t lds = gemv_lds_bytes(K);
 #define POTQ_LAUNCH_GEMVB(SPLIT, COL0)                                                                             \
     do {                                                                                                           \
-        if (group == 64)                                                                                           \
+        if (group == 64) {                                                                                         \
+            if (const hipError_t e_ = allow_large_lds<gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, true, COL0>>(lds)) \
+                return e_;                                                                                         \
             hipLaunchKernelGGL((gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, true, COL0>), dim3(blocks),          \
                                dim3(kGemvWaves * kWave), lds, stream, b, (const u32x4 *)x, (int)K);                \
-        else                                                                                                       \
+        } else {                                                                                                   \
+            if (const hipError_t e_ = allow_large_lds<gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, false, COL0>>(lds)) \
+                return e_;                                                                                         \
             hipLaunchKernelGGL((gemv_tile16_batch_kernel<BITS, IS_INT, SPLIT, false, COL0>), dim3(blocks),         \
                                dim3(kGemvWaves * kWave), lds, stream, b, (const u32x4 *)x, (int)K);                \
+        }                                                                                                          \
     } while (0)
     if (split == 8 && kGemvWaves >= 8) {
         if (gemv_col0_fetch(K)) POTQ_LAUNCH_GEMVB((kGemvWaves >= 8 ? 8 : 1), true);
@@ -602,6 +614,7 @@ static void launch_gemv_batch(const GemvBatch &b, unsigned blocks, const void *x
     else if (split == 2) POTQ_LAUNCH_GEMVB(2, false);
     else POTQ_LAUNCH_GEMVB(1, false);
 #undef POTQ_LAUNCH_GEMVB
+    return hipGetLastError();
 }
 
 // The exponent form of the PoT GEMV (gemv_exp.hip).
@@ -645,15 +658,14 @@ hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *code
     if (blocks == 0) return hipSuccess;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     if (is_int) {
-        if (bits == 4) launch_gemv_batch<4, true>(b, (unsigned)blocks, x, K, group, split, stream);
-        else if (bits == 3) launch_gemv_batch<3, true>(b, (unsigned)blocks, x, K, group, split, stream);
-        else launch_gemv_batch<2, true>(b, (unsigned)blocks, x, K, group, split, stream);
+        if (bits == 4) return launch_gemv_batch<4, true>(b, (unsigned)blocks, x, K, group, split, stream);
+        else if (bits == 3) return launch_gemv_batch<3, true>(b, (unsigned)blocks, x, K, group, split, stream);
+        else return launch_gemv_batch<2, true>(b, (unsigned)blocks, x, K, group, split, stream);
     } else {
-        if (bits == 4) launch_gemv_batch<4, false>(b, (unsigned)blocks, x, K, group, split, stream);
-        else if (bits == 3) launch_gemv_batch<3, false>(b, (unsigned)blocks, x, K, group, split, stream);
-        else launch_gemv_batch<2, false>(b, (unsigned)blocks, x, K, group, split, stream);
+        if (bits == 4) return launch_gemv_batch<4, false>(b, (unsigned)blocks, x, K, group, split, stream);
+        else if (bits == 3) return launch_gemv_batch<3, false>(b, (unsigned)blocks, x, K, group, split, stream);
+        else return launch_gemv_batch<2, false>(b, (unsigned)blocks, x, K, group, split, stream);
     }
-    return hipGetLastError();
 }
 
 
@@ -663,15 +675,14 @@ hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, c
     // large PoT matrices at 2 and 3 bits: the exponent form (scale applied per group, integer inner sums)
     if (POTQ_GEMV_EXP && !is_int && gemv_exp_ok(N, K, bits)) return run_gemv_exp(codes, scales, x, y, N, K, bits, group, stream);
     if (is_int) {
-        if (bits == 4) launch_gemv<4, true>(codes, scales, zeros, x, y, N, K, group, stream);
-        else if (bits == 3) launch_gemv<3, true>(codes, scales, zeros, x, y, N, K, group, stream);
-        else launch_gemv<2, true>(codes, scales, zeros, x, y, N, K, group, stream);
+        if (bits == 4) return launch_gemv<4, true>(codes, scales, zeros, x, y, N, K, group, stream);
+        else if (bits == 3) return launch_gemv<3, true>(codes, scales, zeros, x, y, N, K, group, stream);
+        else return launch_gemv<2, true>(codes, scales, zeros, x, y, N, K, group, stream);
     } else {
-        if (bits == 4) launch_gemv<4, false>(codes, scales, zeros, x, y, N, K, group, stream);
-        else if (bits == 3) launch_gemv<3, false>(codes, scales, zeros, x, y, N, K, group, stream);
-        else launch_gemv<2, false>(codes, scales, zeros, x, y, N, K, group, stream);
+        if (bits == 4) return launch_gemv<4, false>(codes, scales, zeros, x, y, N, K, group, stream);
+        else if (bits == 3) return launch_gemv<3, false>(codes, scales, zeros, x, y, N, K, group, stream);
+        else return launch_gemv<2, false>(codes, scales, zeros, x, y, N, K, group, stream);
     }
-    return hipGetLastError();
 }
 
 }  // namespace potq

@@ -28,4 +28,12 @@ inline hipError_t allow_large_lds(const void *kernel, size_t lds_bytes, std::ato
     return e;
 }
 
+// The same for a kernel given as a template argument: one flag word per kernel.
+template <auto Kernel>
+inline hipError_t allow_large_lds(size_t lds_bytes)
+{
+    static std::atomic<uint64_t> raised{0};
+    return allow_large_lds((const void *)Kernel, lds_bytes, raised);
+}
+
 }  // namespace potq

@@ -72,6 +72,7 @@ def test_host_side_validation(lib):
     assert g(A, A, None, A, 16, 128, 3, 128, 1, None) == NULL
     assert g(A, A, A, None, 16, 128, 3, 128, 1, None) == NULL
     assert g(None, None, None, None, 0, 128, 3, 128, 1, None) == OK
+    assert g(A, A, A, A, 16, 76672 + 128, 3, 128, 1, None) == SHAPE   # x no longer fits the LDS of a workgroup
     m = lib.pot_gemm
     assert m(A, A, A, A, -2, 16, 128, 3, 128, 1, None, 0, None) == SHAPE
     assert m(A, A, A, A, 4, 16, 128, 3, 128, 0, None, 0, None) == LAYOUT

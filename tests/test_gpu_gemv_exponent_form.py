@@ -79,7 +79,7 @@ def _assert_close(got, want, K, what):
     (8208, 8192, 2, 128),      # 513 tiles: the last workgroup has one tile fewer
     (9600, 7040, 3, 64),       # group size 64, 55 groups
     (4112, 16384, 2, 64),      # long rows: sixteen wavefronts, two tiles at a time, odd number of tiles
-    (2320, 30464, 3, 128),     # the longest row pot_gemv accepts
+    (2320, 30464, 3, 128),     # long rows: the digits of x take 134 KB of LDS
 ])
 def test_shapes(potq, N, K, bits, group):
     _check(potq, N, K, bits, group)

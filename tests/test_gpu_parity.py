@@ -345,3 +345,26 @@ def test_gemm_every_dispatch_configuration(potq, M, N, K, is_int):
         got = _run_gemm(potq, packed, S, Z, X, K, bits, use_workspace=use_ws)
         e, nw, nfloor = rel_err(got, want, K)
         assert e <= REL_TOL, (use_ws, e, nw, nfloor)
+
+
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("K", [32768, 53248, 76672])
+def test_gemv_rows_beyond_64_kib_of_lds(potq, K, is_int):
+    """x of long rows needs more LDS than a kernel gets by default (the limit is raised once per
+    device); 76672 is the longest row the entry points accept."""
+    bits, N = 3, 48
+    packed = workloads.packed_codes(workloads.seed_of(9, K % 97, 0), N, K, bits)
+    x = workloads.activations(workloads.seed_of(9, K % 97, 2), 1, K)
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    if is_int:
+        S, Z = workloads.int_scales_zeros(workloads.seed_of(9, K % 97, 3), N, K, bits, 128)
+        got = host_bits(potq.int_gemv(tiled, dev(S), dev(Z), dev(x[0]), K, bits))
+        got1 = host_bits(potq.int_gemm(tiled, dev(S), dev(Z), dev(x), K, bits))[0]
+    else:
+        S, Z = workloads.pot_scales(workloads.seed_of(9, K % 97, 1), N, K, 128), None
+        got = host_bits(potq.pot_gemv(tiled, dev(S), dev(x[0]), K, bits))
+        got1 = host_bits(potq.pot_gemm(tiled, dev(S), dev(x), K, bits))[0]
+    want = oracle.gemm(packed, S, Z, x, K, bits, 128)[0]
+    e, nw, nfloor = rel_err(got, want, K)
+    assert e <= REL_TOL, (K, is_int, e, nw, nfloor)
+    assert np.array_equal(got, got1)          # one token through the GEMM entry point is the same launch
