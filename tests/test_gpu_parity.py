@@ -368,3 +368,10 @@ def test_gemv_rows_beyond_64_kib_of_lds(potq, K, is_int):
     e, nw, nfloor = rel_err(got, want, K)
     assert e <= REL_TOL, (K, is_int, e, nw, nfloor)
     assert np.array_equal(got, got1)          # one token through the GEMM entry point is the same launch
+    if is_int:
+        ys = potq.int_gemv_batch([(tiled, dev(S), dev(Z)), (tiled, dev(S), dev(Z))],
+                                 dev(x[0]), K, bits)
+    else:
+        ys = potq.pot_gemv_batch([(tiled, dev(S)), (tiled, dev(S))], dev(x[0]), K, bits)
+    for y in ys:                              # the multi-matrix launch shares the kernel body
+        assert np.array_equal(host_bits(y), got)
