@@ -538,9 +538,13 @@ static size_t exp_lds_bytes(int64_t K, int waves)
 constexpr int kExpGroups = POTQ_EXP_GROUPS;
 constexpr size_t kExpLdsSmall = kLdsDefaultLimit, kExpLdsLarge = kLdsPerWorkgroup;
 
-// Wavefronts per workgroup: eight while two workgroups' digits of x fit the LDS of a compute
-// unit together, else sixteen (two tiles at a time) for one workgroup per compute unit.
-static int exp_waves(int64_t K) { return exp_lds_bytes(K, 8) <= kExpLdsSmall ? 8 : 16; }
+// Wavefronts per workgroup.  A single matrix always takes sixteen (two tiles at a time, one
+// workgroup per compute unit): x is converted once per compute unit instead of twice, which
+// measured 3-8 % faster than two workgroups of eight on every eligible shape (28672 x 8192:
+// 17.4 against 17.9 us, 5120 x 13824: 10.2 against 11.1 us).  Matrices sharing x keep eight
+// while two workgroups' digits of x fit the LDS of a compute unit together (no consistent
+// difference there, and small members of a batch get a finer share of the workgroups).
+static int exp_waves(int64_t K, bool batch) { return batch && exp_lds_bytes(K, 8) <= kExpLdsSmall ? 8 : 16; }
 
 // Whether the exponent form serves this PoT GEMV: signed-byte weights (2 or 3 bits), rows long
 // enough for eight wavefronts per tile, the digits of x within LDS and within the staging
@@ -552,9 +556,9 @@ bool gemv_exp_ok(int64_t N, int64_t K, int bits)
     const int64_t G = K / kTileCols;
     if (bits != 2 && bits != 3) return false;
     if (G < 32 || N * K < POTQ_EXP_MIN_WEIGHTS) return false;
-    const int waves = exp_waves(K);
-    if (K > (int64_t)kExpOctetsPerThread * waves * kWave * 8) return false;
-    return exp_lds_bytes(K, waves) <= kExpLdsLarge;
+    // (the eight-wavefront variant is only used where its footprint is smaller still)
+    if (K > (int64_t)kExpOctetsPerThread * 16 * kWave * 8) return false;
+    return exp_lds_bytes(K, 16) <= kExpLdsLarge;
 }
 
 // The same question for `count` matrices that share x (N = the sum of their rows).
@@ -602,7 +606,6 @@ hipError_t run_gemv_exp(const void *codes, const void *scales, const void *x, vo
 #define POTQ_LAUNCH_EXP(BITS, WAVES)                                                              \
     (g64 ? launch_exp<BITS, true, WAVES>(codes, scales, x, y, N, K, stream)                       \
          : launch_exp<BITS, false, WAVES>(codes, scales, x, y, N, K, stream))
-    if (exp_waves(K) == 8) return bits == 3 ? POTQ_LAUNCH_EXP(3, 8) : POTQ_LAUNCH_EXP(2, 8);
     return bits == 3 ? POTQ_LAUNCH_EXP(3, 16) : POTQ_LAUNCH_EXP(2, 16);
 #undef POTQ_LAUNCH_EXP
 }
@@ -648,7 +651,7 @@ hipError_t run_gemv_exp_batch(int count, const void *const *codes, const void *c
 #define POTQ_LAUNCH_EXPB(BITS, WAVES)                                                             \
     (g64 ? launch_exp_batch<BITS, true, WAVES>(count, codes, scales, y, N, x, K, stream)          \
          : launch_exp_batch<BITS, false, WAVES>(count, codes, scales, y, N, x, K, stream))
-    if (exp_waves(K) == 8) return bits == 3 ? POTQ_LAUNCH_EXPB(3, 8) : POTQ_LAUNCH_EXPB(2, 8);
+    if (exp_waves(K, true) == 8) return bits == 3 ? POTQ_LAUNCH_EXPB(3, 8) : POTQ_LAUNCH_EXPB(2, 8);
     return bits == 3 ? POTQ_LAUNCH_EXPB(3, 16) : POTQ_LAUNCH_EXPB(2, 16);
 #undef POTQ_LAUNCH_EXPB
 }
