@@ -398,35 +398,45 @@ def main() -> int:
             torch.cuda.empty_cache()
         del outs70
         torch.cuda.empty_cache()
-        g70 = []
-        for (N, K) in ((8192, 8192), (1024, 8192), (28672, 8192), (8192, 28672)):
-            nbytes = workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
-            R = rotate(nbytes)
-            cs = [torch.randint(0, 256, (N, K * b3 // 8), dtype=torch.uint8, device=dev, generator=gen) for _ in range(R)]
-            sc_ = to_dev(workloads.pot_scales(workloads.seed_of(3, 0, 1), N, K, G))
-            S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(3, 0, 3), N, K, b3, G)
-            Sd_, Zd_ = to_dev(S_h), to_dev(Z_h)
-            x = to_dev(workloads.activations(workloads.seed_of(3, 0, 2), 1, K)[0])
-            y = torch.empty((N,), dtype=torch.float16, device=dev)
+        def gemv_pairs(shapes):
+            """PoT and INT3 GEMV per shape, measured alternately, weight buffers rotating through HBM."""
+            rows_ = []
+            for (N, K) in shapes:
+                nbytes = workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
+                R = rotate(nbytes)
+                cs = [torch.randint(0, 256, (N, K * b3 // 8), dtype=torch.uint8, device=dev, generator=gen)
+                      for _ in range(R)]
+                sc_ = to_dev(workloads.pot_scales(workloads.seed_of(3, 0, 1), N, K, G))
+                S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(3, 0, 3), N, K, b3, G)
+                Sd_, Zd_ = to_dev(S_h), to_dev(Z_h)
+                x = to_dev(workloads.activations(workloads.seed_of(3, 0, 2), 1, K)[0])
+                y = torch.empty((N,), dtype=torch.float16, device=dev)
 
-            def pot70():
-                for c in cs:
-                    check(lib.pot_gemv(c.data_ptr(), sc_.data_ptr(), x.data_ptr(), y.data_ptr(), N, K, b3, G, 1, stream))
+                def pot70():
+                    for c in cs:
+                        check(lib.pot_gemv(c.data_ptr(), sc_.data_ptr(), x.data_ptr(), y.data_ptr(), N, K, b3, G, 1,
+                                           stream))
 
-            def int70():
-                for c in cs:
-                    check(lib.int_gemv(c.data_ptr(), Sd_.data_ptr(), Zd_.data_ptr(), x.data_ptr(), y.data_ptr(), N, K,
-                                       b3, G, 1, stream))
+                def int70():
+                    for c in cs:
+                        check(lib.int_gemv(c.data_ptr(), Sd_.data_ptr(), Zd_.data_ptr(), x.data_ptr(), y.data_ptr(),
+                                           N, K, b3, G, 1, stream))
 
-            reps = max(2, 64 // R)
-            us_p, us_i = (t * 1e3 / R for t in _time_pair(torch, pot70, int70, reps, 1))
-            g70.append({"shape": f"{N}x{K}", "us": round(us_p, 2), "GBps": round(nbytes / us_p / 1e3, 1),
-                        "pct_hbm_peak": round(nbytes / us_p / 1e3 / HBM_PEAK_GBPS * 100, 1), "int_us": round(us_i, 2),
-                        "pot_speedup_vs_int": round(us_i / us_p, 3), "buffers_rotated": R})
-            del cs
-            torch.cuda.empty_cache()
+                reps = max(2, 64 // R)
+                us_p, us_i = (t * 1e3 / R for t in _time_pair(torch, pot70, int70, reps, 1))
+                rows_.append({"shape": f"{N}x{K}", "us": round(us_p, 2), "GBps": round(nbytes / us_p / 1e3, 1),
+                              "pct_hbm_peak": round(nbytes / us_p / 1e3 / HBM_PEAK_GBPS * 100, 1),
+                              "int_us": round(us_i, 2), "pot_speedup_vs_int": round(us_i / us_p, 3),
+                              "buffers_rotated": R})
+                del cs
+                torch.cuda.empty_cache()
+            return rows_
+
+        g70 = gemv_pairs(((8192, 8192), (1024, 8192), (28672, 8192), (8192, 28672)))
         big["gemv_3bit"] = g70
         extras["llama2_70b_layer"] = big
+        # the vocabulary projection of a decoder (32000 or 128256 rows): the largest matrix of a decode step
+        extras["pot_gemv_3bit_vocabulary_projection"] = gemv_pairs(((32000, 4096), (128256, 4096), (128256, 8192)))
 
         # fused MFMA GEMM, 3-bit, 13B shapes; the calls rotate through enough copies of the weight codes
         # (random bytes are valid codes) that they are read from HBM, not from the 256 MB last-level cache
