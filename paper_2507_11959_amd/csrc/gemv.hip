@@ -244,6 +244,125 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_kernel(
     gemv_tile16_body<BITS, IS_INT, S, G64, COL0>(codes, scales, zeros, x, y, rowtiles, K, blockIdx.x);
 }
 
+// The GEMV for large matrices: the same arithmetic, in the same order, as gemv_tile16_kernel with
+// eight wavefronts per tile, but a workgroup stages x once and walks the row tiles first,
+// first + stride, ...; the codes of the next step -- the next round of the tile or the first
+// round of the next tile -- are requested before the current ones are expanded, so the memory
+// traffic of a wavefront never pauses at a tile boundary, and the grid is no larger than what
+// the chip holds at once.  (The exponent-form kernel of gemv_exp.hip is built the same way;
+// this one serves what that one cannot: the uniform baseline and 4-bit codes.)
+template <int BITS, bool IS_INT, bool G64, bool COL0>
+__global__ __launch_bounds__(kGemvWaves * kWave) void gemv_tile16_walk_kernel(
+    const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
+    const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int64_t rowtiles, int K)
+{
+    static_assert(kGemvWaves == 8, "eight wavefronts share a tile");
+    constexpr int gs = G64 ? 1 : 0;
+    constexpr int kStep = 4 * kGemvWaves;
+    extern __shared__ u32x4 smem[];
+    u32x4 *xs = smem;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int part = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront index: uniform, kept in a scalar
+    const int r = lane & 15;
+    const int t = lane >> 4;
+    const int G = K / kTileCols;
+    const int scale_owner = (4 * r + t) * 4;
+    const int my_rounds = (G - part * 4 + kStep - 1) / kStep;   // G >= 32: at least one
+    u32x4 *zero_block = smem + G * kXRun;               // 16 uint4 of zeros
+    float *red = (float *)(zero_block + 16);            // 2 x 8 wavefronts x 16 partial sums
+    const int64_t first = blockIdx.x, stride = gridDim.x;
+
+    auto fetch = [&](int64_t tile, int round, u32x4 (&Lx)[BITS], uint32_t &sx, uint32_t &zx) {
+        const int g0 = round * kStep + part * 4;                        // uniform
+        const int gc = min(g0 + t, G - 1);
+        const u32x4 *tile_codes = codes + tile * G * (BITS * 16);       // uniform
+        const uint32_t at = (uint32_t)(gc * (BITS * 16) + r);
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) Lx[j] = __builtin_nontemporal_load(tile_codes + at + 16 * j);
+        zx = 0u;
+        if (gs) {
+            const uint32_t i = (uint32_t)(r * G + gc);
+            sx = ((const uint32_t *)(scales + tile * kTileRows * (int64_t)(2 * G)))[i];
+            if (IS_INT) zx = ((const uint32_t *)(zeros + tile * kTileRows * (int64_t)(2 * G)))[i];
+        } else {
+            const uint32_t i = (uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1));
+            sx = (scales + tile * kTileRows * (int64_t)G)[i];
+            if (IS_INT) zx = (zeros + tile * kTileRows * (int64_t)G)[i];
+        }
+    };
+    int64_t ftile = first;
+    int fround = 0;
+    auto advance = [&]() {
+        if (fround + 1 < my_rounds) {
+            ++fround;
+        } else if (ftile + stride < rowtiles) {
+            ftile += stride;
+            fround = 0;
+        }
+    };
+    u32x4 L[BITS];
+    uint32_t s, z;
+    fetch(ftile, fround, L, s, z);
+    advance();
+
+    for (int i = tid; i < K / 8; i += kGemvWaves * kWave) xs[(i >> 4) * kXRun + (i & 15)] = x[i];
+    if (tid < 16) zero_block[tid] = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
+
+    int it = 0;
+    for (int64_t tile = first; tile < rowtiles; tile += stride, ++it) {
+        float4_t acc[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = float4_t{0.f, 0.f, 0.f, 0.f};
+        for (int round = 0; round < my_rounds; ++round) {
+            u32x4 Ln[BITS];
+            uint32_t sn, zn;
+            fetch(ftile, fround, Ln, sn, zn);
+            advance();
+            const int g = round * kStep + part * 4 + t;
+            uint32_t so, zo = 0u, so_hi, zo_hi = 0u;
+            if (gs) {
+                so = s & 0xFFFFu;
+                so_hi = s >> 16;
+                if (IS_INT) {
+                    zo = z & 0xFFFFu;
+                    zo_hi = z >> 16;
+                }
+            } else {
+                so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)s);
+                if (IS_INT) zo = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)z);
+                so_hi = so;
+                zo_hi = zo;
+            }
+            if (g >= G) {                               // past the end of the row: finite weights times zeros
+                so = so_hi = 0x3C00u;
+                zo = zo_hi = 0u;
+            }
+            const u32x4 *xg = g < G ? xs + g * kXRun : zero_block;
+            gemv_group<BITS, IS_INT, (COL0 ? 1 : 0)>(L, so, zo, so_hi, zo_hi, gs != 0, [&](int j) { return xg[j]; }, acc);
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
+            s = sn;
+            z = zn;
+        }
+        // as in gemv_tile16_kernel: lane (c, q) holds rows 4q..4q+3; the eight wavefronts' sums are
+        // added in a fixed order.  The buffer alternates between tiles, so one barrier per tile
+        // separates the writes of tile i + 2 from the reads of tile i.
+        const float4_t part_sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+        float *red_it = red + (it & 1) * (kGemvWaves * kTileRows);
+        if (r == 0) *(float4_t *)(red_it + part * kTileRows + 4 * t) = part_sum;
+        __syncthreads();
+        if (tid < kTileRows) {
+            float sum = 0.f;
+#pragma unroll
+            for (int p = 0; p < kGemvWaves; ++p) sum += red_it[p * kTileRows + tid];
+            const _Float16 h = (_Float16)sum;
+            y[tile * kTileRows + tid] = __builtin_bit_cast(uint16_t, h);
+        }
+    }
+}
+
 // Several matrices that consume the same activation vector (q/k/v, gate/up) in one launch:
 // a batch-1 GEMV on a 4096x4096 matrix is a 4 us kernel of which most is launch and memory
 // latency, so sharing one launch pays more than anything inside the kernel.
@@ -547,10 +666,64 @@ static int gemv_split(int64_t G)
     return split;
 }
 
+#ifndef POTQ_GEMV_WALK
+#define POTQ_GEMV_WALK 1
+#endif
+#ifndef POTQ_GEMV_WALK_GROUPS
+#define POTQ_GEMV_WALK_GROUPS 512                     // two resident workgroups per compute unit
+#endif
+#ifndef POTQ_GEMV_WALK_MIN_WEIGHTS
+#define POTQ_GEMV_WALK_MIN_WEIGHTS (256ll << 20)
+#endif
+
+static size_t gemv_walk_lds_bytes(int64_t K)
+{
+    return (size_t)(K / kTileCols) * kXRun * 16 + 256 + 2 * kGemvWaves * kTileRows * sizeof(float);
+}
+
+// Whether the tile-walking kernel serves this GEMV: rows long enough for eight wavefronts per
+// tile and a very large matrix.  Unlike the exponent form, this kernel is bound by its decode
+// work, not by the structure of its launch: at 128256 x 4096 it measured 10 % faster than one
+// workgroup per tile (INT3 54 -> 49 us, 4-bit PoT 54 -> 47 us), from 28672 x 8192 down the same
+// or slower (17920 x 6656, INT3: 15.3 -> 16.5 us), so it only takes the vocabulary-sized ones.
+static bool gemv_walk_ok(int64_t N, int64_t K)
+{
+    return POTQ_GEMV_WALK && kGemvWaves == 8 && K / kTileCols >= 32 && N * K >= POTQ_GEMV_WALK_MIN_WEIGHTS &&
+           gemv_walk_lds_bytes(K) <= kLdsPerWorkgroup;
+}
+
+template <int BITS, bool IS_INT>
+static hipError_t launch_gemv_walk(const void *codes, const void *scales, const void *zeros, const void *x, void *y,
+                                   int64_t N, int64_t K, int group, hipStream_t stream)
+{
+    const int64_t rowtiles = N / kTileRows;
+    const size_t lds = gemv_walk_lds_bytes(K);
+    const int64_t cap = POTQ_GEMV_WALK_GROUPS;
+    const int64_t per_group = (rowtiles + cap - 1) / cap;
+    const dim3 grid((unsigned)((rowtiles + per_group - 1) / per_group)), block(kGemvWaves * kWave);
+#define POTQ_LAUNCH_WALK(G64, COL0)                                                                               \
+    do {                                                                                                          \
+        if (const hipError_t e_ = allow_large_lds<gemv_tile16_walk_kernel<BITS, IS_INT, G64, COL0>>(lds)) return e_; \
+        hipLaunchKernelGGL((gemv_tile16_walk_kernel<BITS, IS_INT, G64, COL0>), grid, block, lds, stream,          \
+                           (const u32x4 *)codes, (const uint16_t *)scales, (const uint16_t *)zeros,               \
+                           (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K);                                    \
+    } while (0)
+    if (group == 64) {
+        if (gemv_col0_fetch(K)) POTQ_LAUNCH_WALK(true, true);
+        else POTQ_LAUNCH_WALK(true, false);
+    } else {
+        if (gemv_col0_fetch(K)) POTQ_LAUNCH_WALK(false, true);
+        else POTQ_LAUNCH_WALK(false, false);
+    }
+#undef POTQ_LAUNCH_WALK
+    return hipGetLastError();
+}
+
 template <int BITS, bool IS_INT>
 static hipError_t launch_gemv(const void *codes, const void *scales, const void *zeros, const void *x, void *y,
                         int64_t N, int64_t K, int group, hipStream_t stream)
 {
+    if (gemv_walk_ok(N, K)) return launch_gemv_walk<BITS, IS_INT>(codes, scales, zeros, x, y, N, K, group, stream);
     const int64_t rowtiles = N / kTileRows;
     const size_t lds = gemv_lds_bytes(K);
     const int64_t G = K / kTileCols;

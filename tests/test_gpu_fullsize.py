@@ -177,6 +177,30 @@ def test_gemm_few_row_tiles_large_matrices_sampled_rows(potq, M, is_int):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("N,K,bits,group,is_int", [
+    (65552, 4096, 3, 128, True),      # vocabulary-sized: a resident grid of workgroups walks the row tiles
+    (65552, 4096, 4, 64, False),      # 4-bit PoT, group size 64
+    (16400, 16384, 2, 128, True),     # long rows (x fetched by the lanes of result column 0 only), ragged tile count
+])
+def test_gemv_vocabulary_sized_matrices_sampled_rows(potq, N, K, bits, group, is_int):
+    rng = np.random.default_rng(N + bits)
+    packed = workloads.packed_codes(workloads.seed_of(8, bits, 0), N, K, bits)
+    x = workloads.activations(workloads.seed_of(8, bits, 2), 1, K)
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    if is_int:
+        S, Z = workloads.int_scales_zeros(workloads.seed_of(8, bits, 3), N, K, bits, group)
+        y = potq.int_gemv(tiled, dev(S), dev(Z), dev(x[0]), K, bits, group)
+    else:
+        S, Z = workloads.pot_scales(workloads.seed_of(8, bits, 1), N, K, group), None
+        y = potq.pot_gemv(tiled, dev(S), dev(x[0]), K, bits, group)
+    rows = np.unique(np.concatenate([[0, 15, 16, N - 17, N - 1], rng.integers(0, N, 2000)]))
+    want = oracle.gemm(packed[rows], S[rows], None if Z is None else Z[rows], x, K, bits, group,
+                       nthreads=_threads())[0]
+    e, nw, nfloor = rel_err(host_bits(y[torch.from_numpy(rows).to("cuda:0")]), want, K)
+    assert e <= REL_TOL, (N, K, bits, group, is_int, e, nw, nfloor)
+    assert bool(torch.isfinite(y).all())
+
+
 @pytest.mark.parametrize("bits", [2, 3])
 def test_second_workload_llama30b_layer(potq, bits):
     """LLaMA-30B-shaped layer: batched dequant (sampled rows + invariants) and the q/k/v and gate/up
