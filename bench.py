@@ -84,7 +84,9 @@ def main() -> int:
     import numpy as np
     import torch
 
-    import paper_2507_11959_amd as potq     # raises if libpotq.so has not been built
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # loads what is built; builds only if the tree holds no library
+    import paper_2507_11959_amd as potq     # raises if libpotq.so is still missing: there is no fallback path
     from paper_2507_11959_amd import binding
     import workloads
 

@@ -10,6 +10,9 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run through the C ABI on cuda:0)")
+    # the tests load the library that is built; only a tree with none gets one built here
+    import __graft_entry__
+    __graft_entry__.ensure_built()
 
 
 def _have_gpu() -> bool:
