@@ -61,7 +61,8 @@ typedef enum {
     POTQ_ERR_SHAPE = 4,      /* negative size, K not a multiple of 128, N not a multiple of 16 (tiled) */
     POTQ_ERR_ALIGN = 5,      /* a pointer is not 16-byte aligned */
     POTQ_ERR_LAYOUT = 6,     /* layout id unknown or not supported by this entry point */
-    POTQ_ERR_LAUNCH = 7      /* the HIP runtime refused the launch */
+    POTQ_ERR_LAUNCH = 7,     /* the HIP runtime refused the launch */
+    POTQ_ERR_WORKSPACE = 8   /* pot_gemm_noalloc: the shape needs more scratch than the built-in buffer holds */
 } potq_status;
 
 typedef enum {
@@ -230,6 +231,31 @@ int pot_gemm(const void *codes, const void *scales, const void *X_f16, void *Y_f
 int int_gemm(const void *codes, const void *scales, const void *zeros, const void *X_f16, void *Y_f16,
              int64_t M, int64_t N, int64_t K, int bits, int group, int layout,
              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * pot_gemm_noalloc -- pot_gemm for callers that cannot allocate device memory or
+ * carry a workspace around: code running under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments and the same result,
+ * bit for bit, as pot_gemm called with a workspace of
+ * potq_gemm_workspace_bytes(M, N, K, bits) bytes; the split-K partial sums go to a
+ * buffer of POTQ_STATIC_SCRATCH_BYTES built into the library's code object
+ * (every GPU the library runs on holds its own copy until the process ends; its
+ * address is looked up once per device, on the first call there).  The call
+ * itself allocates and frees nothing and calls no allocating routine.
+ *  - A shape whose preferred workspace exceeds the buffer is refused with
+ *    POTQ_ERR_WORKSPACE and nothing is launched.  That can only happen with 17 to 64
+ *    tokens and M * N above 2^20 elements; every other shape fits.
+ *  - All calls on one GPU share that GPU's buffer: calls that overlap in time on
+ *    different streams of one GPU race on it and must be serialised by the
+ *    caller.  Calls on one stream are ordered and safe.  Nothing in the buffer
+ *    has to start at zero (every partial sum that is read was written by the same
+ *    call), so it is never cleared and keeps the last call's contents.
+ */
+#define POTQ_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+
+int pot_gemm_noalloc(const void *codes, const void *scales, const void *X_f16, void *Y_f16,
+                     int64_t M, int64_t N, int64_t K, int bits, int group, int layout,
+                     void *hip_stream);
 
 /*
  * pot_quantize -- Step 1 of the method, the data-agnostic scale search (Sec. 3.2,

@@ -44,6 +44,7 @@ EXPORTS = {
     "potq_gemm_workspace_bytes": (ctypes.c_size_t, [_i64, _i64, _i64, _int]),
     "potq_gemv_exponent_form": (_int, [_i64, _i64, _int]),
     "pot_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
+    "pot_gemm_noalloc": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp]),
     "int_gemm": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
     "pot_check_scales": (_int, [_vp, _i64, _int, _vp, _vp]),
     "pot_quantize": (_int, [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]),
@@ -255,6 +256,20 @@ def pot_gemm(codes, scales, X, K: int, bits: int, group: int = 128, layout: int 
     _ok(_lib.pot_gemm(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                       _dev(X, torch.float16, "X"), _dev(out, torch.float16, "Y"), M, N, K, bits, group, layout,
                       wp, wn, _stream()))
+    return out
+
+
+def pot_gemm_noalloc(codes, scales, X, out, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16):
+    """pot_gemm with the library's built-in scratch buffer; `out` (M, N) is the caller's: nothing is allocated."""
+    N = _shape_codes(codes, K, bits)
+    if X.dim() != 2 or X.shape[1] != K:
+        raise ValueError("X must be (M, K)")
+    M = X.shape[0]
+    if tuple(out.shape) != (M, N):
+        raise ValueError("out must be (M, N)")
+    _ok(_lib.pot_gemm_noalloc(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
+                              _dev(X, torch.float16, "X"), _dev(out, torch.float16, "Y"), M, N, K, bits, group,
+                              layout, _stream()))
     return out
 
 

@@ -27,6 +27,8 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, void *ws, size_t ws_bytes,
                            hipStream_t stream);
 size_t gemm_workspace_bytes(int64_t M, int64_t N);
+size_t gemm_static_scratch_bytes();
+hipError_t gemm_static_scratch(void **ptr);
 hipError_t run_fakequant_forward(const void *W, const void *S, const void *Gamma, void *Wq, int64_t N, int64_t K,
                                  int bits, int group, hipStream_t stream);
 hipError_t run_fakequant_backward(const void *W, const void *S, const void *Gamma, const void *dWq, void *dGamma,
@@ -160,7 +162,7 @@ int gemv_batch_entry(bool is_int, const potq_gemv_item *items, int count, const 
 
 int gemm_entry(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                int64_t M, int64_t N, int64_t K, int bits, int group, int layout, void *workspace,
-               size_t workspace_bytes, void *stream)
+               size_t workspace_bytes, void *stream, bool static_scratch = false)
 {
     const int st = check_common(N, K, bits, group, true);
     if (st != POTQ_OK) return st;
@@ -174,6 +176,14 @@ int gemm_entry(bool is_int, const void *codes, const void *scales, const void *z
     if (!codes || !scales || !X || (is_int && !zeros)) return POTQ_ERR_NULL;
     if (misaligned(codes) || misaligned(scales) || misaligned(X) || (is_int && misaligned(zeros)))
         return POTQ_ERR_ALIGN;
+    if (static_scratch) {
+        // the library's built-in buffer takes the place of the caller's workspace.  Shapes whose
+        // preferred split does not fit it are refused, so that the result is always the one the
+        // call gives with the workspace potq_gemm_workspace_bytes() asks for.
+        if (potq::gemm_workspace_bytes(M, N) > potq::gemm_static_scratch_bytes()) return POTQ_ERR_WORKSPACE;
+        if (potq::gemm_static_scratch(&workspace) != hipSuccess) return POTQ_ERR_LAUNCH;
+        workspace_bytes = potq::gemm_static_scratch_bytes();
+    }
     if (workspace && misaligned(workspace)) return POTQ_ERR_ALIGN;
     if (!workspace) workspace_bytes = 0;
     return finish(potq::run_gemm_tile16(is_int, codes, scales, zeros, X, Y, M, N, K, bits, group, workspace, workspace_bytes,
@@ -197,6 +207,7 @@ const char *potq_strerror(int status)
     case POTQ_ERR_ALIGN: return "a pointer is not 16-byte aligned";
     case POTQ_ERR_LAYOUT: return "layout not supported by this entry point";
     case POTQ_ERR_LAUNCH: return "the HIP runtime refused the launch";
+    case POTQ_ERR_WORKSPACE: return "the shape needs more scratch memory than the library's built-in buffer holds";
     default: return "unknown status";
     }
 }
@@ -298,6 +309,13 @@ int int_gemm(const void *codes, const void *scales, const void *zeros, const voi
 {
     return gemm_entry(true, codes, scales, zeros, X_f16, Y_f16, M, N, K, bits, group, layout, workspace,
                       workspace_bytes, hip_stream);
+}
+
+int pot_gemm_noalloc(const void *codes, const void *scales, const void *X_f16, void *Y_f16, int64_t M, int64_t N,
+                     int64_t K, int bits, int group, int layout, void *hip_stream)
+{
+    return gemm_entry(false, codes, scales, nullptr, X_f16, Y_f16, M, N, K, bits, group, layout, nullptr, 0,
+                      hip_stream, true);
 }
 
 int pot_quantize(const void *W_f16, void *codes_out, void *scales_out, int64_t N, int64_t K, int bits, int group,

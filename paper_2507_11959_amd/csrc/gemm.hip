@@ -431,6 +431,35 @@ static hipError_t launch_gemm(const void *codes, const void *scales, const void 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Split-K partial sums for callers that may not allocate: one array in the code object itself.
+// Every GPU the library runs on holds its own copy at its own address until the process ends;
+// in host code the array's name is only a handle for hipGetSymbolAddress, never an address.
+// ---------------------------------------------------------------------------
+constexpr size_t kScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+size_t gemm_static_scratch_bytes() { return kScratchBytes; }
+
+// Device address of `scratch` on the current device, asked for once per device and process.
+hipError_t gemm_static_scratch(void **ptr)
+{
+    constexpr int kKnownDevices = 64;
+    static std::atomic<void *> address[kKnownDevices];   // zero-initialised: not asked yet
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    void *p = (device >= 0 && device < kKnownDevices) ? address[device].load(std::memory_order_acquire) : nullptr;
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        if (device >= 0 && device < kKnownDevices) address[device].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return hipSuccess;
+}
+
 hipError_t run_gemm_fewtok(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 

@@ -41,7 +41,7 @@ def test_sizes_and_strings(lib):
     assert lib.potq_packed_row_bytes(4096, 2) == 1024
     assert lib.potq_packed_bytes(11008, 4096, 2) == 11008 * 1024
     assert lib.potq_packed_row_bytes(100, 3) == 0
-    for s in range(8):
+    for s in range(9):
         assert lib.potq_strerror(s)
     assert lib.potq_strerror(0) == b"ok"
 
@@ -79,6 +79,14 @@ def test_host_side_validation(lib):
     assert m(None, None, None, None, 0, 16, 128, 3, 128, 1, None, 0, None) == OK
     assert m(A, A, A, A, 4, 16, 128, 3, 128, 1, MIS, 1 << 20, None) == ALIGN
     assert lib.int_gemm(A, A, None, A, A, 4, 16, 128, 3, 128, 1, None, 0, None) == NULL
+    na = lib.pot_gemm_noalloc                                             # same checks, then the scratch limit
+    assert na(A, A, A, A, -2, 16, 128, 3, 128, 1, None) == SHAPE
+    assert na(A, A, A, A, 4, 16, 128, 3, 128, 0, None) == LAYOUT
+    assert na(A, A, None, A, 4, 16, 128, 3, 128, 1, None) == NULL
+    assert na(A, MIS, A, A, 4, 16, 128, 3, 128, 1, None) == ALIGN
+    assert na(None, None, None, None, 0, 16, 128, 3, 128, 1, None) == OK
+    assert na(A, A, A, A, 64, 28672, 8192, 3, 128, 1, None) == 8          # 117 MB of partial sums: refused
+    assert lib.potq_gemm_workspace_bytes(64, 13824, 5120, 3) <= 64 << 20  # the largest shape of config 5 fits
     assert lib.potq_gemm_workspace_bytes(16, 4096, 4096, 3) == 0          # up to 16 tokens: no workspace is used
     assert lib.potq_gemm_workspace_bytes(32, 4096, 4096, 3) == 16 * 32 * 4096 * 4
     assert lib.potq_gemm_workspace_bytes(256, 13824, 5120, 3) == 0      # enough output tiles: no split
