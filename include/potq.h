@@ -159,8 +159,10 @@ int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits,
  * one fp32 rounding per group.  For scales inside the domain of pot_dequant
  * this is the same sum; for scales outside it (pot_check_scales() finds them,
  * pot_quantize() never produces them) this form multiplies by 2^E where the
- * other adds into the exponent field, and the results differ.  An infinity or
- * NaN anywhere in x makes every y[n] NaN in this form.
+ * other adds into the exponent field, and the results differ.  Activations
+ * with an infinity or a NaN among them have no fixed-point form and are
+ * multiplied one by one in binary32, which gives what the definition gives:
+ * the infinity whose sign all infinite terms of a row agree on, NaN otherwise.
  */
 int pot_gemv(const void *codes, const void *scales, const void *x_f16, void *y_f16,
              int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
@@ -207,8 +209,8 @@ int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f1
  *   Y[m,n] = fp16( sum_k X[m,k] * W~[n,k] ),   X: M x K fp16 row-major,
  *   Y: M x N fp16 row-major (Y = X . W~^T, the nn.Linear convention).
  * fp16 MFMA with fp32 accumulation (up to four tokens on large 2-/3-bit PoT
- * matrices: the exponent form described at pot_gemv, with its conditions on
- * scales and non-finite activations).  `codes` must be in POTQ_LAYOUT_TILE16.
+ * matrices: the exponent form described at pot_gemv, with its condition on
+ * the scales).  `codes` must be in POTQ_LAYOUT_TILE16.
  *
  * `workspace` is optional device scratch memory (16-byte aligned) owned by the
  * caller.  With few tokens there are too few output tiles to occupy the chip, so

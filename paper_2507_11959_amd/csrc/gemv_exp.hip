@@ -55,12 +55,15 @@ struct ExpDecoder {
 // Eight 16-byte LDS reads by the lanes of `lanes` only, which leave the registers of the other
 // lanes untouched: the off-diagonal lanes of the A operand hold zeros, written once, and never
 // read LDS.  The compiler does not count these reads, so lds_wait() stands between them and
-// their first use.  They overwrite registers that the MFMAs of the previous round read: the
-// caller must have consumed those MFMAs' results (the recombination does) before it issues the
-// next reads -- an MFMA that has been issued but not started may not have read its operands yet
-// (re-reading the registers right after issuing the MFMAs gave wrong results).
+// their first use.  They overwrite registers that the MFMAs of the previous round read, and the
+// compiler sees neither that nor the hazards of the instructions inside the block: an MFMA that
+// has been issued may not have read its operands yet (re-reading the registers right after
+// issuing the MFMAs gave wrong results).  `after` is a value computed from the results of those
+// MFMAs (the running row sum): as an input of the block it keeps every instruction that produces
+// it -- the MFMAs, which by then have long read their operands, and the recombination of their
+// results -- ahead of the reads.  The block also changes SCC (s_and_b64).
 typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
-__device__ __forceinline__ void lds_read_keep(u32x4 (&xa)[8], uint32_t lds_byte_address, uint64_t lanes)
+__device__ __forceinline__ void lds_read_keep(u32x4 (&xa)[8], uint32_t lds_byte_address, uint64_t lanes, float after)
 {
     uint64_t saved;
     asm volatile("s_mov_b64 %[saved], exec\n\t"
@@ -76,7 +79,8 @@ __device__ __forceinline__ void lds_read_keep(u32x4 (&xa)[8], uint32_t lds_byte_
                  "s_mov_b64 exec, %[saved]"
                  : [x0] "+v"(xa[0]), [x1] "+v"(xa[1]), [x2] "+v"(xa[2]), [x3] "+v"(xa[3]), [x4] "+v"(xa[4]),
                    [x5] "+v"(xa[5]), [x6] "+v"(xa[6]), [x7] "+v"(xa[7]), [saved] "=&s"(saved)
-                 : [at] "v"(lds_byte_address), [lanes] "s"(lanes));
+                 : [at] "v"(lds_byte_address), [lanes] "s"(lanes), [after] "v"(after)
+                 : "scc");
 }
 __device__ __forceinline__ void lds_wait(u32x4 (&xa)[8])
 {
@@ -111,6 +115,37 @@ __device__ __forceinline__ float exp_recombine(const int4_t d)
     const int hi = d[3] * 256 + d[2];               // |d_p| <= 128 * 8 * 128
     const int lo = d[1] * 256 + d[0];
     return __builtin_fmaf((float)hi, 65536.f, (float)lo);
+}
+
+// Activations with an infinity or a NaN among them have no fixed-point form.  Their products are
+// taken one by one in binary32 instead: (+-2^E) * x[k] is exact, an infinity keeps the sign the
+// weight gives it, a NaN stays one, so a row whose infinite terms agree in sign comes out as that
+// infinity and any other as NaN, which is what the definition of the product gives; the finite
+// activations add finite amounts that do not matter next to them.  Blocks b0 .. b1-1 of one
+// group of one row against xg[0 .. 127], the fp16 activations of that group.  Speed is no concern.
+template <int BITS>
+__device__ __forceinline__ float exp_blocks_plain(const u32x4 (&L)[BITS], const uint16_t *__restrict__ xg, int b0, int b1)
+{
+    ExpDecoder<BITS> dec;
+    float sum = 0.f;
+#pragma unroll 1
+    for (int b = b0; b < b1; ++b) {
+        uint32_t w[BITS];
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) w[j] = b == 0 ? L[j][0] : b == 1 ? L[j][1] : b == 2 ? L[j][2] : L[j][3];
+        dec.set_block(w);
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            const uint32_t wt = dec.get(m);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int column = 32 * b + 4 * m + ((j & 1) << 1) + (j >> 1);     // byte j of a selector: column (0, 2, 1, 3)[j]
+                const float wv = (float)(int)(int8_t)(wt >> (8 * j));
+                sum = __builtin_fmaf(wv, (float)__builtin_bit_cast(_Float16, xg[column]), sum);
+            }
+        }
+    }
+    return sum;
 }
 
 // Eight fp16 activations (columns 8i .. 8i+7) -> fixed point m = rne(x * 2^k), each m cut into
@@ -240,8 +275,57 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
     const int e = max((int)(am >> 10), 1);
     const int k = 44 - e;
     const float two_k = __builtin_bit_cast(float, (uint32_t)(k + 127) << 23);
-    // an infinity or NaN among the activations makes every result NaN
-    const float two_mk = e == 31 ? __builtin_nanf("") : __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
+    const float two_mk = __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
+
+    // lane (r, t) holds the groups of lane group t of row r: add the lane groups, then the
+    // wavefronts of the slot, in a fixed order.  The buffer alternates between tile sets, so one
+    // barrier per set separates the writes of set i + 2 from the reads of set i.
+    auto finish_tiles = [&](int64_t q, int it, float row_sum) {
+        float *red_it = red + (it & 1) * (WAVES * kTileRows);
+        row_sum += __shfl_xor(row_sum, 16, kWave);
+        row_sum += __shfl_xor(row_sum, 32, kWave);
+        if (t == 0) red_it[wave * kTileRows + r] = row_sum;
+        __syncthreads();
+        if (tid < SLOTS * kTileRows) {
+            const int of_slot = tid / kTileRows, row = tid % kTileRows;
+            const int64_t tile = q * SLOTS + of_slot;
+            float sum = 0.f;
+#pragma unroll
+            for (int p = 0; p < kExpSplit; ++p) sum += red_it[(of_slot * kExpSplit + p) * kTileRows + row];
+            const _Float16 h = (_Float16)sum;
+            if (tile < rowtiles) y[tile * kTileRows + row] = __builtin_bit_cast(uint16_t, h);
+        }
+    };
+
+    // An infinity or NaN among the activations (the same for every workgroup of the launch):
+    // plain binary32 products, same tiles, same reduction.
+    if (e == 31) {
+        int it = 0;
+        for (int64_t q = first; q * SLOTS < rowtiles; q += stride, ++it) {
+            float row_sum = 0.f;
+            for (int round = 0; round < my_rounds; ++round) {
+                u32x4 Lp[BITS];
+                uint32_t sp;
+                fetch(tile_of(q), round, Lp, sp);
+                const int g = round * kStep + part * 4 + t;
+                const uint16_t *xg = (const uint16_t *)x + (size_t)min(g, G - 1) * kTileCols;
+                if (gs) {
+                    const float v0 = exp_blocks_plain<BITS>(Lp, xg, 0, 2), v1 = exp_blocks_plain<BITS>(Lp, xg, 2, 4);
+                    if (g < G) {      // a lane past the end of the row adds nothing (not even 0 * inf)
+                        row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(sp & 0xFFFFu)), v0, row_sum);
+                        row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(sp >> 16)), v1, row_sum);
+                    }
+                } else {
+                    const uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)sp);
+                    const float v = exp_blocks_plain<BITS>(Lp, xg, 0, 4);
+                    if (g < G) row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)so), v, row_sum);
+                }
+            }
+            finish_tiles(q, it, row_sum);
+        }
+        return;
+    }
+
 #pragma unroll
     for (int n = 0; n < kExpOctetsPerThread; ++n) {
         const int i = tid + n * (WAVES * kWave);
@@ -259,6 +343,7 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
     const uint32_t zeros_at = (uint32_t)(uintptr_t)(lds_u32x4 *)zero_block;
 
     int it = 0;
+    float consumed = 0.f;       // the latest value computed from MFMA results: orders lds_read_keep behind them
     for (int64_t q = first; q * SLOTS < rowtiles; q += stride, ++it) {
         float row_sum = 0.f;
         for (int round = 0; round < my_rounds; ++round) {
@@ -269,7 +354,7 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
             const int g = round * kStep + part * 4 + t;
             // a lane past the end of the row multiplies the (valid) last group by zeros
             lds_read_keep(xa, g < G ? pieces_at + (uint32_t)((g * 4 + (lane & 3)) * (kPieceRun * 16)) : zeros_at,
-                          diagonal_lanes);
+                          diagonal_lanes, consumed);
             if (gs) {
                 lds_wait(xa);
                 int4_t d0{0, 0, 0, 0}, d1{0, 0, 0, 0};
@@ -286,29 +371,12 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
                 exp_blocks<BITS>(L, xa, 0, 4, d);
                 row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)so), exp_recombine(d), row_sum);
             }
+            consumed = row_sum;
 #pragma unroll
             for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
             s = sn;
         }
-
-        // lane (r, t) holds the groups of lane group t of row r: add the lane groups, then the
-        // wavefronts of the slot, in a fixed order.  The buffer alternates between tile sets, so one
-        // barrier per set separates the writes of set i + 2 from the reads of set i.
-        float *red_it = red + (it & 1) * (WAVES * kTileRows);
-        row_sum *= two_mk;
-        row_sum += __shfl_xor(row_sum, 16, kWave);
-        row_sum += __shfl_xor(row_sum, 32, kWave);
-        if (t == 0) red_it[wave * kTileRows + r] = row_sum;
-        __syncthreads();
-        if (tid < SLOTS * kTileRows) {
-            const int of_slot = tid / kTileRows, row = tid % kTileRows;
-            const int64_t tile = q * SLOTS + of_slot;
-            float sum = 0.f;
-#pragma unroll
-            for (int p = 0; p < kExpSplit; ++p) sum += red_it[(of_slot * kExpSplit + p) * kTileRows + row];
-            const _Float16 h = (_Float16)sum;
-            if (tile < rowtiles) y[tile * kTileRows + row] = __builtin_bit_cast(uint16_t, h);
-        }
+        finish_tiles(q, it, row_sum * two_mk);
     }
 }
 
@@ -410,15 +478,69 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
     if (tid < 8) zero_block[tid] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
     float two_k[MT], two_mk[MT];
+    bool non_finite = false;
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
 #pragma unroll
         for (int p = 0; p < WAVES; ++p) am[m] = max(am[m], amax_part[p * MT + m]);
         const int e = max((int)(am[m] >> 10), 1);
         const int k = 44 - e;
+        non_finite |= e == 31;
         two_k[m] = __builtin_bit_cast(float, (uint32_t)(k + 127) << 23);
-        two_mk[m] = e == 31 ? __builtin_nanf("") : __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
+        two_mk[m] = __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
     }
+
+    auto finish_tiles = [&](int64_t q, int it, const float (&row_sum)[MT]) {
+        float *red_it = red + (it & 1) * (WAVES * MT * kTileRows);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            float v = row_sum[m];
+            v += __shfl_xor(v, 16, kWave);
+            v += __shfl_xor(v, 32, kWave);
+            if (t == 0) red_it[(wave * MT + m) * kTileRows + r] = v;
+        }
+        __syncthreads();
+        if (tid < SLOTS * MT * kTileRows) {
+            const int of_slot = tid / (MT * kTileRows), m = (tid / kTileRows) % MT, row = tid % kTileRows;
+            const int64_t tile = q * SLOTS + of_slot;
+            float sum = 0.f;
+#pragma unroll
+            for (int p = 0; p < kExpSplit; ++p) sum += red_it[((of_slot * kExpSplit + p) * MT + m) * kTileRows + row];
+            const _Float16 h = (_Float16)sum;
+            if (tile < rowtiles && m < tokens) y[m * ystride + tile * kTileRows + row] = __builtin_bit_cast(uint16_t, h);
+        }
+    };
+
+    // An infinity or NaN in any of the vectors (the same for every workgroup of the launch): all
+    // vectors take plain binary32 products (see exp_blocks_plain), same tiles, same reduction.
+    if (non_finite) {
+        int it = 0;
+        for (int64_t q = first; q * SLOTS < rowtiles; q += stride, ++it) {
+            float row_sum[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m) row_sum[m] = 0.f;
+            for (int round = 0; round < my_rounds; ++round) {
+                u32x4 Lp[BITS];
+                uint32_t sp;
+                fetch(tile_of(q), round, Lp, sp);
+                const int g = round * kStep + part * 4 + t;
+                const float sf = (float)__builtin_bit_cast(_Float16, (uint16_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)sp));
+#pragma unroll 1
+                for (int m = 0; m < MT; ++m) {
+                    if (m >= tokens) break;
+                    const uint16_t *xg = (const uint16_t *)x + (size_t)m * K + (size_t)min(g, G - 1) * kTileCols;
+                    const float v = exp_blocks_plain<BITS>(Lp, xg, 0, 4);
+                    float add = __builtin_fmaf(sf, v, 0.f);
+#pragma unroll
+                    for (int mm = 0; mm < MT; ++mm)
+                        if (mm == m && g < G) row_sum[mm] += add;
+                }
+            }
+            finish_tiles(q, it, row_sum);
+        }
+        return;
+    }
+
 #pragma unroll
     for (int n = 0; n < kExpOctetsPerThread; ++n) {
         const int i = tid + n * THREADS;
@@ -475,25 +597,9 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
             for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
             s = sn;
         }
-
-        float *red_it = red + (it & 1) * (WAVES * MT * kTileRows);
 #pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            float v = row_sum[m] * two_mk[m];
-            v += __shfl_xor(v, 16, kWave);
-            v += __shfl_xor(v, 32, kWave);
-            if (t == 0) red_it[(wave * MT + m) * kTileRows + r] = v;
-        }
-        __syncthreads();
-        if (tid < SLOTS * MT * kTileRows) {
-            const int of_slot = tid / (MT * kTileRows), m = (tid / kTileRows) % MT, row = tid % kTileRows;
-            const int64_t tile = q * SLOTS + of_slot;
-            float sum = 0.f;
-#pragma unroll
-            for (int p = 0; p < kExpSplit; ++p) sum += red_it[((of_slot * kExpSplit + p) * MT + m) * kTileRows + row];
-            const _Float16 h = (_Float16)sum;
-            if (tile < rowtiles && m < tokens) y[m * ystride + tile * kTileRows + row] = __builtin_bit_cast(uint16_t, h);
-        }
+        for (int m = 0; m < MT; ++m) row_sum[m] *= two_mk[m];
+        finish_tiles(q, it, row_sum);
     }
 }
 

@@ -92,14 +92,61 @@ def test_activation_ranges(potq, kind):
         assert not got.any()
 
 
-def test_non_finite_activation_gives_nan(potq):
-    N, K, bits = 8192, 8192, 3
-    packed, S = workloads.pot_matrix(6, 9, N, K, bits, 128)
+def _same_non_finite(got_bits, want_bits, what):
+    g = got_bits.view(np.float16).astype(np.float64)
+    w = want_bits.view(np.float16).astype(np.float64)
+    assert not np.isfinite(w).any(), what              # every row meets the non-finite activation
+    assert np.array_equal(np.isnan(g), np.isnan(w)), what
+    inf = np.isinf(w)
+    assert np.array_equal(g[inf], w[inf]), what         # the same sign of infinity
+
+
+@pytest.mark.parametrize("N,K,bits,group", [(8192, 8192, 3, 128), (8208, 8192, 2, 64)])
+@pytest.mark.parametrize("case", ["one_inf", "two_inf_same_sign", "inf_both_signs", "nan", "inf_and_nan"])
+def test_non_finite_activations_follow_the_definition(potq, N, K, bits, group, case):
+    """An infinity among the activations reaches every row with the sign its weight gives it: rows whose
+    infinite terms agree come out as that infinity, the others as NaN; a NaN makes every row NaN.  The
+    result is the oracle's whichever kernel serves the matrix."""
+    packed, S = workloads.pot_matrix(6, 9, N, K, bits, group)
     x = _x("normal", K, 9)
-    x[17] = np.float16(np.inf)
+    if case == "one_inf":
+        x[17] = np.float16(np.inf)
+    elif case == "two_inf_same_sign":
+        x[17] = x[K - 3] = np.float16(-np.inf)
+    elif case == "inf_both_signs":
+        x[5], x[4100], x[K - 1] = np.float16(np.inf), np.float16(-np.inf), np.float16(np.inf)
+    elif case == "nan":
+        x[4242] = np.float16(np.nan)
+    else:
+        x[0], x[1] = np.float16(np.inf), np.float16(np.nan)
     tiled = potq.potq_repack(dev(packed), K, bits)
-    y = potq.pot_gemv(tiled, dev(S), dev(x), K, bits)
-    assert bool(torch.isnan(y).all())
+    got = host_bits(potq.pot_gemv(tiled, dev(S), dev(x), K, bits, group))
+    want = oracle.gemm(packed, S, None, x[None, :], K, bits, group, nthreads=_threads())[0]
+    _same_non_finite(got, want, (N, K, bits, group, case))
+    if case == "one_inf":
+        assert np.isinf(want.view(np.float16)).all() and len(np.unique(want)) == 2     # both signs occur
+    if case in ("two_inf_same_sign", "inf_both_signs"):     # the weights' signs decide, row by row
+        w = want.view(np.float16)
+        assert np.isnan(w).any() and np.isinf(w).any()
+
+
+def test_non_finite_activations_with_two_to_four_tokens(potq):
+    """The multi-vector kernel: one vector with an infinity, one with a NaN, two ordinary ones."""
+    M, N, K, bits = 4, 17920, 6656, 3
+    assert potq.potq_gemv_exponent_form(N, K, bits)
+    packed, S = workloads.pot_matrix(6, 58, N, K, bits, 128)
+    X = np.stack([_x("normal", K, 70 + m) for m in range(M)])
+    X[1, 33] = np.float16(-np.inf)
+    X[2, 6000] = np.float16(np.nan)
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    Y = host_bits(potq.pot_gemm(tiled, dev(S), dev(X), K, bits))
+    rows = np.unique(np.concatenate([[0, 15, 16, N - 1], np.arange(5, N, 61)]))
+    want = oracle.gemm(packed[rows], S[rows], None, X, K, bits, 128, nthreads=_threads())
+    for m in (1, 2):
+        _same_non_finite(Y[m][rows], want[m], ("tokens", m))
+    for m in (0, 3):
+        e, nw, nfloor = rel_err(Y[m][rows], want[m], K)
+        assert e <= REL_TOL, (m, e, nw, nfloor)
 
 
 @pytest.mark.parametrize("bits", [2, 3])
