@@ -3,17 +3,19 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras] [--no-cpu]
 
-Headline ("step"): one stand-alone PoT dequant pass over a Llama-2-7B-shaped
-decoder layer (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), 2-bit
-codes, group 128, all seven matrices in one pot_dequant_batch launch, inputs
-resident in HBM: the steps rotate through ten layers' worth of codes and scales
-so that they are read from HBM, not from the 256 MB last-level cache (the
-cache-resident figure is reported separately in the extras).  `value` is
-algorithmic bytes (codes + scales in, fp16 out) per second.  The same JSON
-line carries the roofline of the dominant kernel, the CPU oracle timed on the
-host cores, and (unless --no-extras) the uniform-INT baseline, the fused GEMV on
-the 7B shapes (3-bit) and the fused MFMA GEMM on the 13B shapes (3-bit,
-M = 16/64/256), each with its speed-up over the INT path.
+Headline ("step"): one stand-alone PoT dequant pass over a Llama-2-70B-shaped
+decoder layer (q/o 8192x8192, k/v 1024x8192, gate/up 28672x8192, down
+8192x28672: 855.6 M weights), 2-bit codes, group 128, all seven matrices in one
+pot_dequant_batch launch, inputs resident in HBM: the steps rotate through
+three layers' worth of codes and scales (0.68 GB) so that they are read from
+HBM, not from the 256 MB last-level cache.  `value` is algorithmic bytes (codes
++ scales in, fp16 out) per second.  The same JSON line carries the roofline of
+the dominant kernel, the CPU oracle timed on the host cores, and (unless
+--no-extras) one row per workload of the benchmark description: the 3-bit pass
+over the same layer, the 7B layer with its uniform-INT baseline, the single
+4096x4096 matrix, the fused GEMV on the 7B and 70B shapes at 2 and 3 bits, the
+fused MFMA GEMM on the 13B shapes, each with its fraction of the roof that
+bounds it and its speed-up over the INT path.
 
 All inputs are seeded synthetic tensors from workloads.py.  This run uses one
 GPU; --gpus above 1 is refused.
@@ -32,8 +34,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16 MFMA, published
-CONFIG_INDEX = 1                # the Llama-2-7B layer workload
-CODE_SETS = 10                  # layers' worth of codes and scales the timed steps rotate through (538 MB)
+CONFIG_INDEX = 3                # the Llama-2-70B layer workload (workloads.CONFIGS)
+CODE_SETS = 3                   # layers' worth of codes and scales the timed steps rotate through (3 x 227 MB)
+RAMP_UP = 100                   # untimed launches before the timed region (the first ~10 ms after idling run slow)
+
+# HBM bytes per launch of the headline kernel from rocprofv3 (FETCH_SIZE, WRITE_SIZE), measured once with the
+# commands in profiles/pot_dequant_batch_llama70b_layer.md; not re-measured by this script
+PROFILED_TRAFFIC = {"bytes_per_launch": None, "source": "profiles/pot_dequant_batch_llama70b_layer.md"}
 
 
 def _events(torch):
@@ -66,11 +73,28 @@ def _time_pair(torch, step_a, step_b, steps, warmup, reps=3):
     return ta[len(ta) // 2], tb[len(tb) // 2]
 
 
+def _hbm(nbytes, us):
+    """Row fields of a launch bound by HBM: algorithmic bytes over time against the 8 TB/s peak."""
+    gbps = nbytes / us / 1e3
+    return {"us": round(us, 2), "GBps": round(gbps, 1), "bound": "hbm", "frac": round(gbps / HBM_PEAK_GBPS, 4)}
+
+
+def _gemm_roof(M, N, K, nbytes, us):
+    """Row fields of a fused GEMM: the roof is whichever of HBM time and fp16 MFMA time is longer."""
+    flops = 2.0 * M * N * K
+    t_hbm, t_mfma = nbytes / HBM_PEAK_GBPS / 1e3, flops / MFMA_F16_PEAK_TFLOPS / 1e6      # microseconds
+    bound = "mfma" if t_mfma > t_hbm else "hbm"
+    return {"us": round(us, 2), "TFLOPs": round(flops / us / 1e6, 1), "GBps": round(nbytes / us / 1e3, 1),
+            "bound": bound, "frac": round(max(t_hbm, t_mfma) / us, 4),
+            "pct_mfma_peak": round(flops / us / 1e6 / MFMA_F16_PEAK_TFLOPS * 100, 2)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--bits", type=int, default=2, choices=(2, 3), help="code width of the headline pass")
     ap.add_argument("--no-extras", action="store_true", help="headline only (used for profiling runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -96,6 +120,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream().cuda_stream
     G = workloads.GROUP
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(workloads.seed_of(CONFIG_INDEX, 0, 9))
+    turn = [0]
 
     def to_dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
@@ -104,70 +131,68 @@ def main() -> int:
         if status != 0:
             raise RuntimeError(f"potq status {status}: {potq.strerror(status)}")
 
-    # ---------------------------------------------------------------- headline: 7B layer, 2-bit dequant
-    # The codes and scales of one layer (53.8 MB) would stay resident in the 256 MB last-level cache if every
-    # step re-read the same buffers, and the step would then be timed against cache, not HBM.  A decoder walks
-    # distinct layers, so the timed steps rotate through CODE_SETS layers' worth of codes and scales (538 MB,
-    # twice the cache) that all write the same output buffers.  Set 0 is the seeded workload of the parity
-    # tests; the others are filled with random bytes on the device (value-independent kernels).
-    bits = 2
-    shapes = workloads.LLAMA2_7B_LAYER
-    mats = []
-    for i, (name, N, K) in enumerate(shapes):
-        codes, scales = workloads.pot_matrix(CONFIG_INDEX, i, N, K, bits, G)
-        S, Z = workloads.int_scales_zeros(workloads.seed_of(CONFIG_INDEX, i, 3), N, K, bits, G)
-        mats.append(dict(name=name, N=N, K=K, codes_h=codes, scales_h=scales,
-                         codes=to_dev(codes), scales=to_dev(scales), S=to_dev(S), Z=to_dev(Z),
-                         out=torch.empty((N, K), dtype=torch.float16, device=dev)))
-    pot_bytes = sum(workloads.algorithmic_bytes_dequant(m["N"], m["K"], bits, G) for m in mats)
-    int_bytes = sum(workloads.algorithmic_bytes_dequant(m["N"], m["K"], bits, G, True) for m in mats)
-    weights = sum(m["N"] * m["K"] for m in mats)
+    def random_codes(N, K, bits):        # uniformly random bytes are uniformly random codes
+        return torch.randint(0, 256, (N, K * bits // 8), dtype=torch.uint8, device=dev, generator=gen)
 
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(workloads.seed_of(CONFIG_INDEX, 0, 9))
-    code_sets = [[(m["codes"], m["scales"], m["S"], m["Z"]) for m in mats]]
-    for _ in range(1, CODE_SETS):
-        layer = []
-        for m in mats:
-            c = torch.randint(0, 256, m["codes"].shape, dtype=torch.uint8, device=dev, generator=gen)
-            # scales drawn from the seeded ones by a device-side permutation: same distribution, other bytes
-            perm = torch.randperm(m["scales"].numel(), device=dev, generator=gen)
-            layer.append((c, m["scales"].flatten()[perm].reshape(m["scales"].shape).contiguous(),
-                          m["S"].flatten()[perm].reshape(m["S"].shape).contiguous(),
-                          m["Z"].flatten()[perm].reshape(m["Z"].shape).contiguous()))
-        code_sets.append(layer)
+    def permuted(t):                      # same values, other places: same distribution, other bytes
+        perm = torch.randperm(t.numel(), device=dev, generator=gen)
+        return t.flatten()[perm].reshape(t.shape).contiguous()
 
-    pot_calls = [(m["codes"].data_ptr(), m["scales"].data_ptr(), m["out"].data_ptr(), m["N"], m["K"], bits, G, stream)
-                 for m in mats]
-    pot_items = [binding.make_batch([(cs[0], cs[1], None, m["out"], m["K"], bits) for cs, m in zip(layer, mats)])
-                 for layer in code_sets]
-    int_items = [binding.make_batch([(cs[0], cs[2], cs[3], m["out"], m["K"], bits) for cs, m in zip(layer, mats)],
-                                    is_int=True) for layer in code_sets]
-    turn = [0]
+    class Layer:
+        """A decoder layer's matrices for the stand-alone dequant: `sets` rotating sets of codes and scales
+        (set 0 is the seeded workload of the parity tests, the others are device-side random bytes and
+        permutations of the seeded scales) that all write the same output buffers."""
 
-    def pot_step():          # the whole layer in one launch, next layer's codes every step
-        turn[0] += 1
-        check(lib.pot_dequant_batch(pot_items[turn[0] % CODE_SETS], len(mats), bits, G, stream))
+        def __init__(self, config, shapes, bits, sets, with_int=False, keep_host=False):
+            self.shapes, self.bits, self.n_sets = shapes, bits, sets
+            self.outs = [torch.empty((N, K), dtype=torch.float16, device=dev) for _, N, K in shapes]
+            self.host = []
+            first = []
+            for i, (_, N, K) in enumerate(shapes):
+                codes, scales = workloads.pot_matrix(config, i, N, K, bits, G)
+                if keep_host:
+                    self.host.append((codes, scales, K))
+                S = Z = None
+                if with_int:
+                    S, Z = (to_dev(a) for a in workloads.int_scales_zeros(workloads.seed_of(config, i, 3), N, K, bits, G))
+                first.append((to_dev(codes), to_dev(scales), S, Z))
+            self.sets = [first]
+            for _ in range(1, sets):
+                self.sets.append([(random_codes(N, K, bits), permuted(f[1]),
+                                   permuted(f[2]) if with_int else None, permuted(f[3]) if with_int else None)
+                                  for f, (_, N, K) in zip(first, shapes)])
+            self.pot_items = [binding.make_batch([(c, s, None, o, K, bits) for (c, s, _, _), o, (_, _, K)
+                                                  in zip(layer, self.outs, shapes)]) for layer in self.sets]
+            self.int_items = [binding.make_batch([(c, S, Z, o, K, bits) for (c, _, S, Z), o, (_, _, K)
+                                                  in zip(layer, self.outs, shapes)], is_int=True)
+                              for layer in self.sets] if with_int else None
+            self.pot_bytes = sum(workloads.algorithmic_bytes_dequant(N, K, bits, G) for _, N, K in shapes)
+            self.int_bytes = sum(workloads.algorithmic_bytes_dequant(N, K, bits, G, True) for _, N, K in shapes)
+            self.weights = sum(N * K for _, N, K in shapes)
 
-    def int_step():
-        turn[0] += 1
-        check(lib.int_dequant_batch(int_items[turn[0] % CODE_SETS], len(mats), bits, G, stream))
+        def pot_step(self):                # the whole layer in one launch, the next set's codes every step
+            turn[0] += 1
+            check(lib.pot_dequant_batch(self.pot_items[turn[0] % self.n_sets], len(self.shapes), self.bits, G, stream))
 
-    def pot_step_resident():  # the same buffers every step: codes served by the last-level cache
-        check(lib.pot_dequant_batch(pot_items[0], len(mats), bits, G, stream))
+        def int_step(self):
+            turn[0] += 1
+            check(lib.int_dequant_batch(self.int_items[turn[0] % self.n_sets], len(self.shapes), self.bits, G, stream))
 
-    def pot_step_7():        # the same work as seven separate launches (same buffers every step)
-        for c in pot_calls:
-            check(lib.pot_dequant(*c))
+        def ramp_up(self, n=RAMP_UP):
+            for _ in range(n):
+                self.pot_step()
+            torch.cuda.synchronize()
 
-    # The first ~10 ms of GPU work in a process run 4-7 % slow (clock ramp-up, cold TLBs): whatever --warmup
-    # says, 200 untimed steps of the same launch come first so that the timed region sees the steady state.
-    for _ in range(200):
-        pot_step()
-    torch.cuda.synchronize()
-    ms = _time_steps(torch, pot_step, args.steps, args.warmup)
-    value = pot_bytes / (ms * 1e-3) / 1e9
-    launches = 1
+    # ---------------------------------------------------------------- headline: 70B layer dequant
+    # The codes and scales of one layer (227 MB at 2 bits) would partly stay in the 256 MB last-level cache if
+    # every step re-read the same buffers; a decoder walks distinct layers, so the steps rotate through
+    # CODE_SETS layers' worth.  Whatever --warmup says, RAMP_UP untimed launches come first so that the timed
+    # region sees the steady state (clock ramp-up, cold address translation).
+    bits = args.bits
+    head = Layer(CONFIG_INDEX, workloads.LLAMA2_70B_LAYER, bits, CODE_SETS, keep_host=not args.no_cpu)
+    head.ramp_up()
+    ms = _time_steps(torch, head.pot_step, args.steps, args.warmup)
+    value = head.pot_bytes / (ms * 1e-3) / 1e9
     result = {
         "metric": "PoT dequant GB/s (algorithmic bytes: codes + scales in, fp16 out)",
         "value": round(value, 1),
@@ -181,24 +206,24 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "u16",
         "data": "synthetic",
-        "config": {"workload": "Llama-2-7B decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008), "
-                               "2-bit PoT codes, group 128, stand-alone dequant of all seven matrices",
-                   "bits": bits, "group": G, "weights": weights, "launches_per_step": launches,
+        "config": {"workload": "Llama-2-70B decoder layer (q,o 8192x8192; k,v 1024x8192; gate,up 28672x8192; "
+                               f"down 8192x28672), {bits}-bit PoT codes, group 128, stand-alone dequant of all "
+                               "seven matrices",
+                   "bits": bits, "group": G, "weights": head.weights, "launches_per_step": 1,
                    "entry_point": "pot_dequant_batch", "layout": "canonical",
-                   "code_sets_rotated": CODE_SETS},
+                   "code_sets_rotated": CODE_SETS, "untimed_ramp_up_launches": RAMP_UP},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "roofline": {
-            "kernel": "potq::dequant_batch_kernel<2, false>",
+            "kernel": f"potq::dequant_batch_kernel<{bits}, false>",
             "bound": "hbm",
             "achieved": round(value, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(value / HBM_PEAK_GBPS, 4),
-            "bytes_per_launch": pot_bytes / launches,
-            "us_per_launch": round(ms * 1e3 / launches, 3),
-            # HBM bytes per launch from rocprofv3 FETCH_SIZE (x2.000) + WRITE_SIZE (x1.000), factors calibrated
-            # on a 256 MiB copy; figures and commands in profiles/pot_dequant_batch_b2_llama7b_layer.md
-            "traffic": 458576323,
+            "bytes_per_launch": head.pot_bytes,
+            "us_per_launch": round(ms * 1e3, 3),
+            "traffic": PROFILED_TRAFFIC["bytes_per_launch"] if bits == 2 else None,
+            "traffic_source": PROFILED_TRAFFIC["source"],
         },
     }
 
@@ -219,64 +244,127 @@ def main() -> int:
         passes = 0
         t0 = time.perf_counter()
         while passes < 64 and (passes == 0 or time.perf_counter() - t0 < 12.0):
-            for m in mats:
-                oracle.pot_dequant(m["codes_h"], m["scales_h"], m["K"], bits, G, nthreads=threads)
+            for codes_h, scales_h, K in head.host:
+                oracle.pot_dequant(codes_h, scales_h, K, bits, G, nthreads=threads)
             passes += 1
         dt = time.perf_counter() - t0
         result["cpu_baseline"] = {
-            "value": round(passes * pot_bytes / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": f"{passes} full passes over the same seven matrices (202.4 M weights each), "
+            "value": round(passes * head.pot_bytes / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{passes} full passes over the same seven matrices ({head.weights / 1e6:.1f} M weights each), "
                       "oracle/potq_oracle.c pot_dequant, OpenMP over rows",
             "seconds": round(dt, 2),
         }
-    for m in mats:
-        del m["codes_h"], m["scales_h"]
+    head.host = []
+
+    if args.no_extras:
+        print(json.dumps(result))
+        return 0
 
     # ---------------------------------------------------------------- extras
-    if not args.no_extras:
-        extras = {}
-        for _ in range(200):                 # the GPU idled during the CPU baseline: ramp up again, untimed
-            pot_step()
-        torch.cuda.synchronize()
-        ms_pot2, ms_int = _time_pair(torch, pot_step, int_step, args.steps, 20)
-        extras["int_dequant_7b_layer_2bit"] = {
-            "GBps": round(int_bytes / (ms_int * 1e-3) / 1e9, 1), "ms_per_step": round(ms_int, 5),
-            "pot_ms_per_step_same_pass": round(ms_pot2, 5), "pot_speedup_vs_int": round(ms_int / ms_pot2, 4),
-            "note": "PoT and INT measured alternately, three times each, medians"}
-        ms_res = _time_steps(torch, pot_step_resident, args.steps, args.warmup)
-        extras["pot_dequant_7b_layer_2bit_cache_resident_codes"] = {
-            "GBps": round(pot_bytes / (ms_res * 1e-3) / 1e9, 1), "ms_per_step": round(ms_res, 5),
-            "note": "one set of code buffers re-read every step: the 53.8 MB of codes and scales come from the "
-                    "256 MB last-level cache, only the writes reach HBM"}
-        ms7 = _time_steps(torch, pot_step_7, args.steps, args.warmup)
-        extras["pot_dequant_7b_layer_2bit_seven_launches"] = {
-            "GBps": round(pot_bytes / (ms7 * 1e-3) / 1e9, 1), "ms_per_step": round(ms7, 5),
-            "note": "cache-resident codes (one buffer set)"}
-        del mats, pot_calls, pot_items, int_items, code_sets
-        torch.cuda.empty_cache()
+    extras = {}
+    head.ramp_up()                       # the GPU idled during the CPU baseline: ramp up again, untimed
 
-        def rotate(nbytes_per_set):
-            return max(2, min(64, (1 << 30) // max(1, nbytes_per_set) + 1))
+    # value-independence of the (branch-free) kernel: the same pass over all-zero codes
+    zero_items = []
+    zero_keep = []
+    for _ in range(CODE_SETS):
+        layer = [(torch.zeros_like(c), s) for (c, s, _, _) in head.sets[0]]
+        zero_keep.append(layer)
+        zero_items.append(binding.make_batch([(c, s, None, o, K, bits) for (c, s), o, (_, _, K)
+                                              in zip(layer, head.outs, head.shapes)]))
 
-        # fused GEMV, 3-bit, 7B shapes, rotating through distinct weight buffers (>= 1 GiB in total)
-        gemv = []
-        b3 = 3
-        for i, (name, N, K) in enumerate(workloads.GEMV_7B_SHAPES):
-            nbytes = workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
+    def zero_step():
+        turn[0] += 1
+        check(lib.pot_dequant_batch(zero_items[turn[0] % CODE_SETS], len(head.shapes), bits, G, stream))
+
+    ms_rand, ms_zero = _time_pair(torch, head.pot_step, zero_step, 30, 5)
+    extras["value_independence"] = {
+        "random_codes_us": round(ms_rand * 1e3, 1), "all_zero_codes_us": round(ms_zero * 1e3, 1),
+        "ratio": round(ms_zero / ms_rand, 4), "independent_within_3pct": bool(abs(ms_zero / ms_rand - 1.0) < 0.03)}
+    del zero_items, zero_keep
+
+    # ceilings of this machine: a plain device copy and a plain fill (torch kernels, 512 MiB buffers)
+    ca = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+    cb = torch.empty_like(ca)
+    ms_copy = _time_steps(torch, lambda: cb.copy_(ca), 20, 5)
+    ms_fill = _time_steps(torch, lambda: cb.zero_(), 20, 5)
+    extras["box_ceilings"] = {"device_copy_GBps": round(2 * ca.numel() / ms_copy / 1e6, 1),
+                              "fill_GBps": round(ca.numel() / ms_fill / 1e6, 1),
+                              "note": "torch copy_ / zero_ on 512 MiB: what plain streaming kernels reach here"}
+    del ca, cb
+
+    # the other code width on the same layer
+    other = 5 - bits
+    del head
+    torch.cuda.empty_cache()
+    lay = Layer(CONFIG_INDEX, workloads.LLAMA2_70B_LAYER, other, CODE_SETS)
+    lay.ramp_up()
+    ms_o = _time_steps(torch, lay.pot_step, args.steps, args.warmup)
+    extras[f"pot_dequant_70b_layer_{other}bit"] = dict(_hbm(lay.pot_bytes, ms_o * 1e3), kernel=f"dequant_batch_kernel<{other}, false>")
+    del lay
+    torch.cuda.empty_cache()
+
+    # Llama-2-7B layer, 2 bits, with the uniform-INT baseline (ten rotating sets: 538 MB)
+    l7 = Layer(1, workloads.LLAMA2_7B_LAYER, 2, 10, with_int=True)
+    l7.ramp_up(200)
+    ms_p7, ms_i7 = _time_pair(torch, l7.pot_step, l7.int_step, 200, 20)
+    extras["pot_dequant_7b_layer_2bit"] = dict(_hbm(l7.pot_bytes, ms_p7 * 1e3), int_us=round(ms_i7 * 1e3, 2),
+                                                int_GBps=round(l7.int_bytes / ms_i7 / 1e6, 1),
+                                                pot_speedup_vs_int=round(ms_i7 / ms_p7, 4),
+                                                note="PoT and INT measured alternately, three times each, medians")
+    one = l7.pot_items[0]
+    ms_res = _time_steps(torch, lambda: check(lib.pot_dequant_batch(one, 7, 2, G, stream)), 200, 20)
+    extras["pot_dequant_7b_layer_2bit_cache_resident_codes"] = dict(
+        _hbm(l7.pot_bytes, ms_res * 1e3),
+        note="one set of code buffers re-read every step: the 53.8 MB of codes and scales come from the 256 MB "
+             "last-level cache, only the writes reach HBM")
+    del l7, one
+    torch.cuda.empty_cache()
+
+    # single 4096 x 4096 matrix, 3 bits (pot_dequant): rotating through 27 buffer sets (1.08 GB), and re-using one
+    N1 = K1 = 4096
+    nb1 = workloads.algorithmic_bytes_dequant(N1, K1, 3, G)
+    c1, s1 = (to_dev(a) for a in workloads.pot_matrix(0, 0, N1, K1, 3, G))
+    sets1 = [(c1, s1, torch.empty((N1, K1), dtype=torch.float16, device=dev))]
+    for _ in range(26):
+        sets1.append((random_codes(N1, K1, 3), permuted(s1), torch.empty((N1, K1), dtype=torch.float16, device=dev)))
+    calls1 = [(c.data_ptr(), s.data_ptr(), o.data_ptr(), N1, K1, 3, G, stream) for c, s, o in sets1]
+
+    def single_rot():
+        for c in calls1:
+            check(lib.pot_dequant(*c))
+
+    def single_res():
+        check(lib.pot_dequant(*calls1[0]))
+
+    single_rot()
+    us_rot = _time_steps(torch, single_rot, 10, 3) * 1e3 / len(calls1)
+    us_res = _time_steps(torch, single_res, 200, 20) * 1e3
+    extras["pot_dequant_4096x4096_3bit"] = dict(_hbm(nb1, us_rot), buffers_rotated=len(calls1),
+                                                 cache_resident=dict(_hbm(nb1, us_res),
+                                                                     note="one 40 MB buffer set re-used: inputs and "
+                                                                          "outputs stay in the 256 MB last-level cache"))
+    del sets1, calls1, c1, s1
+    torch.cuda.empty_cache()
+
+    def rotate(nbytes_per_set):
+        return max(2, min(64, (1 << 30) // max(1, nbytes_per_set) + 1))
+
+    def gemv_pairs(shapes, bb, seed_cfg):
+        """PoT and INT GEMV per shape, measured alternately, weight buffers rotating through HBM."""
+        rows_ = []
+        for j, (N, K) in enumerate(shapes):
+            nbytes = workloads.algorithmic_bytes_gemm(1, N, K, bb, G)
             R = rotate(nbytes)
-            codes_h, scales_h = workloads.pot_matrix(2, i, N, K, b3, G)
-            S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(2, i, 3), N, K, b3, G)
-            x = to_dev(workloads.activations(workloads.seed_of(2, i, 2), 1, K)[0])
-            tiled = potq.potq_repack(to_dev(codes_h), K, b3)
-            sets = [tiled.clone() for _ in range(R)]
-            sc = [to_dev(scales_h) for _ in range(R)]
-            Ss = [to_dev(S_h) for _ in range(R)]
-            Zs = [to_dev(Z_h) for _ in range(R)]
+            cs = [random_codes(N, K, bb) for _ in range(R)]
+            sc_ = to_dev(workloads.pot_scales(workloads.seed_of(seed_cfg, j, 1), N, K, G))
+            S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(seed_cfg, j, 3), N, K, bb, G)
+            Sd_, Zd_ = to_dev(S_h), to_dev(Z_h)
+            x = to_dev(workloads.activations(workloads.seed_of(seed_cfg, j, 2), 1, K)[0])
             y = torch.empty((N,), dtype=torch.float16, device=dev)
-            pc = [(sets[r].data_ptr(), sc[r].data_ptr(), x.data_ptr(), y.data_ptr(), N, K, b3, G, 1, stream)
-                  for r in range(R)]
-            ic = [(sets[r].data_ptr(), Ss[r].data_ptr(), Zs[r].data_ptr(), x.data_ptr(), y.data_ptr(), N, K, b3, G, 1,
-                   stream) for r in range(R)]
+            pc = [(c.data_ptr(), sc_.data_ptr(), x.data_ptr(), y.data_ptr(), N, K, bb, G, 1, stream) for c in cs]
+            ic = [(c.data_ptr(), Sd_.data_ptr(), Zd_.data_ptr(), x.data_ptr(), y.data_ptr(), N, K, bb, G, 1, stream)
+                  for c in cs]
 
             def pot_rot():
                 for c in pc:
@@ -286,232 +374,163 @@ def main() -> int:
                 for c in ic:
                     check(lib.int_gemv(*c))
 
-            reps = max(2, 256 // R)
-            us_p, us_i = (t * 1e3 / R for t in _time_pair(torch, pot_rot, int_rot, reps, 2))
-            gemv.append({"shape": f"{N}x{K}", "us": round(us_p, 2), "GBps": round(nbytes / us_p / 1e3, 1),
-                         "pct_hbm_peak": round(nbytes / us_p / 1e3 / HBM_PEAK_GBPS * 100, 1),
-                         "TFLOPs": round(2.0 * N * K / us_p / 1e6, 2), "int_us": round(us_i, 2),
-                         "pot_speedup_vs_int": round(us_i / us_p, 3), "buffers_rotated": R})
-            del sets, sc, Ss, Zs, pc, ic
-        extras["pot_gemv_3bit_7b_shapes"] = gemv
-        torch.cuda.empty_cache()
-
-        # shared-activation batches: q/k/v (3 x 4096x4096) and gate/up (2 x 11008x4096) in one launch each
-        shared = []
-        for label, (N, K), copies in (("qkv 3x4096x4096", (4096, 4096), 3), ("gate_up 2x11008x4096", (11008, 4096), 2)):
-            nbytes = copies * workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
-            R = rotate(nbytes)
-            codes_h, scales_h = workloads.pot_matrix(2, 7, N, K, b3, G)
-            x = to_dev(workloads.activations(workloads.seed_of(2, 7, 2), 1, K)[0])
-            tiled = potq.potq_repack(to_dev(codes_h), K, b3)
-            keep, batches, singles = [], [], []
-            for r in range(R):
-                ms_ = [(tiled.clone(), to_dev(scales_h), None,
-                        torch.empty((N,), dtype=torch.float16, device=dev)) for _ in range(copies)]
-                keep.append(ms_)
-                batches.append(binding.make_gemv_batch(ms_, K, b3))
-                singles.append([(m_[0].data_ptr(), m_[1].data_ptr(), x.data_ptr(), m_[3].data_ptr(), N, K, b3, G, 1,
-                                 stream) for m_ in ms_])
-
-            def batch_rot():
-                for arr in batches:
-                    check(lib.pot_gemv_batch(arr, copies, x.data_ptr(), K, b3, G, 1, stream))
-
-            def single_rot():
-                for calls in singles:
-                    for c in calls:
-                        check(lib.pot_gemv(*c))
-
             reps = max(2, 128 // R)
-            us_b, us_s = (t * 1e3 / R for t in _time_pair(torch, batch_rot, single_rot, reps, 2))
-            shared.append({"batch": label, "us_one_launch": round(us_b, 2), "us_separate_launches": round(us_s, 2),
-                           "GBps": round(nbytes / us_b / 1e3, 1), "buffers_rotated": R})
-            del keep, batches, singles
-        extras["pot_gemv_batch_3bit_shared_activation"] = shared
-        torch.cuda.empty_cache()
-
-        # the seven projections of one decoder layer at batch 1 as a decoder issues them: q/k/v in one launch,
-        # o, gate/up in one launch, down (four launches), rotating through enough layers' worth of weights to
-        # exceed the last-level cache; random bytes are valid codes, the activations are unrelated vectors
-        def decoder_layer_batch1(hidden, kv_rows, ffn, layers):
-            shapes = [(hidden, hidden), (kv_rows, hidden), (kv_rows, hidden), (hidden, hidden),
-                      (ffn, hidden), (ffn, hidden), (hidden, ffn)]
-            layer_bytes = sum(workloads.algorithmic_bytes_gemm(1, N, K, b3, G) for N, K in shapes)
-            xh = to_dev(workloads.activations(workloads.seed_of(2, 8, 2), 1, hidden)[0])
-            xf = to_dev(workloads.activations(workloads.seed_of(2, 9, 2), 1, ffn)[0])
-            keep, steps_ = [], []
-            for _ in range(layers):
-                def mat(N, K):
-                    c = torch.randint(0, 256, (N, K * b3 // 8), dtype=torch.uint8, device=dev, generator=gen)
-                    sc_ = to_dev(workloads.pot_scales(workloads.seed_of(2, 8, 1), N, K, G))
-                    return (c, sc_, None, torch.empty((N,), dtype=torch.float16, device=dev))
-                qkv = [mat(hidden, hidden), mat(kv_rows, hidden), mat(kv_rows, hidden)]
-                o = mat(hidden, hidden)
-                gu = [mat(ffn, hidden) for _ in range(2)]
-                dn = mat(hidden, ffn)
-                keep.append((qkv, o, gu, dn))
-                steps_.append((binding.make_gemv_batch(qkv, hidden, b3), binding.make_gemv_batch(gu, hidden, b3),
-                               (o[0].data_ptr(), o[1].data_ptr(), xh.data_ptr(), o[3].data_ptr(), hidden, hidden, b3, G,
-                                1, stream),
-                               (dn[0].data_ptr(), dn[1].data_ptr(), xf.data_ptr(), dn[3].data_ptr(), hidden, ffn, b3, G,
-                                1, stream)))
-
-            def layer_rot():
-                for b_qkv, b_gu, c_o, c_dn in steps_:
-                    check(lib.pot_gemv_batch(b_qkv, 3, xh.data_ptr(), hidden, b3, G, 1, stream))
-                    check(lib.pot_gemv(*c_o))
-                    check(lib.pot_gemv_batch(b_gu, 2, xh.data_ptr(), hidden, b3, G, 1, stream))
-                    check(lib.pot_gemv(*c_dn))
-
-            us_layer = _time_steps(torch, layer_rot, max(2, 128 // layers), 2) * 1e3 / layers
-            del keep, steps_
+            us_p, us_i = (t * 1e3 / R for t in _time_pair(torch, pot_rot, int_rot, reps, 2))
+            rows_.append(dict(_hbm(nbytes, us_p), shape=f"{N}x{K}", bits=bb, TFLOPs=round(2.0 * N * K / us_p / 1e6, 2),
+                              int_us=round(us_i, 2), pot_speedup_vs_int=round(us_i / us_p, 3), buffers_rotated=R,
+                              exponent_form=bool(potq.potq_gemv_exponent_form(N, K, bb))))
+            del cs, pc, ic
             torch.cuda.empty_cache()
-            return {"us_per_layer": round(us_layer, 2), "launches_per_layer": 4,
-                    "GBps": round(layer_bytes / us_layer / 1e3, 1),
-                    "pct_hbm_peak": round(layer_bytes / us_layer / 1e3 / HBM_PEAK_GBPS * 100, 1),
-                    "layers_rotated": layers}
+        return rows_
 
-        extras["pot_gemv_3bit_7b_decoder_layer_batch1"] = decoder_layer_batch1(4096, 4096, 11008, 16)
-        extras["pot_gemv_3bit_70b_decoder_layer_batch1"] = decoder_layer_batch1(8192, 1024, 28672, 3)
+    b3 = 3
+    shapes7 = [(N, K) for _, N, K in workloads.GEMV_7B_SHAPES]
+    shapes70 = [(8192, 8192), (1024, 8192), (28672, 8192), (8192, 28672)]
+    extras["pot_gemv_7b_shapes"] = gemv_pairs(shapes7, 3, 2) + gemv_pairs(shapes7, 2, 2)
+    extras["pot_gemv_70b_shapes"] = gemv_pairs(shapes70, 3, 3) + gemv_pairs(shapes70, 2, 3)
+    # the vocabulary projection of a decoder (32000 or 128256 rows): the largest matrix of a decode step
+    extras["pot_gemv_3bit_vocabulary_projection"] = gemv_pairs(((32000, 4096), (128256, 4096), (128256, 8192)), 3, 3)
 
-        # Llama-2-70B layer (GQA shapes): stand-alone dequant of all seven matrices in one launch at 2 and 3
-        # bits (four rotating code sets: 0.9 / 1.3 GB of codes), and the batch-1 GEMV of its four distinct shapes
-        big = {}
-        outs70 = [torch.empty((N, K), dtype=torch.float16, device=dev) for _, N, K in workloads.LLAMA2_70B_LAYER]
-        for bb in (2, 3):
-            nb = sum(workloads.algorithmic_bytes_dequant(N, K, bb, G) for _, N, K in workloads.LLAMA2_70B_LAYER)
-            sets70, keep70 = [], []
-            for _ in range(4):
-                ms_ = []
-                for j, (_, N, K) in enumerate(workloads.LLAMA2_70B_LAYER):
-                    c = torch.randint(0, 256, (N, K * bb // 8), dtype=torch.uint8, device=dev, generator=gen)
-                    ms_.append((c, to_dev(workloads.pot_scales(workloads.seed_of(3, j, 1), N, K, G)), None, outs70[j], K, bb))
-                keep70.append(ms_)
-                sets70.append(binding.make_batch(ms_))
+    # shared-activation batches: q/k/v (3 x 4096x4096) and gate/up (2 x 11008x4096) in one launch each
+    shared = []
+    for label, (N, K), copies in (("qkv 3x4096x4096", (4096, 4096), 3), ("gate_up 2x11008x4096", (11008, 4096), 2)):
+        nbytes = copies * workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
+        R = rotate(nbytes)
+        scales_h = workloads.pot_scales(workloads.seed_of(2, 7, 1), N, K, G)
+        x = to_dev(workloads.activations(workloads.seed_of(2, 7, 2), 1, K)[0])
+        keep, batches, singles = [], [], []
+        for r in range(R):
+            ms_ = [(random_codes(N, K, b3), to_dev(scales_h), None,
+                    torch.empty((N,), dtype=torch.float16, device=dev)) for _ in range(copies)]
+            keep.append(ms_)
+            batches.append(binding.make_gemv_batch(ms_, K, b3))
+            singles.append([(m_[0].data_ptr(), m_[1].data_ptr(), x.data_ptr(), m_[3].data_ptr(), N, K, b3, G, 1,
+                             stream) for m_ in ms_])
 
-            def step70():
+        def batch_rot():
+            for arr in batches:
+                check(lib.pot_gemv_batch(arr, copies, x.data_ptr(), K, b3, G, 1, stream))
+
+        def single_rot2():
+            for calls in singles:
+                for c in calls:
+                    check(lib.pot_gemv(*c))
+
+        reps = max(2, 128 // R)
+        us_b, us_s = (t * 1e3 / R for t in _time_pair(torch, batch_rot, single_rot2, reps, 2))
+        shared.append(dict(_hbm(nbytes, us_b), batch=label, us_separate_launches=round(us_s, 2), buffers_rotated=R))
+        del keep, batches, singles
+    extras["pot_gemv_batch_3bit_shared_activation"] = shared
+    torch.cuda.empty_cache()
+
+    # the seven projections of one decoder layer at batch 1 as a decoder issues them: q/k/v in one launch,
+    # o, gate/up in one launch, down (four launches), rotating through enough layers' worth of weights to
+    # exceed the last-level cache; random bytes are valid codes, the activations are unrelated vectors
+    def decoder_layer_batch1(hidden, kv_rows, ffn, layers):
+        shapes = [(hidden, hidden), (kv_rows, hidden), (kv_rows, hidden), (hidden, hidden),
+                  (ffn, hidden), (ffn, hidden), (hidden, ffn)]
+        layer_bytes = sum(workloads.algorithmic_bytes_gemm(1, N, K, b3, G) for N, K in shapes)
+        xh = to_dev(workloads.activations(workloads.seed_of(2, 8, 2), 1, hidden)[0])
+        xf = to_dev(workloads.activations(workloads.seed_of(2, 9, 2), 1, ffn)[0])
+        keep, steps_ = [], []
+        for _ in range(layers):
+            def mat(N, K):
+                sc_ = to_dev(workloads.pot_scales(workloads.seed_of(2, 8, 1), N, K, G))
+                return (random_codes(N, K, b3), sc_, None, torch.empty((N,), dtype=torch.float16, device=dev))
+            qkv = [mat(hidden, hidden), mat(kv_rows, hidden), mat(kv_rows, hidden)]
+            o = mat(hidden, hidden)
+            gu = [mat(ffn, hidden) for _ in range(2)]
+            dn = mat(hidden, ffn)
+            keep.append((qkv, o, gu, dn))
+            steps_.append((binding.make_gemv_batch(qkv, hidden, b3), binding.make_gemv_batch(gu, hidden, b3),
+                           (o[0].data_ptr(), o[1].data_ptr(), xh.data_ptr(), o[3].data_ptr(), hidden, hidden, b3, G,
+                            1, stream),
+                           (dn[0].data_ptr(), dn[1].data_ptr(), xf.data_ptr(), dn[3].data_ptr(), hidden, ffn, b3, G,
+                            1, stream)))
+
+        def layer_rot():
+            for b_qkv, b_gu, c_o, c_dn in steps_:
+                check(lib.pot_gemv_batch(b_qkv, 3, xh.data_ptr(), hidden, b3, G, 1, stream))
+                check(lib.pot_gemv(*c_o))
+                check(lib.pot_gemv_batch(b_gu, 2, xh.data_ptr(), hidden, b3, G, 1, stream))
+                check(lib.pot_gemv(*c_dn))
+
+        us_layer = _time_steps(torch, layer_rot, max(2, 128 // layers), 2) * 1e3 / layers
+        del keep, steps_
+        torch.cuda.empty_cache()
+        return dict(_hbm(layer_bytes, us_layer), launches_per_layer=4, layers_rotated=layers)
+
+    extras["pot_gemv_3bit_7b_decoder_layer_batch1"] = decoder_layer_batch1(4096, 4096, 11008, 16)
+    extras["pot_gemv_3bit_70b_decoder_layer_batch1"] = decoder_layer_batch1(8192, 1024, 28672, 3)
+
+    # fused MFMA GEMM, 3-bit, 13B shapes; the calls rotate through enough copies of the weight codes
+    # (random bytes are valid codes) that they are read from HBM, not from the 256 MB last-level cache
+    gemm = []
+    for i, (name, N, K) in enumerate(workloads.GEMM_13B_SHAPES):
+        codes_h, scales_h = workloads.pot_matrix(4, i, N, K, b3, G)
+        S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(4, i, 3), N, K, b3, G)
+        tiled = [potq.potq_repack(to_dev(codes_h), K, b3)]
+        R = max(2, int(640e6 // tiled[0].numel()) + 1)
+        for _ in range(1, R):
+            tiled.append(torch.randint(0, 256, tiled[0].shape, dtype=torch.uint8, device=dev, generator=gen))
+        sc, Sd, Zd = to_dev(scales_h), to_dev(S_h), to_dev(Z_h)
+        for M in workloads.GEMM_TOKENS:
+            X = to_dev(workloads.activations(workloads.seed_of(4, i, 2) + M, M, K))
+            Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+            ws = potq.gemm_workspace(M, N, K, b3)
+            wp, wn = (ws.data_ptr(), ws.numel()) if ws is not None else (None, 0)
+            pas = [(t.data_ptr(), sc.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1, wp, wn, stream)
+                   for t in tiled]
+            ias = [(t.data_ptr(), Sd.data_ptr(), Zd.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1,
+                    wp, wn, stream) for t in tiled]
+
+            def pot_rot():
                 turn[0] += 1
-                check(lib.pot_dequant_batch(sets70[turn[0] % 4], 7, bb, G, stream))
+                check(lib.pot_gemm(*pas[turn[0] % R]))
 
-            ms70 = _time_steps(torch, step70, 24, 4)
-            big[f"dequant_{bb}bit"] = {"us": round(ms70 * 1e3, 1), "GBps": round(nb / ms70 / 1e6, 1),
-                                       "pct_hbm_peak": round(nb / ms70 / 1e6 / HBM_PEAK_GBPS * 100, 1)}
-            del sets70, keep70
-            torch.cuda.empty_cache()
-        del outs70
+            def int_rot():
+                turn[0] += 1
+                check(lib.int_gemm(*ias[turn[0] % R]))
+
+            us_p, us_i = (t * 1e3 for t in _time_pair(torch, pot_rot, int_rot, 2 * R, 3))
+            gemm.append(dict(_gemm_roof(M, N, K, workloads.algorithmic_bytes_gemm(M, N, K, b3, G), us_p),
+                             shape=f"{N}x{K}", M=M, int_us=round(us_i, 2), pot_speedup_vs_int=round(us_i / us_p, 3),
+                             buffers_rotated=R))
+        del tiled
         torch.cuda.empty_cache()
-        def gemv_pairs(shapes):
-            """PoT and INT3 GEMV per shape, measured alternately, weight buffers rotating through HBM."""
-            rows_ = []
-            for (N, K) in shapes:
-                nbytes = workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
-                R = rotate(nbytes)
-                cs = [torch.randint(0, 256, (N, K * b3 // 8), dtype=torch.uint8, device=dev, generator=gen)
-                      for _ in range(R)]
-                sc_ = to_dev(workloads.pot_scales(workloads.seed_of(3, 0, 1), N, K, G))
-                S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(3, 0, 3), N, K, b3, G)
-                Sd_, Zd_ = to_dev(S_h), to_dev(Z_h)
-                x = to_dev(workloads.activations(workloads.seed_of(3, 0, 2), 1, K)[0])
-                y = torch.empty((N,), dtype=torch.float16, device=dev)
+    extras["pot_gemm_3bit_13b_shapes"] = gemm
+    del sc, Sd, Zd
+    torch.cuda.empty_cache()
 
-                def pot70():
-                    for c in cs:
-                        check(lib.pot_gemv(c.data_ptr(), sc_.data_ptr(), x.data_ptr(), y.data_ptr(), N, K, b3, G, 1,
-                                           stream))
-
-                def int70():
-                    for c in cs:
-                        check(lib.int_gemv(c.data_ptr(), Sd_.data_ptr(), Zd_.data_ptr(), x.data_ptr(), y.data_ptr(),
-                                           N, K, b3, G, 1, stream))
-
-                reps = max(2, 64 // R)
-                us_p, us_i = (t * 1e3 / R for t in _time_pair(torch, pot70, int70, reps, 1))
-                rows_.append({"shape": f"{N}x{K}", "us": round(us_p, 2), "GBps": round(nbytes / us_p / 1e3, 1),
-                              "pct_hbm_peak": round(nbytes / us_p / 1e3 / HBM_PEAK_GBPS * 100, 1),
-                              "int_us": round(us_i, 2), "pot_speedup_vs_int": round(us_i / us_p, 3),
-                              "buffers_rotated": R})
-                del cs
-                torch.cuda.empty_cache()
-            return rows_
-
-        g70 = gemv_pairs(((8192, 8192), (1024, 8192), (28672, 8192), (8192, 28672)))
-        big["gemv_3bit"] = g70
-        extras["llama2_70b_layer"] = big
-        # the vocabulary projection of a decoder (32000 or 128256 rows): the largest matrix of a decode step
-        extras["pot_gemv_3bit_vocabulary_projection"] = gemv_pairs(((32000, 4096), (128256, 4096), (128256, 8192)))
-
-        # fused MFMA GEMM, 3-bit, 13B shapes; the calls rotate through enough copies of the weight codes
-        # (random bytes are valid codes) that they are read from HBM, not from the 256 MB last-level cache
-        gemm = []
-        for i, (name, N, K) in enumerate(workloads.GEMM_13B_SHAPES):
-            codes_h, scales_h = workloads.pot_matrix(4, i, N, K, b3, G)
-            S_h, Z_h = workloads.int_scales_zeros(workloads.seed_of(4, i, 3), N, K, b3, G)
-            tiled = [potq.potq_repack(to_dev(codes_h), K, b3)]
-            R = max(2, int(640e6 // tiled[0].numel()) + 1)
-            for _ in range(1, R):
-                tiled.append(torch.randint(0, 256, tiled[0].shape, dtype=torch.uint8, device=dev, generator=gen))
-            sc, Sd, Zd = to_dev(scales_h), to_dev(S_h), to_dev(Z_h)
-            for M in workloads.GEMM_TOKENS:
-                X = to_dev(workloads.activations(workloads.seed_of(4, i, 2) + M, M, K))
-                Y = torch.empty((M, N), dtype=torch.float16, device=dev)
-                ws = potq.gemm_workspace(M, N, K, b3)
-                wp, wn = (ws.data_ptr(), ws.numel()) if ws is not None else (None, 0)
-                pas = [(t.data_ptr(), sc.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1, wp, wn, stream)
-                       for t in tiled]
-                ias = [(t.data_ptr(), Sd.data_ptr(), Zd.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1,
-                        wp, wn, stream) for t in tiled]
-
-                def pot_rot():
-                    turn[0] += 1
-                    check(lib.pot_gemm(*pas[turn[0] % R]))
-
-                def int_rot():
-                    turn[0] += 1
-                    check(lib.int_gemm(*ias[turn[0] % R]))
-
-                us_p, us_i = (t * 1e3 for t in _time_pair(torch, pot_rot, int_rot, 2 * R, 3))
-                tf = 2.0 * M * N * K / us_p / 1e6
-                gemm.append({"shape": f"{N}x{K}", "M": M, "us": round(us_p, 2), "TFLOPs": round(tf, 1),
-                             "pct_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 2),
-                             "GBps": round(workloads.algorithmic_bytes_gemm(M, N, K, b3, G) / us_p / 1e3, 1),
-                             "int_us": round(us_i, 2), "pot_speedup_vs_int": round(us_i / us_p, 3),
-                             "buffers_rotated": R})
-            del tiled
-            torch.cuda.empty_cache()
-        extras["pot_gemm_3bit_13b_shapes"] = gemm
-        del sc, Sd, Zd
-        torch.cuda.empty_cache()
-
-        # Step 1 scale search (Algorithm 1) on one 4096x4096 fp16 matrix, 3-bit, group 128: plain vector-ALU
-        # work, about eight lane operations per weight and multiplier (200 multipliers)
-        Wq = to_dev(workloads.weights_f16(workloads.seed_of(0, 0, 4), 4096, 4096))
-        qc = torch.empty((4096, 4096 * b3 // 8), dtype=torch.uint8, device=dev)
-        qs = torch.empty((4096, 4096 // G), dtype=torch.float16, device=dev)
-        qa = (Wq.data_ptr(), qc.data_ptr(), qs.data_ptr(), 4096, 4096, b3, G, stream)
-        ms_q = _time_steps(torch, lambda: check(lib.pot_quantize(*qa)), 10, 2)
-        lane_ops = 4096.0 * 4096 * 200 * 8
-        extras["pot_quantize_3bit_4096x4096"] = {
-            "ms": round(ms_q, 4), "Mweights_per_s": round(4096 * 4096 / ms_q / 1e3, 1),
-            "bound": "alu", "T_lane_ops_per_s": round(lane_ops / ms_q / 1e9, 2),
-            "pct_valu_peak_39.3T": round(lane_ops / ms_q / 1e9 / 39.3 * 100, 1)}
-        # Step 2 weight path (Sec. 3.3) on one 7B MLP matrix: streaming kernels, 4 bytes per weight each way
-        fN, fK = 11008, 4096
-        fW = to_dev(workloads.weights_f16(workloads.seed_of(0, 1, 4), fN, fK))
-        fS = to_dev(workloads.pot_scales(workloads.seed_of(0, 1, 1), fN, fK, G))
-        fG = torch.zeros((fN, fK // G), dtype=torch.float32, device=dev)
-        fdG = torch.empty_like(fG)
-        fD = to_dev(workloads.weights_f16(workloads.seed_of(0, 1, 5), fN, fK))
-        fO = torch.empty_like(fW)
-        fa = (fW.data_ptr(), fS.data_ptr(), fG.data_ptr(), fO.data_ptr(), fN, fK, b3, G, stream)
-        ba = (fW.data_ptr(), fS.data_ptr(), fG.data_ptr(), fD.data_ptr(), fdG.data_ptr(), fN, fK, b3, G, stream)
-        ms_f = _time_steps(torch, lambda: check(lib.pot_fakequant_forward(*fa)), 50, 5)
-        ms_b = _time_steps(torch, lambda: check(lib.pot_fakequant_backward(*ba)), 50, 5)
-        fbytes = fN * fK * 4 + fN * (fK // G) * 6
-        extras["pot_fakequant_3bit_11008x4096"] = {
-            "forward_us": round(ms_f * 1e3, 2), "forward_GBps": round(fbytes / ms_f / 1e6, 1),
-            "backward_us": round(ms_b * 1e3, 2), "backward_GBps": round((fbytes + fN * (fK // G) * 4) / ms_b / 1e6, 1),
-            "bound": "hbm", "note": "single buffer set (180 MB per pass: partly served by the 256 MB last-level cache)"}
-        result["extras"] = extras
+    # Step 1 scale search (Algorithm 1) on one 4096x4096 fp16 matrix, 3-bit, group 128: plain vector-ALU
+    # work, about eight lane operations per weight and multiplier (200 multipliers)
+    Wq = to_dev(workloads.weights_f16(workloads.seed_of(0, 0, 4), 4096, 4096))
+    qc = torch.empty((4096, 4096 * b3 // 8), dtype=torch.uint8, device=dev)
+    qs = torch.empty((4096, 4096 // G), dtype=torch.float16, device=dev)
+    qa = (Wq.data_ptr(), qc.data_ptr(), qs.data_ptr(), 4096, 4096, b3, G, stream)
+    ms_q = _time_steps(torch, lambda: check(lib.pot_quantize(*qa)), 10, 2)
+    lane_ops = 4096.0 * 4096 * 200 * 8
+    extras["pot_quantize_3bit_4096x4096"] = {
+        "ms": round(ms_q, 4), "Mweights_per_s": round(4096 * 4096 / ms_q / 1e3, 1),
+        "bound": "alu", "T_lane_ops_per_s": round(lane_ops / ms_q / 1e9, 2),
+        "frac": round(lane_ops / ms_q / 1e9 / 39.3, 4), "peak_T_lane_ops_per_s": 39.3}
+    # Step 2 weight path (Sec. 3.3) on one 7B MLP matrix: streaming kernels, 4 bytes per weight each way
+    fN, fK = 11008, 4096
+    fW = to_dev(workloads.weights_f16(workloads.seed_of(0, 1, 4), fN, fK))
+    fS = to_dev(workloads.pot_scales(workloads.seed_of(0, 1, 1), fN, fK, G))
+    fG = torch.zeros((fN, fK // G), dtype=torch.float32, device=dev)
+    fdG = torch.empty_like(fG)
+    fD = to_dev(workloads.weights_f16(workloads.seed_of(0, 1, 5), fN, fK))
+    fO = torch.empty_like(fW)
+    fa = (fW.data_ptr(), fS.data_ptr(), fG.data_ptr(), fO.data_ptr(), fN, fK, b3, G, stream)
+    ba = (fW.data_ptr(), fS.data_ptr(), fG.data_ptr(), fD.data_ptr(), fdG.data_ptr(), fN, fK, b3, G, stream)
+    ms_f = _time_steps(torch, lambda: check(lib.pot_fakequant_forward(*fa)), 50, 5)
+    ms_b = _time_steps(torch, lambda: check(lib.pot_fakequant_backward(*ba)), 50, 5)
+    fbytes = fN * fK * 4 + fN * (fK // G) * 6
+    extras["pot_fakequant_3bit_11008x4096"] = {
+        "forward": _hbm(fbytes, ms_f * 1e3), "backward": _hbm(fbytes + fN * (fK // G) * 4, ms_b * 1e3),
+        "note": "single buffer set (180 MB per pass: partly served by the 256 MB last-level cache)"}
+    result["extras"] = extras
 
     print(json.dumps(result))
     return 0

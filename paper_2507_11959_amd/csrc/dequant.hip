@@ -12,18 +12,36 @@
 
 namespace potq {
 
-#ifndef POTQ_DQ_NT
-#define POTQ_DQ_NT 1
-#endif
-// Shape of the launch by code width: octets (16-byte stores) per lane and threads per
-// workgroup.  Chosen by measurement with code buffers that are not resident in the
-// last-level cache (a rotating set of layers): three octets per lane and 1024 threads are
-// 8-12 % faster than two and 512 at 2 and 3 bits, and 12 % slower at 4 bits.
-#if defined(POTQ_DQ_OCTETS) && defined(POTQ_DQ_BLOCK)
-template <int BITS> struct DequantShape { static constexpr int octets = POTQ_DQ_OCTETS, block = POTQ_DQ_BLOCK; };
-#else
-template <int BITS> struct DequantShape { static constexpr int octets = (BITS == 4) ? 2 : 3, block = (BITS == 4) ? 512 : 1024; };
-#endif
+// Shape of the launch by code width: octets (16-byte stores) per lane, threads per workgroup,
+// and the order in which the workgroups take the 48 KB pieces of the output.  Chosen by
+// measurement on a 70B-sized layer with code buffers that are not resident in the last-level
+// cache: three octets per lane and 1024 threads are 4-10 % faster than any other pair tried
+// (one to seven octets, 256 to 1024 threads, runs of 8 to 64 lanes) at 2 and 3 bits, two and
+// 512 are at 4 bits.  Workgroups are dealt to the eight XCDs in turn (workgroup b runs on XCD
+// b % 8); at 3 bits it pays (76.9 -> 80.2 % of the HBM peak) to renumber them so that each XCD
+// takes runs of sixteen consecutive pieces, at 2 bits it costs 1 %.
+template <int BITS> struct DequantShape {
+    static constexpr int octets = (BITS == 4) ? 2 : 3;
+    static constexpr int block = (BITS == 4) ? 512 : 1024;
+    static constexpr int xcd_run = (BITS == 3) ? 16 : 0;     // 0: workgroups take the pieces in launch order
+};
+constexpr int kXcds = 8;
+
+// Piece of the output that workgroup `bid` of `nblocks` works on: a bijection of [0, nblocks).
+// Whole rounds of 8 * RUN workgroups are renumbered so that the workgroups of one XCD (equal
+// bid % 8) take RUN consecutive pieces; the incomplete last round keeps the launch order.
+template <int RUN>
+__device__ __forceinline__ int64_t xcd_piece(int64_t bid, int64_t nblocks)
+{
+    if constexpr (RUN == 0) {
+        return bid;
+    } else {
+        constexpr int64_t round = (int64_t)kXcds * RUN;
+        if (bid >= nblocks / round * round) return bid;
+        const int64_t in = bid % round;
+        return bid - in + (in % kXcds) * RUN + in / kXcds;
+    }
+}
 
 // 32 (bits=4), 24 (bits=3) or 16 (bits=2) code bits of octet `o`, from aligned 32-bit words.
 template <int BITS>
@@ -95,7 +113,7 @@ __device__ __forceinline__ u32x4 int_octet(uint32_t f, half2_t zm1024, half2_t s
     return out;
 }
 
-// The work of one workgroup: `block` indexes 256-thread slices of the matrix's octet stream.
+// The work of one workgroup: `block` indexes the workgroup-sized pieces of the matrix's octet stream.
 template <int BITS, bool IS_INT>
 __device__ __forceinline__ void dequant_block(const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales,
                                               const uint16_t *__restrict__ zeros, u32x4 *__restrict__ out,
@@ -127,11 +145,7 @@ __device__ __forceinline__ void dequant_block(const uint32_t *__restrict__ codes
             } else {
                 w = pot_octet<BITS>(f, s);
             }
-#if POTQ_DQ_NT
             __builtin_nontemporal_store(w, &out[o]);   // the output is not read again by this pass
-#else
-            out[o] = w;
-#endif
         }
     }
 }
@@ -141,7 +155,8 @@ __global__ __launch_bounds__(DequantShape<BITS>::block) void dequant_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales,
     const uint16_t *__restrict__ zeros, u32x4 *__restrict__ out, int64_t n_octets, int group_shift)
 {
-    dequant_block<BITS, IS_INT>(codes, scales, zeros, out, n_octets, group_shift, blockIdx.x);
+    dequant_block<BITS, IS_INT>(codes, scales, zeros, out, n_octets, group_shift,
+                                xcd_piece<DequantShape<BITS>::xcd_run>(blockIdx.x, gridDim.x));
 }
 
 // Several matrices in one launch: every launch costs a fixed ramp-up and drain
@@ -161,10 +176,12 @@ struct DequantBatch {
 template <int BITS, bool IS_INT>
 __global__ __launch_bounds__(DequantShape<BITS>::block) void dequant_batch_kernel(const DequantBatch batch, int group_shift)
 {
+    // the pieces of all matrices form one sequence, renumbered as a whole
+    const uint32_t piece = (uint32_t)xcd_piece<DequantShape<BITS>::xcd_run>(blockIdx.x, gridDim.x);
     int i = 0;
-    while (i + 1 < batch.count && blockIdx.x >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
+    while (i + 1 < batch.count && piece >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
     dequant_block<BITS, IS_INT>(batch.codes[i], batch.scales[i], batch.zeros[i], batch.out[i], batch.n_octets[i],
-                                group_shift, blockIdx.x - batch.first_block[i]);
+                                group_shift, piece - batch.first_block[i]);
 }
 
 static int dequant_block_threads(int bits) { return bits == 4 ? DequantShape<4>::block : DequantShape<2>::block; }
