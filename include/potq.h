@@ -12,8 +12,12 @@
  * ---------------------------------
  *  - All data pointers are DEVICE pointers (HIP global memory) unless a
  *    parameter name ends in `_host`.  The caller owns every buffer; the library
- *    never allocates, frees or keeps device memory and has no mutable global
- *    state, so calls are re-entrant.
+ *    never allocates, frees or keeps device memory.  Its only state that
+ *    outlives a call is a set of process-wide flags and addresses that are set
+ *    once per device and never change afterwards (the raised on-chip memory
+ *    limit of the kernels that need it, the address of pot_gemm_noalloc's
+ *    built-in buffer); they are atomics, so calls are re-entrant and may come
+ *    from several host threads.
  *  - `hip_stream` is a `hipStream_t` passed as `void*` (NULL = the null stream).
  *    Every call only enqueues work on that stream and returns; nothing
  *    synchronises.
@@ -142,8 +146,8 @@ int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits,
                 int to_layout, void *hip_stream);
 
 /*
- * pot_gemv -- fused de-quantise + matrix-vector product, batch-1 decode
- * (the consumer of Sec. 4.2's weights: "dequantizing back to FP16 for GEMM", Sec. 1):
+ * pot_gemv -- fused de-quantise + matrix-vector product, batch-1 decode (the
+ * consumer of Sec. 4.2's weights: Sec. 1 de-quantises to fp16 for the GEMM):
  *   y[n] = fp16( sum_k W~[n,k] * x[k] ),  W~ as defined by pot_dequant,
  * products exact, accumulation in fp32, one rounding to fp16 at the end.
  *   x_f16 in  K fp16;   y_f16 out  N fp16
@@ -205,7 +209,8 @@ int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f1
                    int bits, int group, int layout, void *hip_stream);
 
 /*
- * pot_gemm -- fused de-quantise + GEMM on the matrix cores:
+ * pot_gemm -- fused de-quantise + GEMM on the matrix cores (Sec. 1: the weights
+ * are de-quantised to fp16 for the GEMM that consumes them; W~ is Sec. 4.2's):
  *   Y[m,n] = fp16( sum_k X[m,k] * W~[n,k] ),   X: M x K fp16 row-major,
  *   Y: M x N fp16 row-major (Y = X . W~^T, the nn.Linear convention).
  * fp16 MFMA with fp32 accumulation (up to four tokens on large 2-/3-bit PoT
@@ -222,6 +227,8 @@ int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f1
  * workgroups and the workspace is never touched (the size query returns 0).
  * The workspace may be reused by the next call on the
  * same stream; concurrent calls on different streams need separate workspaces.
+ * The size query returns 0 for a shape pot_gemm would refuse (bits, K % 128,
+ * N % 16, negative sizes); today the size depends on M and N only.
  */
 size_t potq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
 

@@ -18,15 +18,20 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "potq_oracle.c")
-_LIB = os.path.join(_HERE, "libpotq_oracle.so")
+# POTQ_ORACLE_SANITIZE=1 in the environment: the same source built with the undefined-behaviour
+# sanitizer (every finding aborts), kept beside the plain build; the CPU test suite re-runs the
+# oracle's pins under it (tests/test_oracle_sanitizers.py)
+_SANITIZE = os.environ.get("POTQ_ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "libpotq_oracle_ubsan.so" if _SANITIZE else "libpotq_oracle.so")
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP over rows only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        extra = ["-g", "-fsanitize=undefined", "-fno-sanitize-recover=all"] if _SANITIZE else []
         subprocess.check_call(
-            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC,
-             "-lm"]
+            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", *extra,
+             "-o", _LIB, _SRC, "-lm"]
         )
     return _LIB
 

@@ -106,11 +106,26 @@ def _shape_codes(codes: torch.Tensor, K: int, bits: int) -> int:
     return n_bytes // rb
 
 
+def _per_group(t: torch.Tensor, N: int, K: int, group: int, name: str) -> None:
+    """One value per (row, group): a wrong group size or a short tensor must not reach the kernels."""
+    if group not in (64, 128):
+        raise ValueError("group must be 64 or 128")
+    if t.numel() != N * (K // group):
+        raise ValueError(f"{name} must hold N*(K/group) = {N * (K // group)} values, got {t.numel()}")
+
+
+def _numel(t: torch.Tensor, n: int, name: str) -> None:
+    if t.numel() != n:
+        raise ValueError(f"{name} must hold {n} values, got {t.numel()}")
+
+
 def pot_dequant(codes, scales, K: int, bits: int, group: int = 128, out=None):
     """codes: uint8 (N, K*bits/8) canonical; scales: fp16 (N, K/group) -> fp16 (N, K)."""
     N = _shape_codes(codes, K, bits)
+    _per_group(scales, N, K, group, "scales")
     if out is None:
         out = torch.empty((N, K), dtype=torch.float16, device=codes.device)
+    _numel(out, N * K, "out")
     _ok(_lib.pot_dequant(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                          _dev(out, torch.float16, "out"), N, K, bits, group, _stream()))
     return out
@@ -118,8 +133,11 @@ def pot_dequant(codes, scales, K: int, bits: int, group: int = 128, out=None):
 
 def int_dequant(codes, scales, zeros, K: int, bits: int, group: int = 128, out=None):
     N = _shape_codes(codes, K, bits)
+    _per_group(scales, N, K, group, "scales")
+    _per_group(zeros, N, K, group, "zeros")
     if out is None:
         out = torch.empty((N, K), dtype=torch.float16, device=codes.device)
+    _numel(out, N * K, "out")
     _ok(_lib.int_dequant(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                          _dev(zeros, torch.float16, "zeros"), _dev(out, torch.float16, "out"),
                          N, K, bits, group, _stream()))
@@ -134,13 +152,17 @@ class DequantItem(ctypes.Structure):
     _fields_ = [("codes", _vp), ("scales", _vp), ("zeros", _vp), ("out_f16", _vp), ("N", _i64), ("K", _i64)]
 
 
-def make_batch(mats, is_int: bool = False):
+def make_batch(mats, is_int: bool = False, group: int = 128):
     """mats: list of (codes, scales, zeros-or-None, out, K, bits) device tensors -> ctypes descriptor array.
 
     The returned array only holds raw pointers: keep the tensors alive while it is in use."""
     arr = (DequantItem * len(mats))()
     for i, (codes, scales, zeros, out, K, bits) in enumerate(mats):
         N = _shape_codes(codes, K, bits)
+        _per_group(scales, N, K, group, "scales")
+        if is_int:
+            _per_group(zeros, N, K, group, "zeros")
+        _numel(out, N * K, "out")
         arr[i].codes = _dev(codes, torch.uint8, "codes")
         arr[i].scales = _dev(scales, torch.float16, "scales")
         arr[i].zeros = _dev(zeros, torch.float16, "zeros") if is_int else None
@@ -151,13 +173,13 @@ def make_batch(mats, is_int: bool = False):
 
 def pot_dequant_batch(mats, bits: int, group: int = 128):
     """mats: list of (codes, scales, out, K); one launch for all of them."""
-    arr = make_batch([(c, s, None, o, K, bits) for (c, s, o, K) in mats])
+    arr = make_batch([(c, s, None, o, K, bits) for (c, s, o, K) in mats], group=group)
     _ok(_lib.pot_dequant_batch(arr, len(mats), bits, group, _stream()))
 
 
 def int_dequant_batch(mats, bits: int, group: int = 128):
     """mats: list of (codes, scales, zeros, out, K); one launch for all of them."""
-    arr = make_batch([(c, s, z, o, K, bits) for (c, s, z, o, K) in mats], is_int=True)
+    arr = make_batch([(c, s, z, o, K, bits) for (c, s, z, o, K) in mats], is_int=True, group=group)
     _ok(_lib.int_dequant_batch(arr, len(mats), bits, group, _stream()))
 
 
@@ -165,6 +187,7 @@ def potq_repack(src, K: int, bits: int, to_layout: int = LAYOUT_TILE16, out=None
     N = _shape_codes(src, K, bits)
     if out is None:
         out = torch.empty_like(src)
+    _numel(out, src.numel(), "dst")
     _ok(_lib.potq_repack(_dev(src, torch.uint8, "src"), _dev(out, torch.uint8, "dst"), N, K, bits, to_layout,
                          _stream()))
     return out
@@ -174,8 +197,10 @@ def pot_gemv(codes, scales, x, K: int, bits: int, group: int = 128, layout: int 
     N = _shape_codes(codes, K, bits)
     if x.numel() != K:
         raise ValueError("x must have K elements")
+    _per_group(scales, N, K, group, "scales")
     if out is None:
         out = torch.empty((N,), dtype=torch.float16, device=codes.device)
+    _numel(out, N, "y")
     _ok(_lib.pot_gemv(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                       _dev(x, torch.float16, "x"), _dev(out, torch.float16, "y"), N, K, bits, group, layout,
                       _stream()))
@@ -186,8 +211,11 @@ def int_gemv(codes, scales, zeros, x, K: int, bits: int, group: int = 128, layou
     N = _shape_codes(codes, K, bits)
     if x.numel() != K:
         raise ValueError("x must have K elements")
+    _per_group(scales, N, K, group, "scales")
+    _per_group(zeros, N, K, group, "zeros")
     if out is None:
         out = torch.empty((N,), dtype=torch.float16, device=codes.device)
+    _numel(out, N, "y")
     _ok(_lib.int_gemv(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                       _dev(zeros, torch.float16, "zeros"), _dev(x, torch.float16, "x"),
                       _dev(out, torch.float16, "y"), N, K, bits, group, layout, _stream()))
@@ -211,10 +239,15 @@ class GemvItem(ctypes.Structure):
     _fields_ = [("codes", _vp), ("scales", _vp), ("zeros", _vp), ("y_f16", _vp), ("N", _i64)]
 
 
-def make_gemv_batch(mats, K: int, bits: int, is_int: bool = False):
+def make_gemv_batch(mats, K: int, bits: int, is_int: bool = False, group: int = 128):
     """mats: list of (codes, scales, zeros-or-None, y) device tensors -> ctypes descriptor array (raw pointers)."""
     arr = (GemvItem * len(mats))()
     for i, (codes, scales, zeros, y) in enumerate(mats):
+        N = _shape_codes(codes, K, bits)
+        _per_group(scales, N, K, group, "scales")
+        if is_int:
+            _per_group(zeros, N, K, group, "zeros")
+        _numel(y, N, "y")
         arr[i].codes = _dev(codes, torch.uint8, "codes")
         arr[i].scales = _dev(scales, torch.float16, "scales")
         arr[i].zeros = _dev(zeros, torch.float16, "zeros") if is_int else None
@@ -231,7 +264,9 @@ def potq_gemv_exponent_form(N: int, K: int, bits: int) -> bool:
 def pot_gemv_batch(mats, x, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16):
     """mats: list of (codes, scales) sharing x; -> list of y tensors, one launch."""
     ys = [torch.empty((_shape_codes(c, K, bits),), dtype=torch.float16, device=c.device) for (c, s) in mats]
-    arr = make_gemv_batch([(c, s, None, y) for (c, s), y in zip(mats, ys)], K, bits)
+    if x.numel() != K:
+        raise ValueError("x must have K elements")
+    arr = make_gemv_batch([(c, s, None, y) for (c, s), y in zip(mats, ys)], K, bits, group=group)
     _ok(_lib.pot_gemv_batch(arr, len(mats), _dev(x, torch.float16, "x"), K, bits, group, layout, _stream()))
     return ys
 
@@ -239,7 +274,9 @@ def pot_gemv_batch(mats, x, K: int, bits: int, group: int = 128, layout: int = L
 def int_gemv_batch(mats, x, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16):
     """mats: list of (codes, scales, zeros) sharing x; -> list of y tensors, one launch."""
     ys = [torch.empty((_shape_codes(c, K, bits),), dtype=torch.float16, device=c.device) for (c, s, z) in mats]
-    arr = make_gemv_batch([(c, s, z, y) for (c, s, z), y in zip(mats, ys)], K, bits, is_int=True)
+    if x.numel() != K:
+        raise ValueError("x must have K elements")
+    arr = make_gemv_batch([(c, s, z, y) for (c, s, z), y in zip(mats, ys)], K, bits, is_int=True, group=group)
     _ok(_lib.int_gemv_batch(arr, len(mats), _dev(x, torch.float16, "x"), K, bits, group, layout, _stream()))
     return ys
 
@@ -250,8 +287,10 @@ def pot_gemm(codes, scales, X, K: int, bits: int, group: int = 128, layout: int 
     if X.dim() != 2 or X.shape[1] != K:
         raise ValueError("X must be (M, K)")
     M = X.shape[0]
+    _per_group(scales, N, K, group, "scales")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=codes.device)
+    _numel(out, M * N, "Y")
     wp, wn = _ws(workspace)
     _ok(_lib.pot_gemm(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                       _dev(X, torch.float16, "X"), _dev(out, torch.float16, "Y"), M, N, K, bits, group, layout,
@@ -267,6 +306,7 @@ def pot_gemm_noalloc(codes, scales, X, out, K: int, bits: int, group: int = 128,
     M = X.shape[0]
     if tuple(out.shape) != (M, N):
         raise ValueError("out must be (M, N)")
+    _per_group(scales, N, K, group, "scales")
     _ok(_lib.pot_gemm_noalloc(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                               _dev(X, torch.float16, "X"), _dev(out, torch.float16, "Y"), M, N, K, bits, group,
                               layout, _stream()))
@@ -279,8 +319,11 @@ def int_gemm(codes, scales, zeros, X, K: int, bits: int, group: int = 128, layou
     if X.dim() != 2 or X.shape[1] != K:
         raise ValueError("X must be (M, K)")
     M = X.shape[0]
+    _per_group(scales, N, K, group, "scales")
+    _per_group(zeros, N, K, group, "zeros")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=codes.device)
+    _numel(out, M * N, "Y")
     wp, wn = _ws(workspace)
     _ok(_lib.int_gemm(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.float16, "scales"),
                       _dev(zeros, torch.float16, "zeros"), _dev(X, torch.float16, "X"),

@@ -290,9 +290,8 @@ int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f1
 
 size_t potq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits)
 {
-    (void)K;
-    (void)bits;
-    if (M <= 0 || N <= 0) return 0;
+    if (M <= 0 || N <= 0 || M > kMaxDim) return 0;
+    if (check_common(N, K, bits, 128, true) != POTQ_OK || N % 16 != 0) return 0;     // a shape pot_gemm refuses
     return potq::gemm_workspace_bytes(M, N);
 }
 

@@ -27,15 +27,11 @@
 
 namespace potq {
 
-#ifndef POTQ_GEMM_XS_LIMIT
-#define POTQ_GEMM_XS_LIMIT 99
-#endif
-#ifndef POTQ_GEMM_WPE
-#define POTQ_GEMM_WPE 2
-#endif
+// wavefronts per SIMD the register allocator is asked to make room for in the 16-fragment tiles
+constexpr int kGemmWavesPerSimd = 2;
 
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC, int KS>
-__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu((RM * CN == 16) ? POTQ_GEMM_WPE : 1, 8)))
+__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu((RM * CN == 16) ? kGemmWavesPerSimd : 1, 8)))
 void gemm_tile16_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
     const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, float *__restrict__ partial, int M, int64_t N, int K,
@@ -122,7 +118,7 @@ void gemm_tile16_kernel(
     // zero afterwards) and every iteration issues the same loads in the same order.
     constexpr bool kAlignedChunks = (GC % 4 == 0);     // chunks start on multiples of four groups (see launch)
     // register stages of X (the LDS buffer is one more stage); the big tiles keep one to stay at two wavefronts per SIMD
-    constexpr int kXStages = (PPT <= 4 && RM * CN < POTQ_GEMM_XS_LIMIT) ? 2 : 1;
+    constexpr int kXStages = PPT <= 4 ? 2 : 1;
     uint32_t wr[2][GC][RM][BITS], sr[2][GC][RM], zr[2][GC][RM];
     u32x4 xreg[kXStages][PPT];
     uint32_t xmask[PPT];
@@ -289,12 +285,8 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4_t *__rest
     *(half4_t *)(Y + 4 * i) = h;
 }
 
-#ifndef POTQ_GEMM_TARGET_WGS
-#define POTQ_GEMM_TARGET_WGS 768
-#endif
-#ifndef POTQ_GEMM_MIN_GROUPS
-#define POTQ_GEMM_MIN_GROUPS 4
-#endif
+constexpr int64_t kSplitTargetWorkgroups = 768;   // four-wavefront workgroups' worth of wavefronts a split aims at
+constexpr int64_t kSplitMinGroups = 4;            // scale groups a K split keeps at least
 
 constexpr int64_t kBigSplitBelow = 120, kBigSplitTarget = 160;
 
@@ -306,12 +298,12 @@ static int choose_splits(int64_t workgroups, int waves, int ks, int64_t G, int64
     // the many-token configurations move M*N*4 bytes per split through the workspace: split only when
     // fewer than about half of the CUs would have a workgroup (of eight wavefronts), and then just
     // enough for 160 workgroups (more splits measured slower: 40.3 us with 8 against 30.0 us with 4
-    // on 5120 x 5120 at 256 tokens); the others aim at POTQ_GEMM_TARGET_WGS four-wavefront
+    // on 5120 x 5120 at 256 tokens); the others aim at kSplitTargetWorkgroups four-wavefront
     // workgroups' worth of wavefronts
     const int64_t units = workgroups * waves / 4;
     int64_t want = big ? (workgroups < kBigSplitBelow ? (kBigSplitTarget + workgroups - 1) / workgroups : 1)
-                       : (POTQ_GEMM_TARGET_WGS + units - 1) / units;
-    if (want > G / (POTQ_GEMM_MIN_GROUPS * ks)) want = G / (POTQ_GEMM_MIN_GROUPS * ks);
+                       : (kSplitTargetWorkgroups + units - 1) / units;
+    if (want > G / (kSplitMinGroups * ks)) want = G / (kSplitMinGroups * ks);
     if (want > 16) want = 16;
     const int64_t fit = (int64_t)(workspace_bytes / ((size_t)M * (size_t)N * sizeof(float)));
     if (want > fit) want = fit;
@@ -464,9 +456,6 @@ hipError_t run_gemm_fewtok(bool is_int, const void *codes, const void *scales, c
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 
 bool gemv_multi_ok(int64_t M, int64_t N, int64_t K, int group);
-#ifndef POTQ_GEMV_EXP_MULTI
-#define POTQ_GEMV_EXP_MULTI 1                         // 0: build without the multi-vector exponent form (for A/B timing)
-#endif
 bool gemv_exp_multi_ok(int64_t M, int64_t N, int64_t K, int bits, int group);
 hipError_t run_gemv_exp_multi(const void *codes, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
                               int64_t K, int bits, hipStream_t stream);
@@ -485,7 +474,7 @@ hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, c
     if (M == 1 && gemv_lds_bytes(K) <= kLdsPerWorkgroup)
         return run_gemv_tile16(is_int, codes, scales, zeros, X, Y, N, K, bits, group, stream);
     // two to four tokens on a large PoT matrix: the exponent form of the GEMV with one MFMA per vector and step
-    if (POTQ_GEMV_EXP_MULTI && !is_int && gemv_exp_multi_ok(M, N, K, bits, group))
+    if (!is_int && gemv_exp_multi_ok(M, N, K, bits, group))
         return run_gemv_exp_multi(codes, scales, X, Y, M, N, K, bits, stream);
     // two to four tokens: the GEMV kernel with one activation vector per result column
     if (gemv_multi_ok(M, N, K, group)) return run_gemv_multi(is_int, codes, scales, zeros, X, Y, M, N, K, bits, stream);

@@ -66,10 +66,7 @@ __device__ __forceinline__ void gemv_group(const u32x4 (&L)[BITS], uint32_t s, u
 }
 
 constexpr int kXRun = 17;   // uint4 per scale group of x in LDS (16 + 1 of padding)
-#ifndef POTQ_GEMV_WAVES
-#define POTQ_GEMV_WAVES 8
-#endif
-constexpr int kGemvWaves = POTQ_GEMV_WAVES;
+constexpr int kGemvWaves = 8;
 
 // A workgroup of 8 wavefronts stages x in LDS once and serves 8/S row tiles of 16
 // rows.  S wavefronts share a tile and split its scale groups: wavefront part p,
@@ -666,15 +663,8 @@ static int gemv_split(int64_t G)
     return split;
 }
 
-#ifndef POTQ_GEMV_WALK
-#define POTQ_GEMV_WALK 1
-#endif
-#ifndef POTQ_GEMV_WALK_GROUPS
-#define POTQ_GEMV_WALK_GROUPS 512                     // two resident workgroups per compute unit
-#endif
-#ifndef POTQ_GEMV_WALK_MIN_WEIGHTS
-#define POTQ_GEMV_WALK_MIN_WEIGHTS (256ll << 20)
-#endif
+constexpr int64_t kWalkGroups = 512;                  // two resident workgroups per compute unit
+constexpr int64_t kWalkMinWeights = 256ll << 20;
 
 static size_t gemv_walk_lds_bytes(int64_t K)
 {
@@ -688,7 +678,7 @@ static size_t gemv_walk_lds_bytes(int64_t K)
 // or slower (17920 x 6656, INT3: 15.3 -> 16.5 us), so it only takes the vocabulary-sized ones.
 static bool gemv_walk_ok(int64_t N, int64_t K)
 {
-    return POTQ_GEMV_WALK && kGemvWaves == 8 && K / kTileCols >= 32 && N * K >= POTQ_GEMV_WALK_MIN_WEIGHTS &&
+    return kGemvWaves == 8 && K / kTileCols >= 32 && N * K >= kWalkMinWeights &&
            gemv_walk_lds_bytes(K) <= kLdsPerWorkgroup;
 }
 
@@ -698,7 +688,7 @@ static hipError_t launch_gemv_walk(const void *codes, const void *scales, const 
 {
     const int64_t rowtiles = N / kTileRows;
     const size_t lds = gemv_walk_lds_bytes(K);
-    const int64_t cap = POTQ_GEMV_WALK_GROUPS;
+    const int64_t cap = kWalkGroups;
     const int64_t per_group = (rowtiles + cap - 1) / cap;
     const dim3 grid((unsigned)((rowtiles + per_group - 1) / per_group)), block(kGemvWaves * kWave);
 #define POTQ_LAUNCH_WALK(G64, COL0)                                                                               \
@@ -797,16 +787,13 @@ hipError_t run_gemv_exp(const void *codes, const void *scales, const void *x, vo
                         int group, hipStream_t stream);
 hipError_t run_gemv_exp_batch(int count, const void *const *codes, const void *const *scales, void *const *y,
                               const int64_t *N, const void *x, int64_t K, int bits, int group, hipStream_t stream);
-#ifndef POTQ_GEMV_EXP
-#define POTQ_GEMV_EXP 1
-#endif
 
 // `count` non-empty matrices (count <= kMaxGemvBatch), validated by the caller; all share x, K, bits, group.
 hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *codes, const void *const *scales,
                                  const void *const *zeros, void *const *y, const int64_t *N, const void *x,
                                  int64_t K, int bits, int group, hipStream_t stream)
 {
-    if (POTQ_GEMV_EXP && !is_int) {
+    if (!is_int) {
         int64_t rows = 0;
         for (int i = 0; i < count; ++i) rows += N[i];
         if (gemv_exp_batch_ok(count, rows, K, bits))
@@ -846,7 +833,7 @@ hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, c
                            void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream)
 {
     // large PoT matrices at 2 and 3 bits: the exponent form (scale applied per group, integer inner sums)
-    if (POTQ_GEMV_EXP && !is_int && gemv_exp_ok(N, K, bits)) return run_gemv_exp(codes, scales, x, y, N, K, bits, group, stream);
+    if (!is_int && gemv_exp_ok(N, K, bits)) return run_gemv_exp(codes, scales, x, y, N, K, bits, group, stream);
     if (is_int) {
         if (bits == 4) return launch_gemv<4, true>(codes, scales, zeros, x, y, N, K, group, stream);
         else if (bits == 3) return launch_gemv<3, true>(codes, scales, zeros, x, y, N, K, group, stream);

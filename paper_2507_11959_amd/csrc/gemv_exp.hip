@@ -632,16 +632,11 @@ static size_t exp_lds_bytes(int64_t K, int waves)
            (size_t)waves * sizeof(uint32_t);
 }
 
-#ifndef POTQ_EXP_GROUPS
-#define POTQ_EXP_GROUPS 512
-#endif
-#ifndef POTQ_EXP_MIN_WEIGHTS
-#define POTQ_EXP_MIN_WEIGHTS (60ll << 20)
-#endif
 // Workgroups per launch: what the chip holds at once (two per compute unit at this register
 // and LDS footprint), each with an equal share of the row tiles, so that x is staged as few
 // times as possible and nobody waits for a second wave of workgroups.
-constexpr int kExpGroups = POTQ_EXP_GROUPS;
+constexpr int kExpGroups = 512;
+constexpr int64_t kExpMinWeights = 60ll << 20;
 constexpr size_t kExpLdsSmall = kLdsDefaultLimit, kExpLdsLarge = kLdsPerWorkgroup;
 
 // Wavefronts per workgroup.  A single matrix always takes sixteen (two tiles at a time, one
@@ -661,7 +656,7 @@ bool gemv_exp_ok(int64_t N, int64_t K, int bits)
 {
     const int64_t G = K / kTileCols;
     if (bits != 2 && bits != 3) return false;
-    if (G < 32 || N * K < POTQ_EXP_MIN_WEIGHTS) return false;
+    if (G < 32 || N * K < kExpMinWeights) return false;
     // (the eight-wavefront variant is only used where its footprint is smaller still)
     if (K > (int64_t)kExpOctetsPerThread * 16 * kWave * 8) return false;
     return exp_lds_bytes(K, 16) <= kExpLdsLarge;

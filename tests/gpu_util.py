@@ -43,3 +43,26 @@ def rel_err(y_bits: np.ndarray, ref_bits: np.ndarray, K: int):
     err = np.abs(y - r) / den
     normwise = np.abs(y - r).max() / max(np.abs(r).max(), 1e-300) if r.size else 0.0
     return (err.max() if r.size else 0.0), normwise, int((np.abs(r) < floor).sum())
+
+
+GUARD_BYTES = 4096
+GUARD_PATTERN = 0xA5
+
+
+class Guarded:
+    """An output tensor with a band of GUARD_BYTES pattern bytes on either side in the same allocation:
+    an entry point that writes outside the tensor it was given changes a band."""
+
+    def __init__(self, shape, dtype, fill=None):
+        n = int(np.prod(shape)) * torch.empty((), dtype=dtype).element_size()
+        pad = (-n) % 16
+        self.raw = torch.full((GUARD_BYTES + n + pad + GUARD_BYTES,), GUARD_PATTERN, dtype=torch.uint8, device=DEV)
+        self.nbytes = n
+        self.tensor = self.raw[GUARD_BYTES:GUARD_BYTES + n].view(dtype).reshape(shape)
+        if fill is not None:
+            self.tensor.fill_(fill)
+
+    def intact(self) -> bool:
+        lo = self.raw[:GUARD_BYTES]
+        hi = self.raw[GUARD_BYTES + self.nbytes:]
+        return bool((lo == GUARD_PATTERN).all()) and bool((hi == GUARD_PATTERN).all())

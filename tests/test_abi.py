@@ -92,6 +92,8 @@ def test_host_side_validation(lib):
     assert lib.potq_gemm_workspace_bytes(256, 13824, 5120, 3) == 0      # enough output tiles: no split
     assert lib.potq_gemm_workspace_bytes(256, 4096, 4096, 3) == 5 * 256 * 4096 * 4   # 64 tiles of 128x128
     assert lib.potq_gemm_workspace_bytes(0, 4096, 4096, 3) == 0
+    assert lib.potq_gemm_workspace_bytes(32, 4096, 4100, 3) == 0          # shapes pot_gemm refuses need nothing
+    assert lib.potq_gemm_workspace_bytes(32, 4096, 4096, 5) == 0 and lib.potq_gemm_workspace_bytes(32, 4100, 4096, 3) == 0
     # the exponent form of the GEMV: large 2- and 3-bit matrices with at least 32 groups per row
     assert lib.potq_gemv_exponent_form(28672, 8192, 3) == 1 and lib.potq_gemv_exponent_form(8192, 28672, 2) == 1
     assert lib.potq_gemv_exponent_form(4096, 4096, 3) == 0        # too small for the conversion of x to pay
@@ -138,3 +140,32 @@ def test_build_step_loads_without_the_built_library():
             "assert m.LIB_PATH.endswith('libpotq.so') and callable(m.build); "
             "assert not any(k.startswith('paper_2507_11959_amd') for k in sys.modules)")
     subprocess.run([sys.executable, "-c", code], check=True, cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+def test_binding_rejects_mismatched_shapes_before_any_launch():
+    """A wrong group size or a short scale / output tensor is a ValueError in the binding, never an
+    out-of-bounds access on the device (host tensors suffice: the checks come before any pointer is taken)."""
+    import torch
+    from paper_2507_11959_amd import binding
+    N, K, bits = 16, 256, 3
+    codes = torch.zeros((N, K * bits // 8), dtype=torch.uint8)
+    scales128 = torch.zeros((N, K // 128), dtype=torch.float16)
+    x = torch.zeros((K,), dtype=torch.float16)
+    with pytest.raises(ValueError, match="scales"):
+        binding.pot_dequant(codes, scales128, K, bits, group=64)
+    with pytest.raises(ValueError, match="out"):
+        binding.pot_dequant(codes, scales128, K, bits, out=torch.zeros((N, K // 2), dtype=torch.float16))
+    with pytest.raises(ValueError, match="zeros"):
+        binding.int_dequant(codes, scales128, scales128[:, :1], K, bits)
+    with pytest.raises(ValueError, match="scales"):
+        binding.pot_gemv(codes, scales128[:8], x, K, bits)
+    with pytest.raises(ValueError, match="y"):
+        binding.pot_gemv(codes, scales128, x, K, bits, out=torch.zeros((N // 2,), dtype=torch.float16))
+    with pytest.raises(ValueError, match="scales"):
+        binding.pot_gemm(codes, scales128, x[None, :], K, bits, group=64)
+    with pytest.raises(ValueError, match="Y"):
+        binding.pot_gemm(codes, scales128, x[None, :], K, bits, out=torch.zeros((1, N + 16), dtype=torch.float16))
+    with pytest.raises(ValueError, match="scales"):
+        binding.make_batch([(codes, scales128, None, torch.zeros((N, K), dtype=torch.float16), K, bits)], group=64)
+    with pytest.raises(ValueError, match="group"):
+        binding.pot_dequant(codes, scales128, K, bits, group=32)

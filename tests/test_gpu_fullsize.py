@@ -201,6 +201,31 @@ def test_gemv_vocabulary_sized_matrices_sampled_rows(potq, N, K, bits, group, is
     assert bool(torch.isfinite(y).all())
 
 
+@pytest.mark.parametrize("N,K,bits", [(32000, 4096, 3), (128256, 4096, 3), (128256, 8192, 3), (128256, 8192, 2)])
+def test_pot_gemv_vocabulary_projections_exponent_form_sampled_rows(potq, N, K, bits):
+    """The vocabulary projections bench.py times (PoT, exponent form: a grid of resident workgroups, each
+    walking every grid-th pair of row tiles).  Sampled against the oracle: every row of the tile pairs on
+    either side of each multiple of the grid size (where a workgroup moves on to its next pair, for grids of
+    250 to 256 workgroups), of the first and the last pairs (the last one is the ragged end), and 1500 random rows."""
+    assert potq.potq_gemv_exponent_form(N, K, bits)
+    rng = np.random.default_rng(N + K + bits)
+    packed, S = workloads.pot_matrix(8, 10 + bits, N, K, bits, G)
+    x = workloads.activations(workloads.seed_of(8, 10 + bits, 2), 1, K)
+    y = potq.pot_gemv(potq.potq_repack(dev(packed), K, bits), dev(S), dev(x[0]), K, bits, G)
+    pairs = (N // 16 + 1) // 2                                    # tile pairs (32 rows each)
+    edge = {0, 1, pairs - 2, pairs - 1}
+    for grid in range(250, 257):
+        for k in range(1, 4):
+            edge.update({k * grid - 1, k * grid, k * grid + 1})
+        edge.update({(pairs // grid) * grid - 1, (pairs // grid) * grid})
+    edge_rows = np.concatenate([np.arange(32 * p, min(32 * p + 32, N)) for p in sorted(edge) if 0 <= p < pairs])
+    rows = np.unique(np.concatenate([edge_rows, rng.integers(0, N, 1500)]))
+    want = oracle.gemm(packed[rows], S[rows], None, x, K, bits, G, nthreads=_threads())[0]
+    e, nw, nfloor = rel_err(host_bits(y[torch.from_numpy(rows).to("cuda:0")]), want, K)
+    assert e <= REL_TOL, (N, K, bits, e, nw, nfloor)
+    assert bool(torch.isfinite(y).all())
+
+
 @pytest.mark.parametrize("bits", [2, 3])
 def test_second_workload_llama30b_layer(potq, bits):
     """LLaMA-30B-shaped layer: batched dequant (sampled rows + invariants) and the q/k/v and gate/up

@@ -51,7 +51,7 @@ def test_two_level_group_is_reproduced_exactly():
 @pytest.mark.parametrize("bits,group", [(2, 128), (3, 128), (3, 64), (4, 128)])
 def test_against_the_literal_formula_in_float64(bits, group):
     qmax = 2 ** (bits - 1) - 1
-    N, K = 6, 512
+    N, K = 48, 1024
     W = workloads.weights_f16(42 + bits + group, N, K)
     codes, scales, idx = oracle.pot_quantize(W, bits, group, want_index=True)
     W64 = W.astype(np.float64).reshape(N, K // group, group)
@@ -67,8 +67,11 @@ def test_against_the_literal_formula_in_float64(bits, group):
     chosen = np.take_along_axis(Q, (idx - 1)[..., None], axis=2)[..., 0]
     # the oracle's choice is optimal up to binary32 rounding of the error sums
     assert np.all(chosen <= qmin * (1 + 1e-5))
-    # and in nearly all groups it is the very same index
-    assert (np.argmin(Q, axis=2) + 1 == idx).mean() > 0.9
+    # and it is the very same index, except where two candidates tie within that rounding (the float64
+    # evaluation then cannot tell which one binary32 prefers); such ties are rare
+    same = np.argmin(Q, axis=2) + 1 == idx
+    assert np.all(same | (chosen <= qmin * (1 + 1e-6)))
+    assert same.mean() >= 0.99
     # the stored scale is the chosen candidate, rounded once to fp16
     s32 = (s0.astype(np.float32) * 0 + (wmax.astype(np.float32) / np.float32(2 ** qmax - 1))) * \
         (idx.astype(np.float32) * np.float32(0.01))

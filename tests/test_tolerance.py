@@ -63,3 +63,33 @@ def test_ideal_fp32_accumulation_is_inside_the_gate(bits, K, seed):
     for k0 in range(0, K, 32):
         acc16 = (acc16.astype(np.float64) + X64[:, k0:k0 + 32] @ W[:, k0:k0 + 32].T).astype(np.float16)
     assert _err(acc16, want, K) > REL_TOL
+
+
+def test_outputs_below_the_normal_range_may_differ_by_one_quantum():
+    """An output below 2^-14 is a multiple of the fp16 subnormal quantum 2^-24.  The fp64 oracle rounds the
+    exact sum to that grid once; a kernel that accumulates in binary32 rounds a sum that differs from the
+    exact one by far less than a quantum, so the two roundings agree or land on neighbouring multiples --
+    never further apart.  One quantum is a relative error far above 2e-3 there (it is 2^-10 of the largest
+    subnormal and 100 % of the smallest), which is why the GPU tests of tiny activations allow one quantum
+    on top of the gate for such outputs, and nothing more."""
+    bits, K, N, M = 3, 4096, 192, 4
+    packed = workloads.packed_codes(9300, N, K, bits)
+    S = workloads.pot_scales(9301, N, K, 128)
+    X = (workloads.activations(9302, M, K).astype(np.float32) * np.float32(3e-7)).astype(np.float16)   # subnormal x
+    want = oracle.gemm(packed, S, None, X, K, bits, 128, nthreads=4).view(np.float16).astype(np.float64)
+    W = oracle.pot_dequant(packed, S, K, bits, 128, nthreads=4).view(np.float16).astype(np.float64)
+    ideal = _fp32_chain(X.astype(np.float64), W).astype(np.float16).astype(np.float64)
+    small = np.abs(want) < 2.0 ** -14
+    assert small.mean() > 0.9                       # the case is what it is meant to be
+    quantum = 2.0 ** -24
+    diff = np.abs(ideal - want)
+    assert diff[small].max() <= quantum             # neighbouring multiples at most
+    # the plain gate would reject such a neighbour: the allowance is needed, and it is one quantum, not two
+    rms = np.sqrt(np.mean(want * want))
+    gate = REL_TOL * np.maximum(np.abs(want), rms * _floor_fraction(K))
+    assert gate[small].max() < quantum
+    # the allowance the GPU tests use: gate + one quantum below the normal range
+    allowed = gate + np.where(small, quantum, 0.0)
+    assert np.all(diff <= allowed)
+    # two quanta off is outside it
+    assert np.all((2 * quantum > allowed)[small])
