@@ -38,9 +38,11 @@ CONFIG_INDEX = 3                # the Llama-2-70B layer workload (workloads.CONF
 CODE_SETS = 3                   # layers' worth of codes and scales the timed steps rotate through (3 x 227 MB)
 RAMP_UP = 100                   # untimed launches before the timed region (the first ~10 ms after idling run slow)
 
-# HBM bytes per launch of the headline kernel from rocprofv3 (FETCH_SIZE, WRITE_SIZE), measured once with the
-# commands in profiles/pot_dequant_batch_llama70b_layer.md; not re-measured by this script
-PROFILED_TRAFFIC = {"bytes_per_launch": None, "source": "profiles/pot_dequant_batch_llama70b_layer.md"}
+# HBM bytes per launch of the headline kernel by code width, from rocprofv3 FETCH_SIZE (x 2.000) + WRITE_SIZE
+# (x 1.000), factors calibrated on a 256 MiB copy: measured once with the commands in the file named here, not
+# re-measured by this script
+PROFILED_TRAFFIC = {"bytes_per_launch": {2: 1938657618, 3: 2045654589},
+                    "source": "profiles/pot_dequant_batch_llama70b_layer.md"}
 
 
 def _events(torch):
@@ -95,6 +97,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--bits", type=int, default=2, choices=(2, 3), help="code width of the headline pass")
+    ap.add_argument("--workload", default="70b", choices=("70b", "7b"),
+                    help="layer of the headline pass: Llama-2-70B (default) or Llama-2-7B (ten rotating code sets; "
+                         "for profiling runs, use with --no-extras)")
     ap.add_argument("--no-extras", action="store_true", help="headline only (used for profiling runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -189,8 +194,15 @@ def main() -> int:
     # CODE_SETS layers' worth.  Whatever --warmup says, RAMP_UP untimed launches come first so that the timed
     # region sees the steady state (clock ramp-up, cold address translation).
     bits = args.bits
-    head = Layer(CONFIG_INDEX, workloads.LLAMA2_70B_LAYER, bits, CODE_SETS, keep_host=not args.no_cpu)
-    head.ramp_up()
+    if args.workload == "7b":
+        head_cfg, head_shapes, head_sets, head_ramp = 1, workloads.LLAMA2_7B_LAYER, 10, 200
+        head_name = "Llama-2-7B decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008)"
+    else:
+        head_cfg, head_shapes, head_sets, head_ramp = CONFIG_INDEX, workloads.LLAMA2_70B_LAYER, CODE_SETS, RAMP_UP
+        head_name = ("Llama-2-70B decoder layer (q,o 8192x8192; k,v 1024x8192; gate,up 28672x8192; "
+                     "down 8192x28672)")
+    head = Layer(head_cfg, head_shapes, bits, head_sets, keep_host=not args.no_cpu)
+    head.ramp_up(head_ramp)
     ms = _time_steps(torch, head.pot_step, args.steps, args.warmup)
     value = head.pot_bytes / (ms * 1e-3) / 1e9
     result = {
@@ -206,12 +218,11 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "u16",
         "data": "synthetic",
-        "config": {"workload": "Llama-2-70B decoder layer (q,o 8192x8192; k,v 1024x8192; gate,up 28672x8192; "
-                               f"down 8192x28672), {bits}-bit PoT codes, group 128, stand-alone dequant of all "
+        "config": {"workload": f"{head_name}, {bits}-bit PoT codes, group 128, stand-alone dequant of all "
                                "seven matrices",
                    "bits": bits, "group": G, "weights": head.weights, "launches_per_step": 1,
                    "entry_point": "pot_dequant_batch", "layout": "canonical",
-                   "code_sets_rotated": CODE_SETS, "untimed_ramp_up_launches": RAMP_UP},
+                   "code_sets_rotated": head_sets, "untimed_ramp_up_launches": head_ramp},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "roofline": {
             "kernel": f"potq::dequant_batch_kernel<{bits}, false>",
@@ -222,7 +233,7 @@ def main() -> int:
             "frac": round(value / HBM_PEAK_GBPS, 4),
             "bytes_per_launch": head.pot_bytes,
             "us_per_launch": round(ms * 1e3, 3),
-            "traffic": PROFILED_TRAFFIC["bytes_per_launch"] if bits == 2 else None,
+            "traffic": PROFILED_TRAFFIC["bytes_per_launch"][bits] if args.workload == "70b" else None,
             "traffic_source": PROFILED_TRAFFIC["source"],
         },
     }
@@ -256,7 +267,7 @@ def main() -> int:
         }
     head.host = []
 
-    if args.no_extras:
+    if args.no_extras or args.workload != "70b":
         print(json.dumps(result))
         return 0
 

@@ -184,7 +184,7 @@ __device__ __forceinline__ void stage_digits(const u32x4 xv, u32x4 *__restrict__
 // 4p + t + 32, ...).  The codes of the next step -- the next round of the tile or the first round
 // of the next tile -- are requested before the current ones are expanded (requests two or three
 // steps ahead measured slower), and the very first request goes out before x is staged.
-template <int BITS, bool G64, int WAVES>
+template <int BITS, bool G64, int WAVES, bool SKIP_LAST>
 __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales,
                                               const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int K,
                                               int64_t rowtiles, int64_t first, int64_t stride)
@@ -216,39 +216,53 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
     // Codes of (tile, round) for lane (r, t); scales in memory order (lane l: row l/4, group
     // first + l%4; handed to their owners by a permute) or, for group size 64, the lane's own pair.
     // Indices past the end of the row are clamped into it: valid memory, multiplied by zeros.
-    auto fetch = [&](int64_t tile, int round, u32x4 (&Lx)[BITS], uint32_t &sx) {
+    // Every round requests the codes of the next step.  After a wavefront's last step there is
+    // nothing left to request; the request is still issued (a branch around it measured no
+    // better), either for the last step once more -- 3 KB fetched again for nothing, since the
+    // loads are non-temporal -- or, with `live` = false, with every lane pointed at the first 16
+    // bytes of each slab of the tile and at its first scale, a handful of 64-byte requests.
+    // SKIP_LAST chooses: with one or two tile sets per workgroup the repeat is a large share
+    // of the traffic and skipping it wins (8192 x 8192: 8.1 against 8.55 us, 8192 x 28672: 18.7
+    // against 19.6 us); with four or more the variant without the choice is scheduled better by
+    // the compiler and wins by more than the traffic costs (28672 x 8192: 17.0 against 18.1 us,
+    // 128256 x 4096: 32.4 against 36.3 us).
+    auto fetch = [&](int64_t tile, int round, bool live, u32x4 (&Lx)[BITS], uint32_t &sx) {
         const int g0 = round * kStep + part * 4;                        // uniform
         const int gc = min(g0 + t, G - 1);
         const u32x4 *tile_codes = codes + tile * G * (BITS * 16);       // uniform
-        const uint32_t at = (uint32_t)(gc * (BITS * 16) + r);
+        const uint32_t at = live ? (uint32_t)(gc * (BITS * 16) + r) : 0u;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) Lx[j] = __builtin_nontemporal_load(tile_codes + at + 16 * j);
         if (gs) {
             const uint32_t *tile_scales = (const uint32_t *)(scales + tile * kTileRows * (int64_t)(2 * G));
-            sx = tile_scales[(uint32_t)(r * G + gc)];
+            sx = tile_scales[live ? (uint32_t)(r * G + gc) : 0u];
         } else {
             const uint16_t *tile_scales = scales + tile * kTileRows * (int64_t)G;
-            sx = tile_scales[(uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1))];
+            sx = tile_scales[live ? (uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1)) : 0u];
         }
     };
 
     // The steps of a wavefront are its (tile set, round) pairs in order.  `fq`/`fround` is the
-    // step of the next request; past the last step the last one is requested again (valid
-    // memory, never used).
+    // step of the next request and `more` tells whether there is one.
     int64_t fq = first;
     int fround = 0;
-    auto advance = [&]() {
+    auto advance = [&]() -> bool {
         if (fround + 1 < my_rounds) {
             ++fround;
-        } else if ((fq + stride) * SLOTS < rowtiles) {
+            return true;
+        }
+        if ((fq + stride) * SLOTS < rowtiles) {
             fq += stride;
             fround = 0;
+            return true;
         }
+        return false;
     };
     u32x4 L[BITS];
     uint32_t s;
-    fetch(tile_of(fq), fround, L, s);
-    advance();
+    fetch(tile_of(fq), fround, true, L, s);
+    bool more = advance();
+    (void)more;
 
     // --- activations: largest exponent, then fixed point digits into LDS ---
     const int octets = K / 8;
@@ -306,7 +320,7 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
             for (int round = 0; round < my_rounds; ++round) {
                 u32x4 Lp[BITS];
                 uint32_t sp;
-                fetch(tile_of(q), round, Lp, sp);
+                fetch(tile_of(q), round, true, Lp, sp);
                 const int g = round * kStep + part * 4 + t;
                 const uint16_t *xg = (const uint16_t *)x + (size_t)min(g, G - 1) * kTileCols;
                 if (gs) {
@@ -349,8 +363,13 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
         for (int round = 0; round < my_rounds; ++round) {
             u32x4 Ln[BITS];
             uint32_t sn;
-            fetch(tile_of(fq), fround, Ln, sn);
-            advance();
+            if constexpr (SKIP_LAST) {
+                fetch(tile_of(fq), fround, more, Ln, sn);
+                more = more && advance();
+            } else {
+                fetch(tile_of(fq), fround, true, Ln, sn);
+                advance();
+            }
             const int g = round * kStep + part * 4 + t;
             // a lane past the end of the row multiplies the (valid) last group by zeros
             lds_read_keep(xa, g < G ? pieces_at + (uint32_t)((g * 4 + (lane & 3)) * (kPieceRun * 16)) : zeros_at,
@@ -380,12 +399,12 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
     }
 }
 
-template <int BITS, bool G64, int WAVES>
+template <int BITS, bool G64, int WAVES, bool SKIP_LAST>
 __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_kernel(
     const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const u32x4 *__restrict__ x,
     uint16_t *__restrict__ y, int K, int64_t rowtiles)
 {
-    gemv_exp_body<BITS, G64, WAVES>(codes, scales, x, y, K, rowtiles, blockIdx.x, gridDim.x);
+    gemv_exp_body<BITS, G64, WAVES, SKIP_LAST>(codes, scales, x, y, K, rowtiles, blockIdx.x, gridDim.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -422,29 +441,33 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
     const int64_t first = blockIdx.x, stride = gridDim.x;
     auto tile_of = [&](int64_t q) { return min(q * SLOTS + slot, rowtiles - 1); };
 
-    auto fetch = [&](int64_t tile, int round, u32x4 (&Lx)[BITS], uint32_t &sx) {
+    auto fetch = [&](int64_t tile, int round, bool live, u32x4 (&Lx)[BITS], uint32_t &sx) {   // as in gemv_exp_body
         const int g0 = round * kStep + part * 4;
         const int gc = min(g0 + t, G - 1);
         const u32x4 *tile_codes = codes + tile * G * (BITS * 16);
-        const uint32_t at = (uint32_t)(gc * (BITS * 16) + r);
+        const uint32_t at = live ? (uint32_t)(gc * (BITS * 16) + r) : 0u;
 #pragma unroll
         for (int j = 0; j < BITS; ++j) Lx[j] = __builtin_nontemporal_load(tile_codes + at + 16 * j);
         const uint16_t *tile_scales = scales + tile * kTileRows * (int64_t)G;
-        sx = tile_scales[(uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1))];
+        sx = tile_scales[live ? (uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1)) : 0u];
     };
     int64_t fq = first;
     int fround = 0;
-    auto advance = [&]() {
+    auto advance = [&]() -> bool {
         if (fround + 1 < my_rounds) {
             ++fround;
-        } else if ((fq + stride) * SLOTS < rowtiles) {
+            return true;
+        }
+        if ((fq + stride) * SLOTS < rowtiles) {
             fq += stride;
             fround = 0;
+            return true;
         }
+        return false;
     };
     u32x4 L[BITS];
     uint32_t s;
-    fetch(tile_of(fq), fround, L, s);
+    fetch(tile_of(fq), fround, true, L, s);
     advance();
 
     // --- activations: per vector the largest exponent, then fixed point digits into LDS ---
@@ -522,7 +545,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
             for (int round = 0; round < my_rounds; ++round) {
                 u32x4 Lp[BITS];
                 uint32_t sp;
-                fetch(tile_of(q), round, Lp, sp);
+                fetch(tile_of(q), round, true, Lp, sp);
                 const int g = round * kStep + part * 4 + t;
                 const float sf = (float)__builtin_bit_cast(_Float16, (uint16_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)sp));
 #pragma unroll 1
@@ -562,7 +585,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
         for (int round = 0; round < my_rounds; ++round) {
             u32x4 Ln[BITS];
             uint32_t sn;
-            fetch(tile_of(fq), fround, Ln, sn);
+            fetch(tile_of(fq), fround, true, Ln, sn);      // after the last step: the last one again (never used)
             advance();
             const int g = round * kStep + part * 4 + t;
             const bool mine = diagonal && g < G;
@@ -615,13 +638,13 @@ struct ExpBatch {
     int count;
 };
 
-template <int BITS, bool G64, int WAVES>
+template <int BITS, bool G64, int WAVES, bool SKIP_LAST>
 __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_batch_kernel(const ExpBatch batch,
                                                                        const u32x4 *__restrict__ x, int K)
 {
     int i = 0;
     while (i + 1 < batch.count && blockIdx.x >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
-    gemv_exp_body<BITS, G64, WAVES>(batch.codes[i], batch.scales[i], x, batch.y[i], K, batch.rowtiles[i],
+    gemv_exp_body<BITS, G64, WAVES, SKIP_LAST>(batch.codes[i], batch.scales[i], x, batch.y[i], K, batch.rowtiles[i],
                                     blockIdx.x - batch.first_block[i],
                                     batch.first_block[i + 1] - batch.first_block[i]);
 }
@@ -668,12 +691,12 @@ bool gemv_exp_batch_ok(int count, int64_t rows_total, int64_t K, int bits)
     return count <= kMaxExpBatch && gemv_exp_ok(rows_total, K, bits);
 }
 
-template <int BITS, bool G64, int WAVES, bool BATCH>
+template <int BITS, bool G64, int WAVES, bool SKIP_LAST, bool BATCH>
 static hipError_t exp_allow_lds(size_t lds)
 {
     static std::atomic<uint64_t> raised{0};           // one flag word per kernel instantiation
-    const void *kernel = BATCH ? (const void *)gemv_exp_batch_kernel<BITS, G64, WAVES>
-                               : (const void *)gemv_exp_kernel<BITS, G64, WAVES>;
+    const void *kernel = BATCH ? (const void *)gemv_exp_batch_kernel<BITS, G64, WAVES, SKIP_LAST>
+                               : (const void *)gemv_exp_kernel<BITS, G64, WAVES, SKIP_LAST>;
     return allow_large_lds(kernel, lds, raised);
 }
 
@@ -685,17 +708,21 @@ static int64_t exp_groups(int64_t sets, int64_t cap)
     return (sets + per_group - 1) / per_group;
 }
 
-template <int BITS, bool G64, int WAVES>
+// Tile sets a workgroup walks at most; up to two, the variant that skips the repeated last request serves.
+static int64_t exp_sets_per_group(int64_t sets, int64_t cap) { return (sets + (cap < 1 ? 1 : cap) - 1) / (cap < 1 ? 1 : cap); }
+constexpr int64_t kSkipLastUpTo = 2;
+
+template <int BITS, bool G64, int WAVES, bool SKIP_LAST>
 static hipError_t launch_exp(const void *codes, const void *scales, const void *x, void *y, int64_t N, int64_t K,
                              hipStream_t stream)
 {
     const size_t lds = exp_lds_bytes(K, WAVES);
-    const hipError_t e = exp_allow_lds<BITS, G64, WAVES, false>(lds);
+    const hipError_t e = exp_allow_lds<BITS, G64, WAVES, SKIP_LAST, false>(lds);
     if (e != hipSuccess) return e;
     constexpr int SLOTS = WAVES / kExpSplit;
     const int64_t rowtiles = N / kTileRows;
     const dim3 grid((unsigned)exp_groups((rowtiles + SLOTS - 1) / SLOTS, kExpGroups / SLOTS)), block(WAVES * kWave);
-    hipLaunchKernelGGL((gemv_exp_kernel<BITS, G64, WAVES>), grid, block, lds, stream, (const u32x4 *)codes,
+    hipLaunchKernelGGL((gemv_exp_kernel<BITS, G64, WAVES, SKIP_LAST>), grid, block, lds, stream, (const u32x4 *)codes,
                        (const uint16_t *)scales, (const u32x4 *)x, (uint16_t *)y, (int)K, rowtiles);
     return hipGetLastError();
 }
@@ -704,10 +731,13 @@ hipError_t run_gemv_exp(const void *codes, const void *scales, const void *x, vo
                         int group, hipStream_t stream)
 {
     const bool g64 = group == 64;
-#define POTQ_LAUNCH_EXP(BITS, WAVES)                                                              \
-    (g64 ? launch_exp<BITS, true, WAVES>(codes, scales, x, y, N, K, stream)                       \
-         : launch_exp<BITS, false, WAVES>(codes, scales, x, y, N, K, stream))
-    return bits == 3 ? POTQ_LAUNCH_EXP(3, 16) : POTQ_LAUNCH_EXP(2, 16);
+    constexpr int WAVES = 16, SLOTS = WAVES / kExpSplit;
+    const bool skip = exp_sets_per_group((N / kTileRows + SLOTS - 1) / SLOTS, kExpGroups / SLOTS) <= kSkipLastUpTo;
+#define POTQ_LAUNCH_EXP(BITS, G64)                                                                \
+    (skip ? launch_exp<BITS, G64, WAVES, true>(codes, scales, x, y, N, K, stream)                 \
+          : launch_exp<BITS, G64, WAVES, false>(codes, scales, x, y, N, K, stream))
+    if (bits == 3) return g64 ? POTQ_LAUNCH_EXP(3, true) : POTQ_LAUNCH_EXP(3, false);
+    return g64 ? POTQ_LAUNCH_EXP(2, true) : POTQ_LAUNCH_EXP(2, false);
 #undef POTQ_LAUNCH_EXP
 }
 
@@ -717,13 +747,12 @@ static hipError_t launch_exp_batch(int count, const void *const *codes, const vo
                                    const int64_t *N, const void *x, int64_t K, hipStream_t stream)
 {
     const size_t lds = exp_lds_bytes(K, WAVES);
-    const hipError_t e = exp_allow_lds<BITS, G64, WAVES, true>(lds);
-    if (e != hipSuccess) return e;
     constexpr int SLOTS = WAVES / kExpSplit;
     int64_t sets_total = 0;
     for (int i = 0; i < count; ++i) sets_total += (N[i] / kTileRows + SLOTS - 1) / SLOTS;
     ExpBatch b;
     uint64_t blocks = 0;
+    int64_t sets_per_group = 0;
     for (int i = 0; i < kMaxExpBatch; ++i) {
         const bool live = i < count;
         b.codes[i] = live ? (const u32x4 *)codes[i] : nullptr;
@@ -734,13 +763,25 @@ static hipError_t launch_exp_batch(int count, const void *const *codes, const vo
         if (live) {
             // each matrix gets the share of the resident workgroups that its share of the tiles asks for
             const int64_t sets = (b.rowtiles[i] + SLOTS - 1) / SLOTS;
-            blocks += (uint64_t)exp_groups(sets, (kExpGroups / SLOTS) * sets / sets_total);
+            const int64_t cap = (kExpGroups / SLOTS) * sets / sets_total;
+            blocks += (uint64_t)exp_groups(sets, cap);
+            if (exp_sets_per_group(sets, cap) > sets_per_group) sets_per_group = exp_sets_per_group(sets, cap);
         }
     }
     b.first_block[kMaxExpBatch] = (uint32_t)blocks;
     b.count = count;
-    hipLaunchKernelGGL((gemv_exp_batch_kernel<BITS, G64, WAVES>), dim3((unsigned)blocks), dim3(WAVES * kWave), lds,
-                       stream, b, (const u32x4 *)x, (int)K);
+    const dim3 grid((unsigned)blocks), block(WAVES * kWave);
+    if (sets_per_group <= kSkipLastUpTo) {
+        const hipError_t e = exp_allow_lds<BITS, G64, WAVES, true, true>(lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((gemv_exp_batch_kernel<BITS, G64, WAVES, true>), grid, block, lds, stream, b, (const u32x4 *)x,
+                           (int)K);
+    } else {
+        const hipError_t e = exp_allow_lds<BITS, G64, WAVES, false, true>(lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((gemv_exp_batch_kernel<BITS, G64, WAVES, false>), grid, block, lds, stream, b, (const u32x4 *)x,
+                           (int)K);
+    }
     return hipGetLastError();
 }
 
