@@ -402,6 +402,34 @@ def main() -> int:
     # the vocabulary projection of a decoder (32000 or 128256 rows): the largest matrix of a decode step
     extras["pot_gemv_3bit_vocabulary_projection"] = gemv_pairs(((32000, 4096), (128256, 4096), (128256, 8192)), 3, 3)
 
+    # the same product on the canonical layout (the boundary's own format, no repack) next to the tiled one
+    canon = []
+    for (N, K) in ((11008, 4096), (28672, 8192), (8192, 28672)):
+        nbytes = workloads.algorithmic_bytes_gemm(1, N, K, b3, G)
+        R = rotate(nbytes)
+        cs = [random_codes(N, K, b3) for _ in range(R)]
+        sc_ = to_dev(workloads.pot_scales(workloads.seed_of(3, 0, 1), N, K, G))
+        x = to_dev(workloads.activations(workloads.seed_of(3, 0, 2), 1, K)[0])
+        y = torch.empty((N,), dtype=torch.float16, device=dev)
+        calls = {lay: [(c.data_ptr(), sc_.data_ptr(), x.data_ptr(), y.data_ptr(), N, K, b3, G, lay, stream) for c in cs]
+                 for lay in (binding.LAYOUT_CANONICAL, binding.LAYOUT_TILE16)}
+
+        def canon_rot():
+            for c in calls[binding.LAYOUT_CANONICAL]:
+                check(lib.pot_gemv(*c))
+
+        def tiled_rot():
+            for c in calls[binding.LAYOUT_TILE16]:
+                check(lib.pot_gemv(*c))
+
+        reps = max(2, 128 // R)
+        us_c, us_t = (t * 1e3 / R for t in _time_pair(torch, canon_rot, tiled_rot, reps, 2))
+        canon.append(dict(_hbm(nbytes, us_c), shape=f"{N}x{K}", bits=b3, layout="canonical",
+                          tiled_us=round(us_t, 2), buffers_rotated=R))
+        del cs, calls
+        torch.cuda.empty_cache()
+    extras["pot_gemv_3bit_canonical_layout"] = canon
+
     # shared-activation batches: q/k/v (3 x 4096x4096) and gate/up (2 x 11008x4096) in one launch each
     shared = []
     for label, (N, K), copies in (("qkv 3x4096x4096", (4096, 4096), 3), ("gate_up 2x11008x4096", (11008, 4096), 2)):

@@ -151,9 +151,12 @@ int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits,
  *   y[n] = fp16( sum_k W~[n,k] * x[k] ),  W~ as defined by pot_dequant,
  * products exact, accumulation in fp32, one rounding to fp16 at the end.
  *   x_f16 in  K fp16;   y_f16 out  N fp16
- * `layout` names the layout `codes` is in; only POTQ_LAYOUT_TILE16 is accepted
- * (POTQ_ERR_LAYOUT otherwise; potq_repack converts), which needs N % 16 == 0.
- * The whole of x is held in on-chip memory: K <= 76672 (POTQ_ERR_SHAPE beyond).
+ * `layout` names the layout `codes` is in.  POTQ_LAYOUT_TILE16 (needs N % 16 == 0;
+ * potq_repack converts) is the fast path.  POTQ_LAYOUT_CANONICAL consumes the
+ * boundary format as it is, any N, with more arithmetic per weight (about half
+ * the speed on large matrices); there scales, zeros and y need only 2-byte
+ * alignment.  The whole of x is held in on-chip memory: K <= 76672 (tiled) or
+ * K <= 81920 (canonical), POTQ_ERR_SHAPE beyond.
  *
  * Large 2- and 3-bit matrices (potq_gemv_exponent_form() tells which) are served
  * in the exponent form of the product (Sec. 4.2, additivity of exponents):
@@ -171,7 +174,7 @@ int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits,
 int pot_gemv(const void *codes, const void *scales, const void *x_f16, void *y_f16,
              int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
 
-/* int_gemv -- the same with W~ as defined by int_dequant. */
+/* int_gemv -- the same with W~ as defined by int_dequant (both layouts). */
 int int_gemv(const void *codes, const void *scales, const void *zeros, const void *x_f16, void *y_f16,
              int64_t N, int64_t K, int bits, int group, int layout, void *hip_stream);
 
@@ -192,8 +195,8 @@ int potq_gemv_exponent_form(int64_t N, int64_t K, int bits);
  * a few-microsecond kernel dominated by launch and memory latency, so sharing a
  * launch is worth more than any tuning inside it.  `items_host` is a HOST array
  * (copied into the launch); all matrices share K, bits, group and layout, each
- * has its own N (a multiple of 16).  Results equal `count` separate calls bit
- * for bit.
+ * has its own N (a multiple of 16); only POTQ_LAYOUT_TILE16 is accepted here and
+ * by pot_gemm / int_gemm.  Results equal `count` separate calls bit for bit.
  */
 typedef struct potq_gemv_item {
     const void *codes;      /* device, POTQ_LAYOUT_TILE16 */

@@ -10,7 +10,7 @@ CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB_PATH = os.path.join(_HERE, "libpotq.so")
 OBJ_DIR = os.path.join(_HERE, "_build")
-SOURCES = ["api.hip", "dequant.hip", "repack.hip", "gemv.hip", "gemv_exp.hip", "gemm.hip", "quantize.hip", "fakequant.hip"]
+SOURCES = ["api.hip", "dequant.hip", "repack.hip", "gemv.hip", "gemv_exp.hip", "gemv_canonical.hip", "gemm.hip", "quantize.hip", "fakequant.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

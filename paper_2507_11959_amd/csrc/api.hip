@@ -18,6 +18,9 @@ hipError_t run_fill_zero(void *p, int64_t count, hipStream_t stream);
 size_t gemv_lds_bytes(int64_t K);
 hipError_t run_gemv_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
                            void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
+size_t gemv_canonical_lds_bytes(int64_t K);
+hipError_t run_gemv_canonical(bool is_int, const void *codes, const void *scales, const void *zeros, const void *x,
+                              void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 int gemv_max_batch();
 bool gemv_exp_ok(int64_t N, int64_t K, int bits);
 hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *codes, const void *const *scales,
@@ -105,15 +108,22 @@ int gemv_entry(bool is_int, const void *codes, const void *scales, const void *z
 {
     const int st = check_common(N, K, bits, group, true);
     if (st != POTQ_OK) return st;
-    if (layout != POTQ_LAYOUT_TILE16) return POTQ_ERR_LAYOUT;
-    if (N % 16 != 0) return POTQ_ERR_SHAPE;
+    if (layout != POTQ_LAYOUT_TILE16 && layout != POTQ_LAYOUT_CANONICAL) return POTQ_ERR_LAYOUT;
+    const bool tiled = layout == POTQ_LAYOUT_TILE16;
+    if (tiled && N % 16 != 0) return POTQ_ERR_SHAPE;
     if (N == 0) return POTQ_OK;
     if (!y) return POTQ_ERR_NULL;
-    if (misaligned(y)) return POTQ_ERR_ALIGN;
+    if (misaligned(y, tiled ? 16 : 2)) return POTQ_ERR_ALIGN;
     if (K == 0) return finish(potq::run_fill_zero(y, N, (hipStream_t)stream));
     if (!codes || !scales || !x || (is_int && !zeros)) return POTQ_ERR_NULL;
-    if (misaligned(codes) || misaligned(scales) || misaligned(x) || (is_int && misaligned(zeros)))
+    if (misaligned(codes) || misaligned(scales, tiled ? 16 : 2) || misaligned(x) ||
+        (is_int && misaligned(zeros, tiled ? 16 : 2)))
         return POTQ_ERR_ALIGN;
+    if (!tiled) {
+        if (potq::gemv_canonical_lds_bytes(K) > kMaxLdsBytes) return POTQ_ERR_SHAPE;
+        return finish(potq::run_gemv_canonical(is_int, codes, scales, zeros, x, y, N, K, bits, group,
+                                               (hipStream_t)stream));
+    }
     if (potq::gemv_lds_bytes(K) > kMaxLdsBytes) return POTQ_ERR_SHAPE;
     return finish(potq::run_gemv_tile16(is_int, codes, scales, zeros, x, y, N, K, bits, group, (hipStream_t)stream));
 }
