@@ -276,14 +276,17 @@ int pot_gemm_noalloc(const void *codes, const void *scales, const void *X_f16, v
  *     s0 = max|w| / (2^qmax - 1),  qmax = 2^(bits-1) - 1
  *     for i = 1..200:  s = s0 * (0.01 i);  E_k = clamp(round(log2(|w_k|/s)), 0, qmax);
  *                      Q(i) = sum_k (w_k - sign(w_k) s 2^E_k)^2
- *     i* = the first i with the smallest Q;  scale = fp16(s0 * 0.01 i*);  codes = (sign, E) under it.
+ *     i* = the first i with the smallest Q;  scale = s(i*);  codes = (sign, E) under it.
  * The paper leaves the arithmetic open; it is fixed here as IEEE binary32, one
- * rounding per operation, no contraction: b_i = (float)i * 0.01f; s = s0 * b_i
- * (s0 by a binary32 division); E = number of e in 1..qmax with |w| >= s * (float)2^(e-1/2)
- * (a tie rounds up, |w| = 0 gives E = 0); w~ = s * 2^E exactly; d = w - w~;
- * Q = fma(d, d, Q) for k ascending; the sign bit is set only for w < 0; an all-zero
- * group gets E = 0 everywhere; the fp16 scale is clamped into [2^-14, largest value with
- * exponent field 30 - qmax] so that it lies in pot_dequant's exact domain.
+ * rounding per operation, no contraction: b_i = (float)i * 0.01f; s0 by a binary32
+ * division; every candidate is taken as it would be stored and used at inference
+ * (Sec. 4.2 keeps the scale as FP16): s = s0 * b_i rounded once to fp16 and clamped
+ * into [2^-14, largest value with exponent field 30 - qmax], pot_dequant's exact
+ * domain, so that Q(i) is the error of exactly what pot_dequant rebuilds and the
+ * codes are the quantisation under the stored scale; E = number of e in 1..qmax with
+ * |w| >= s * (float)2^(e-1/2) (a tie rounds up, |w| = 0 gives E = 0); w~ = s * 2^E
+ * exactly; d = w - w~; Q = fma(d, d, Q) for k ascending; the sign bit is set only
+ * for w < 0; an all-zero group gets the smallest scale, i* = 1 and E = 0 everywhere.
  *   W_f16      in   N x K fp16, row-major
  *   codes_out  out  canonical layout, N rows of K*bits/8 bytes
  *   scales_out out  N x (K/group) fp16

@@ -309,21 +309,34 @@ int orc_max_threads(void)
  * The paper leaves the arithmetic open.  So that the integer decisions (E, the
  * arg-min) are well defined and can be reproduced bit for bit, this oracle fixes
  * it as IEEE binary32 throughout, one rounding per operation, no contraction:
- *   - b_i = (float)i * 0.01f ; s = s0 * b_i ; s0 by a binary32 division;
+ *   - b_i = (float)i * 0.01f ; s0 by a binary32 division; the candidate scale is what would be
+ *     stored and used at inference (Sec. 4.2 keeps the scale as FP16): s = s0 * b_i rounded once
+ *     to binary16 and clamped into the domain on which the de-quantisation recipe is exact
+ *     ([2^-14, largest value with exponent field 30 - qmax]); thresholds, reconstruction and
+ *     error are taken from that value, so Q(i) is the error of exactly what pot_dequant rebuilds;
  *   - round(log2(|w|/s)) is taken through its decision thresholds: E = number of
  *     e in 1..qmax with |w| >= s * c_e, c_e = (float)2^(e - 1/2) (a tie on a
  *     threshold rounds up; |w| = 0 gives E = 0 as clamp(-inf) does);
  *   - w~ = s * 2^E is exact; d = w - w~ ; Q = fmaf(d, d, Q), k ascending;
  *   - sign(0) = +, i.e. the sign bit is set only for w < 0;
- *   - an all-zero group (s0 = 0) gets E = 0 everywhere;
- *   - the scale is rounded once to binary16 and clamped into the domain on which
- *     the de-quantisation recipe is exact ([2^-14, largest value with exponent
- *     field 30 - qmax]).
+ *   - an all-zero group (s0 = 0) has every candidate clamped to 2^-14, equal errors, i* = 1
+ *     and E = 0 everywhere.
  * codes: N*K bytes, one code per byte.  best_i (optional): N*(K/group) ints.
  */
 static const float k_round_thresholds[8] = {
     0.0f, 1.41421356237309504880f, 2.82842712474619009760f, 5.65685424949238019521f,
     11.3137084989847603904f, 22.6274169979695207808f, 45.2548339959390415616f, 90.5096679918780831232f};
+
+/* Candidate i of a group: binary16 pattern of the scale as it would be stored. */
+static uint16_t quantize_candidate(float s0, int i, int qmax)
+{
+    const float s = s0 * ((float)i * 0.01f);
+    uint16_t sb = orc_double_to_half((double)s);
+    const uint16_t lo = 0x0400, hi = (uint16_t)(((30 - qmax) << 10) | 0x3FF);
+    if (sb < lo) sb = lo;          /* positive patterns order like the values */
+    if (sb > hi) sb = hi;
+    return sb;
+}
 
 void orc_pot_quantize(const uint16_t *W, uint8_t *codes, uint16_t *scales, int32_t *best_i,
                       int64_t N, int64_t K, int bits, int group, int nthreads)
@@ -349,8 +362,7 @@ void orc_pot_quantize(const uint16_t *W, uint8_t *codes, uint16_t *scales, int32
             int ibest = 1;
             float qbest = INFINITY;
             for (int i = 1; i <= 200; ++i) {
-                const float b = (float)i * 0.01f;
-                const float s = s0 * b;
+                const float s = (float)orc_half_to_double(quantize_candidate(s0, i, qmax));
                 float q = 0.0f;
                 for (int k = 0; k < group; ++k) {
                     const float a = fabsf(w[k]);
@@ -367,19 +379,15 @@ void orc_pot_quantize(const uint16_t *W, uint8_t *codes, uint16_t *scales, int32
                     ibest = i;
                 }
             }
-            const float sbest = s0 * ((float)ibest * 0.01f);
+            const uint16_t sb = quantize_candidate(s0, ibest, qmax);
+            const float sbest = (float)orc_half_to_double(sb);
             for (int k = 0; k < group; ++k) {
                 const float a = fabsf(w[k]);
                 int E = 0;
-                if (s0 > 0.0f)
-                    for (int e = 1; e <= qmax; ++e)
-                        if (a >= sbest * k_round_thresholds[e]) E = e;
+                for (int e = 1; e <= qmax; ++e)
+                    if (a >= sbest * k_round_thresholds[e]) E = e;
                 dst[k] = (uint8_t)((w[k] < 0.0f ? (1 << (bits - 1)) : 0) | E);
             }
-            uint16_t sb = orc_double_to_half((double)sbest);
-            const uint16_t lo = 0x0400, hi = (uint16_t)(((30 - qmax) << 10) | 0x3FF);
-            if (sb < lo) sb = lo;          /* positive patterns order like the values */
-            if (sb > hi) sb = hi;
             scales[n * ngroups + g] = sb;
             if (best_i) best_i[n * ngroups + g] = ibest;
         }

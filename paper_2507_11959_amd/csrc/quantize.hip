@@ -1,7 +1,7 @@
 // Step 1 of PoT-PTQ on the GPU: data-agnostic scale search (Sec. 3.2, Algorithm 1).
 //
 // For every group of G weights: s0 = max|w| / (2^qmax - 1); for the 200 multipliers
-// b = 0.01 i the group is quantised with s = s0 b (E = clamp(round(log2(|w|/s)), 0, qmax),
+// b = 0.01 i the group is quantised with s = fp16(s0 b) (E = clamp(round(log2(|w|/s)), 0, qmax),
 // w~ = sign(w) s 2^E) and the squared error summed; the first multiplier with the
 // smallest error wins; its scale (fp16) and codes are written out in the canonical
 // packed layout, ready for pot_dequant / potq_repack.
@@ -26,6 +26,29 @@ constexpr int kQuantThreads = 448;       // 7 wavefronts: 400 (group, multiplier
 __device__ __constant__ const float kRoundThreshold[8] = {
     0.0f, 1.41421356237309504880f, 2.82842712474619009760f, 5.65685424949238019521f,
     11.3137084989847603904f, 22.6274169979695207808f, 45.2548339959390415616f, 90.5096679918780831232f};
+
+// Candidate i of a group as it would be stored and used at inference (Sec. 4.2 keeps the scale
+// as FP16): s0 * (0.01 i) rounded once to binary16 and clamped into the domain on which the
+// de-quantisation recipe is exact; returned as its bit pattern.
+template <int BITS>
+__device__ __forceinline__ uint32_t quantize_candidate(float s0, int i)
+{
+    constexpr int qmax = (1 << (BITS - 1)) - 1;
+    float s = s0 * ((float)i * 0.01f);
+    // The product is rounded to binary32 first and to binary16 second, as documented.  Left to
+    // itself the compiler fuses multiply and conversion into one mixed-precision instruction
+    // with a single rounding, which differs when the binary32 product lands on a binary16
+    // midpoint; the empty asm makes the binary32 value the conversion's operand.
+    asm volatile("" : "+v"(s));
+    const uint32_t sb = __builtin_bit_cast(uint16_t, (_Float16)s);
+    const uint32_t lo = 0x0400u, hi = ((30u - qmax) << 10) | 0x3FFu;
+    return sb < lo ? lo : (sb > hi ? hi : sb);
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t bits)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+}
 
 template <int BITS>
 __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
@@ -65,7 +88,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     if (tid < kGroupsPerBlock * kCandidates) {
         const int gi = tid / kCandidates, i = tid % kCandidates + 1;
         const float s0 = __fdiv_rn(wmax_s[gi], (float)((1 << qmax) - 1));
-        const float s = s0 * ((float)i * 0.01f);
+        const float s = half_bits_to_float(quantize_candidate<BITS>(s0, i));
         float thr[qmax + 1], mag_of[qmax + 1];
 #pragma unroll
         for (int e = 0; e <= qmax; ++e) {
@@ -115,23 +138,17 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
         const int gi = tid >> 7, k = tid & 127;
         if (g0 + gi < total_groups && k < group) {
             const float s0 = __fdiv_rn(wmax_s[gi], (float)((1 << qmax) - 1));
-            const float s = s0 * ((float)best_s[gi] * 0.01f);
+            const uint32_t sb = quantize_candidate<BITS>(s0, best_s[gi]);
+            const float s = half_bits_to_float(sb);
             const float x = w[gi][k];
             int E = 0;
-            if (s0 > 0.f) {
 #pragma unroll
-                for (int e = 1; e <= qmax; ++e) E = fabsf(x) >= s * kRoundThreshold[e] ? e : E;
-            }
+            for (int e = 1; e <= qmax; ++e) E = fabsf(x) >= s * kRoundThreshold[e] ? e : E;
             const uint32_t code = (uint32_t)E | (x < 0.f ? (1u << (BITS - 1)) : 0u);
             const int pos = BITS * k, idx = pos >> 5, sh = pos & 31;
             atomicOr(&packed[gi][idx], code << sh);
             if (sh + BITS > 32) atomicOr(&packed[gi][idx + 1], code >> (32 - sh));
-            if (k == 0) {
-                uint32_t sb = __builtin_bit_cast(uint16_t, (_Float16)s);
-                const uint32_t lo = 0x0400u, hi = ((30u - qmax) << 10) | 0x3FFu;
-                sb = sb < lo ? lo : (sb > hi ? hi : sb);
-                scales[g0 + gi] = (uint16_t)sb;
-            }
+            if (k == 0) scales[g0 + gi] = (uint16_t)sb;
         }
     }
     __syncthreads();

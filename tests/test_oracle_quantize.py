@@ -56,34 +56,44 @@ def test_against_the_literal_formula_in_float64(bits, group):
     codes, scales, idx = oracle.pot_quantize(W, bits, group, want_index=True)
     W64 = W.astype(np.float64).reshape(N, K // group, group)
     wmax = np.abs(W64).max(axis=2)
-    s0 = wmax / (2 ** qmax - 1)
-    mult = 0.01 * np.arange(1, 201)
-    # Q(i) for every candidate by the printed formula
+    # the candidates as they would be stored (Sec. 4.2: the scale is FP16): s0 * b_i in binary32, rounded once
+    # to binary16 by numpy, clamped into the exact domain of the de-quantisation recipe
+    s0 = wmax.astype(np.float32) / np.float32(2 ** qmax - 1)
+    mult = np.arange(1, 201, dtype=np.float32) * np.float32(0.01)
+    lo = np.float16(2.0 ** -14)
+    hi = np.array([((30 - qmax) << 10) | 0x3FF], dtype=np.uint16).view(np.float16)[0]
+    cand = np.clip((s0[..., None] * mult).astype(np.float16), lo, hi)                  # (N, groups, 200) fp16
+    # Q(i) for every candidate by the printed formula, in float64
     Q = np.empty((N, K // group, 200))
-    for j, b in enumerate(mult):
-        _, Wq = _literal(W64, (s0 * b)[..., None], qmax)
+    for j in range(200):
+        _, Wq = _literal(W64, cand[..., j].astype(np.float64)[..., None], qmax)
         Q[..., j] = ((W64 - Wq) ** 2).sum(axis=2)
     qmin = Q.min(axis=2)
     chosen = np.take_along_axis(Q, (idx - 1)[..., None], axis=2)[..., 0]
     # the oracle's choice is optimal up to binary32 rounding of the error sums
     assert np.all(chosen <= qmin * (1 + 1e-5))
     # and it is the very same index, except where two candidates tie within that rounding (the float64
-    # evaluation then cannot tell which one binary32 prefers); such ties are rare
+    # evaluation then cannot tell which one binary32 prefers; neighbouring multipliers that round to the same
+    # fp16 scale tie exactly, and both sides keep the first); such ties are rare
     same = np.argmin(Q, axis=2) + 1 == idx
     assert np.all(same | (chosen <= qmin * (1 + 1e-6)))
     assert same.mean() >= 0.99
-    # the stored scale is the chosen candidate, rounded once to fp16
-    s32 = (s0.astype(np.float32) * 0 + (wmax.astype(np.float32) / np.float32(2 ** qmax - 1))) * \
-        (idx.astype(np.float32) * np.float32(0.01))
-    assert np.array_equal(scales, s32.astype(np.float16).view(np.uint16))
-    # the codes are the printed formula's codes under that (binary32) scale, except within rounding of a threshold
-    E_lit, _ = _literal(W64, s32.astype(np.float64)[..., None], qmax)
+    # the stored scale is the chosen candidate
+    stored = np.take_along_axis(cand, (idx - 1)[..., None], axis=2)[..., 0]
+    assert np.array_equal(scales, stored.view(np.uint16))
+    # the codes are the printed formula's codes under the stored scale, except within rounding of a threshold
+    s_stored = stored.astype(np.float64)
+    E_lit, W_lit = _literal(W64, s_stored[..., None], qmax)
     E = (codes & (2 ** (bits - 1) - 1)).reshape(N, K // group, group)
-    ratio = np.abs(W64) / s32.astype(np.float64)[..., None]
+    ratio = np.abs(W64) / s_stored[..., None]
     with np.errstate(divide="ignore"):
         frac = np.abs(np.log2(np.where(ratio > 0, ratio, 1.0)) % 1.0 - 0.5)
     near_threshold = frac < 1e-5
     assert np.all((E == E_lit) | near_threshold)
+    # and what pot_dequant rebuilds from (codes, scale) is that reconstruction, bit for bit
+    Wd = oracle.pot_dequant(oracle.pack_codes(codes, bits), scales, K, bits, group).view(np.float16)
+    Wd = Wd.astype(np.float64).reshape(N, K // group, group)
+    assert np.array_equal(Wd[~near_threshold], W_lit[~near_threshold])
     sign = (codes >> (bits - 1)).reshape(N, K // group, group)
     assert np.array_equal(sign == 1, W64 < 0)
     # never worse than the naive multiplier b = 1 (i = 100)
