@@ -25,7 +25,13 @@ template <int BITS> struct DequantShape {
     static constexpr int octets = (BITS == 4) ? 2 : 3;
     static constexpr int block = (BITS == 4) ? 512 : 1024;
     static constexpr int xcd_run = (BITS == 3) ? 16 : 0;     // 0: workgroups take the pieces in launch order
+    // how the output is stored: streaming and written through at system scope, all stores of a lane after
+    // all its loads (store_streaming), or streaming only, scheduled by the compiler (its non-temporal
+    // store).  Same-process A/B on the 70B layer: at 3 bits the first is 0.8-1.2 % faster (80.1 against
+    // 79.0 % of the HBM peak), at 2 bits 2.5 % slower.
+    static constexpr bool write_through = BITS == 3;
 };
+
 constexpr int kXcds = 8;
 
 // Piece of the output that workgroup `bid` of `nblocks` works on: a bijection of [0, nblocks).
@@ -61,22 +67,60 @@ __device__ __forceinline__ void dequant_block(const uint32_t *__restrict__ codes
     const int64_t o0 = base + (lane >> 4) * (16 * kOctetsPerLane) + (lane & 15);
     const int octet_shift = group_shift - 3;   // octets per group = group / 8
 
+    if constexpr (!DequantShape<BITS>::write_through) {
+        // the compiler hoists the loads of all steps ahead of the first store and paces the stores
+        // between the decodes; written any other way this shape loses up to 10 points at 2 bits
 #pragma unroll
-    for (int j = 0; j < kOctetsPerLane; ++j) {
-        const int64_t o = o0 + 16 * j;
-        if (o < n_octets) {
-            const uint32_t f = load_octet_bits<BITS>(codes, o);
-            const int64_t g = o >> octet_shift;
-            const uint32_t s = scales[g];
-            u32x4 w;
-            if (IS_INT) {
-                const _Float16 S = __builtin_bit_cast(_Float16, (uint16_t)s);
-                const _Float16 Z = __builtin_bit_cast(_Float16, zeros[g]) - (_Float16)1024.0f;
-                w = int_octet<BITS>(f, half2_t{Z, Z}, half2_t{S, S});
-            } else {
-                w = pot_octet<BITS>(f, s);
+        for (int j = 0; j < kOctetsPerLane; ++j) {
+            const int64_t o = o0 + 16 * j;
+            if (o < n_octets) {
+                const uint32_t f = load_octet_bits<BITS>(codes, o);
+                const int64_t g = o >> octet_shift;
+                const uint32_t s = scales[g];
+                u32x4 w;
+                if (IS_INT) {
+                    const _Float16 S = __builtin_bit_cast(_Float16, (uint16_t)s);
+                    const _Float16 Z = __builtin_bit_cast(_Float16, zeros[g]) - (_Float16)1024.0f;
+                    w = int_octet<BITS>(f, half2_t{Z, Z}, half2_t{S, S});
+                } else {
+                    w = pot_octet<BITS>(f, s);
+                }
+                __builtin_nontemporal_store(w, &out[o]);   // the output is not read again by this pass
             }
-            __builtin_nontemporal_store(w, &out[o]);   // the output is not read again by this pass
+        }
+    } else {
+        // All loads first, then decode, then the stores (inline asm: the compiler does not move
+        // loads across them).  A wavefront that lies wholly inside the matrix -- all but the last
+        // one -- runs without any per-lane condition; in the last one an octet past the end
+        // re-reads the last octet (valid memory) and stores nothing.
+        const bool whole = base + kOctetsPerWave <= n_octets;     // wavefront-uniform
+        uint32_t f[kOctetsPerLane], s[kOctetsPerLane], z[kOctetsPerLane];
+#pragma unroll
+        for (int j = 0; j < kOctetsPerLane; ++j) {
+            const int64_t o = whole ? o0 + 16 * j : min(o0 + 16 * j, n_octets - 1);
+            f[j] = load_octet_bits<BITS>(codes, o);
+            const int64_t g = o >> octet_shift;
+            s[j] = scales[g];
+            z[j] = IS_INT ? (uint32_t)zeros[g] : 0u;
+        }
+        u32x4 w[kOctetsPerLane];
+#pragma unroll
+        for (int j = 0; j < kOctetsPerLane; ++j) {
+            if (IS_INT) {
+                const _Float16 S = __builtin_bit_cast(_Float16, (uint16_t)s[j]);
+                const _Float16 Z = __builtin_bit_cast(_Float16, (uint16_t)z[j]) - (_Float16)1024.0f;
+                w[j] = int_octet<BITS>(f[j], half2_t{Z, Z}, half2_t{S, S});
+            } else {
+                w[j] = pot_octet<BITS>(f[j], s[j]);
+            }
+        }
+        if (whole) {
+#pragma unroll
+            for (int j = 0; j < kOctetsPerLane; ++j) store_streaming(&out[o0 + 16 * j], w[j]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < kOctetsPerLane; ++j)
+                if (o0 + 16 * j < n_octets) store_streaming(&out[o0 + 16 * j], w[j]);
         }
     }
 }

@@ -41,6 +41,21 @@ __device__ __forceinline__ uint32_t as_u32(half2_t v)
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// A 16-byte store of output that the pass does not read again: marked streaming (nt) and written
+// through at system scope (sc0 sc1) instead of resting in the L2 until it is evicted.  On the
+// 70B-sized de-quantisation pass the three bits together measured 2 % faster than nt alone (what
+// __builtin_nontemporal_store emits) and 7 % faster than a plain store.  The compiler does not
+// count the store in its s_waitcnt bookkeeping, which can only make a later wait longer (the
+// counter is in order); the hardware waits for outstanding stores when the wavefront ends.
+// Nor does it know the hazard of a store of more than 8 bytes whose data registers the next
+// vector instruction overwrites before they have been read: the s_nop covers the two wait
+// states that needs.  No "memory" clobber: the pointee is output that the kernel never reads,
+// and the clobber would keep the loads of later steps from being issued ahead of the store.
+__device__ __forceinline__ void store_streaming(u32x4 *p, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v));
+}
+
 // ---------------------------------------------------------------------------
 // Private bit map of POTQ_LAYOUT_TILE16.
 //
