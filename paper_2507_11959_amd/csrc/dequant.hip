@@ -138,13 +138,23 @@ __global__ __launch_bounds__(DequantShape<BITS>::block) void dequant_kernel(
 // (about 1.5 us here) during which HBM idles, so the matrices of a decoder
 // layer are best done together.  The descriptor table travels as a kernel argument.
 constexpr int kMaxBatch = 16;
+// The time between the start of a workgroup and its first load shows in the throughput of this
+// pass (512 idle cycles there cost 11 %), so the table is laid out for two rounds of scalar
+// loads: the starts of all matrices in one block at the head (slots from `count` on hold the
+// total, so they never count), then one 64-byte descriptor per matrix, fetched whole.
+struct DequantEntry {
+    const uint32_t *codes;
+    const uint16_t *scales;
+    const uint16_t *zeros;
+    u32x4 *out;
+    int64_t n_octets;
+    uint32_t first_block;     // workgroups of the launch that come before this matrix
+    uint32_t pad[5];
+};
+static_assert(sizeof(DequantEntry) == 64, "one descriptor = one 64-byte scalar load");
 struct DequantBatch {
-    const uint32_t *codes[kMaxBatch];
-    const uint16_t *scales[kMaxBatch];
-    const uint16_t *zeros[kMaxBatch];
-    u32x4 *out[kMaxBatch];
-    int64_t n_octets[kMaxBatch];
-    uint32_t first_block[kMaxBatch + 1];   // prefix sum of workgroups per matrix
+    uint32_t below[kMaxBatch];       // below[k] = first_block of matrix k minus one; the total minus one from `count` on
+    DequantEntry entry[kMaxBatch];
     int count;
 };
 
@@ -153,10 +163,21 @@ __global__ __launch_bounds__(DequantShape<BITS>::block) void dequant_batch_kerne
 {
     // the pieces of all matrices form one sequence, renumbered as a whole
     const uint32_t piece = (uint32_t)xcd_piece<DequantShape<BITS>::xcd_run>(blockIdx.x, gridDim.x);
-    int i = 0;
-    while (i + 1 < batch.count && piece >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
-    dequant_block<BITS, IS_INT>(batch.codes[i], batch.scales[i], batch.zeros[i], batch.out[i], batch.n_octets[i],
-                                group_shift, piece - batch.first_block[i]);
+    // Matrices that start at or before this piece, less one.  Workgroup counts stay below 2^31,
+    // so the top bit of below[k] - piece says piece >= first_block[k]; written as arithmetic so
+    // that it stays on the scalar unit.
+    uint32_t i = 0;
+#pragma unroll
+    for (int k = 1; k < 8; ++k) i += (batch.below[k] - piece) >> 31;
+    if (batch.count > 8) {
+#pragma unroll
+        for (int k = 8; k < kMaxBatch; ++k) i += (batch.below[k] - piece) >> 31;
+    }
+    const DequantEntry e = batch.entry[i];
+    // all fields in one round: left alone, the compiler fetches the pointers only after the
+    // bounds test on n_octets, a third dependent round
+    asm volatile("" : : "s"(e.codes), "s"(e.scales), "s"(e.zeros), "s"(e.out), "s"(e.n_octets), "s"(e.first_block), "s"(group_shift));
+    dequant_block<BITS, IS_INT>(e.codes, e.scales, e.zeros, e.out, e.n_octets, group_shift, piece - e.first_block);
 }
 
 static int dequant_block_threads(int bits) { return bits == 4 ? DequantShape<4>::block : DequantShape<2>::block; }
@@ -212,20 +233,22 @@ hipError_t run_dequant_batch(bool is_int, int count, const void *const *codes, c
             order[j - 1] = t;
         }
     DequantBatch b;
+    b.count = count;
     uint64_t blocks = 0;
     for (int i = 0; i < kMaxBatch; ++i) {
         const bool live = i < count;
         const int k = live ? order[i] : 0;
-        b.codes[i] = live ? (const uint32_t *)codes[k] : nullptr;
-        b.scales[i] = live ? (const uint16_t *)scales[k] : nullptr;
-        b.zeros[i] = (live && is_int) ? (const uint16_t *)zeros[k] : nullptr;
-        b.out[i] = live ? (u32x4 *)out[k] : nullptr;
-        b.n_octets[i] = live ? N[k] * K[k] / 8 : 0;
-        b.first_block[i] = (uint32_t)blocks;
-        if (live) blocks += (uint64_t)dequant_blocks(b.n_octets[i], bits);
+        DequantEntry &e = b.entry[i];
+        e.codes = live ? (const uint32_t *)codes[k] : nullptr;
+        e.scales = live ? (const uint16_t *)scales[k] : nullptr;
+        e.zeros = (live && is_int) ? (const uint16_t *)zeros[k] : nullptr;
+        e.out = live ? (u32x4 *)out[k] : nullptr;
+        e.n_octets = live ? N[k] * K[k] / 8 : 0;
+        e.first_block = (uint32_t)blocks;
+        for (uint32_t &p : e.pad) p = 0;
+        b.below[i] = (uint32_t)blocks - 1u;
+        if (live) blocks += (uint64_t)dequant_blocks(e.n_octets, bits);
     }
-    b.first_block[kMaxBatch] = (uint32_t)blocks;
-    b.count = count;
     if (blocks == 0) return hipSuccess;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const int group_shift = (group == 128) ? 7 : 6;

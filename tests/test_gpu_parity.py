@@ -83,6 +83,26 @@ def test_dequant_batch_equals_single_calls_and_oracle(potq, bits, is_int):
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("count", [8, 9, 16])
+def test_dequant_batch_full_table(potq, bits, count):
+    # up to the largest batch the table holds: equal sizes, empties between them, one-workgroup
+    # and many-workgroup matrices, so that every slot of the lookup decides some piece
+    base = [(24, 4096), (0, 128), (3, 128), (24, 4096), (200, 2048), (1, 256), (0, 512), (65, 1152),
+            (24, 4096), (7, 128), (0, 128), (130, 4096), (2, 11008), (24, 4096), (1, 128), (33, 640)]
+    shapes = base[:count]
+    G = 128
+    mats, wants = [], []
+    for i, (N, K) in enumerate(shapes):
+        packed = workloads.packed_codes(53 * i + bits, N, K, bits)
+        S = workloads.pot_scales(59 * i + bits, N, K, G)
+        wants.append(oracle.pot_dequant(packed, S, K, bits, G, nthreads=4))
+        mats.append((dev(packed), dev(S), torch.full((N, K), 7.0, dtype=torch.float16, device="cuda:0"), K))
+    potq.pot_dequant_batch(mats, bits, G)
+    for m, want in zip(mats, wants):
+        assert np.array_equal(host_bits(m[-2]), want)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_pot_dequant_structured_pattern(potq, bits):
     # code(n,k) = (n + k) mod 2^b, scale(n,g) = 2^((n+g) mod 8 - 8): index mix-ups change the output
     N, K, G = 40, 1024, 128
