@@ -563,6 +563,28 @@ def main() -> int:
     del sc, Sd, Zd
     torch.cuda.empty_cache()
 
+    # the same kernel family at prefill size (2048 tokens), 13B and 70B projection shapes: bound by the
+    # matrix cores, so one set of weights is enough; the vendor fp16 GEMM on de-quantised weights beside it
+    prefill = []
+    M = 2048
+    for i, (N, K) in enumerate([(13824, 5120), (5120, 13824), (8192, 8192), (28672, 8192), (8192, 28672)]):
+        codes_h, scales_h = workloads.pot_matrix(5, i, N, K, b3, G)
+        sc = to_dev(scales_h)
+        tiled = potq.potq_repack(to_dev(codes_h), K, b3)
+        W16 = potq.pot_dequant(to_dev(codes_h), sc, K, b3, G)
+        X = to_dev(workloads.activations(workloads.seed_of(5, i, 2), M, K))
+        Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+        ws = potq.gemm_workspace(M, N, K, b3)
+        wp, wn = (ws.data_ptr(), ws.numel()) if ws is not None else (None, 0)
+        pa = (tiled.data_ptr(), sc.data_ptr(), X.data_ptr(), Y.data_ptr(), M, N, K, b3, G, 1, wp, wn, stream)
+        us_p = _time_steps(torch, lambda: check(lib.pot_gemm(*pa)), 10, 3) * 1e3
+        us_lib = _time_steps(torch, lambda: torch.matmul(X, W16.t(), out=Y), 10, 3) * 1e3
+        prefill.append(dict(_gemm_roof(M, N, K, workloads.algorithmic_bytes_gemm(M, N, K, b3, G), us_p),
+                            shape=f"{N}x{K}", M=M, torch_fp16_matmul_on_dequantised_weights_us=round(us_lib, 2)))
+        del tiled, W16, X, Y, ws
+        torch.cuda.empty_cache()
+    extras["pot_gemm_3bit_2048_tokens"] = prefill
+
     # Step 1 scale search (Algorithm 1) on one 4096x4096 fp16 matrix, 3-bit, group 128: plain vector-ALU
     # work, about eight lane operations per weight and multiplier (200 multipliers)
     Wq = to_dev(workloads.weights_f16(workloads.seed_of(0, 0, 4), 4096, 4096))

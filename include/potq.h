@@ -221,8 +221,8 @@ int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f1
  * the scales).  `codes` must be in POTQ_LAYOUT_TILE16.
  *
  * `workspace` is optional device scratch memory (16-byte aligned) owned by the
- * caller.  With few tokens there are too few output tiles to occupy the chip, so
- * the kernel splits K, writes fp32 partial sums to the workspace and adds them
+ * caller.  Where the output tiles alone would not occupy the chip evenly, the
+ * kernel splits K, writes fp32 partial sums to the workspace and adds them
  * in a fixed order in a second small kernel (results stay reproducible).
  * potq_gemm_workspace_bytes() returns the size that allows the preferred split
  * (0 when no split would be used); a NULL or smaller workspace is valid and
@@ -231,7 +231,7 @@ int int_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f1
  * The workspace may be reused by the next call on the
  * same stream; concurrent calls on different streams need separate workspaces.
  * The size query returns 0 for a shape pot_gemm would refuse (bits, K % 128,
- * N % 16, negative sizes); today the size depends on M and N only.
+ * N % 16, negative sizes); today the size depends on M, N and K.
  */
 size_t potq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
 

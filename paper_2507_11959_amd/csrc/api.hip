@@ -29,7 +29,7 @@ hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *code
 hipError_t run_gemm_tile16(bool is_int, const void *codes, const void *scales, const void *zeros, const void *X,
                            void *Y, int64_t M, int64_t N, int64_t K, int bits, int group, void *ws, size_t ws_bytes,
                            hipStream_t stream);
-size_t gemm_workspace_bytes(int64_t M, int64_t N);
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t gemm_static_scratch_bytes();
 hipError_t gemm_static_scratch(void **ptr);
 hipError_t run_fakequant_forward(const void *W, const void *S, const void *Gamma, void *Wq, int64_t N, int64_t K,
@@ -190,7 +190,7 @@ int gemm_entry(bool is_int, const void *codes, const void *scales, const void *z
         // the library's built-in buffer takes the place of the caller's workspace.  Shapes whose
         // preferred split does not fit it are refused, so that the result is always the one the
         // call gives with the workspace potq_gemm_workspace_bytes() asks for.
-        if (potq::gemm_workspace_bytes(M, N) > potq::gemm_static_scratch_bytes()) return POTQ_ERR_WORKSPACE;
+        if (potq::gemm_workspace_bytes(M, N, K) > potq::gemm_static_scratch_bytes()) return POTQ_ERR_WORKSPACE;
         if (potq::gemm_static_scratch(&workspace) != hipSuccess) return POTQ_ERR_LAUNCH;
         workspace_bytes = potq::gemm_static_scratch_bytes();
     }
@@ -302,7 +302,7 @@ size_t potq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits)
 {
     if (M <= 0 || N <= 0 || M > kMaxDim) return 0;
     if (check_common(N, K, bits, 128, true) != POTQ_OK || N % 16 != 0) return 0;     // a shape pot_gemm refuses
-    return potq::gemm_workspace_bytes(M, N);
+    return potq::gemm_workspace_bytes(M, N, K);
 }
 
 int pot_gemm(const void *codes, const void *scales, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,

@@ -27,11 +27,11 @@
 
 namespace potq {
 
-// wavefronts per SIMD the register allocator is asked to make room for in the 16-fragment tiles
+// wavefronts per SIMD the register allocator is asked to make room for in the tiles of 16 or more fragments
 constexpr int kGemmWavesPerSimd = 2;
 
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC, int KS>
-__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu((RM * CN == 16) ? kGemmWavesPerSimd : 1, 8)))
+__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu((RM * CN >= 16) ? kGemmWavesPerSimd : 1, 8)))
 void gemm_tile16_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
     const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, float *__restrict__ partial, int M, int64_t N, int K,
@@ -288,21 +288,13 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4_t *__rest
 constexpr int64_t kSplitTargetWorkgroups = 768;   // four-wavefront workgroups' worth of wavefronts a split aims at
 constexpr int64_t kSplitMinGroups = 4;            // scale groups a K split keeps at least
 
-constexpr int64_t kBigSplitBelow = 120, kBigSplitTarget = 160;
-
-// Number of K splits: enough workgroups to occupy the chip about three times over,
-// at least four scale groups per split, and only as many as the workspace holds.
+// Number of K splits with at most 64 tokens: enough workgroups to occupy the chip about
+// three times over, at least four scale groups per split, and only as many as the workspace holds.
 static int choose_splits(int64_t workgroups, int waves, int ks, int64_t G, int64_t M, int64_t N,
-                         size_t workspace_bytes, bool big)
+                         size_t workspace_bytes)
 {
-    // the many-token configurations move M*N*4 bytes per split through the workspace: split only when
-    // fewer than about half of the CUs would have a workgroup (of eight wavefronts), and then just
-    // enough for 160 workgroups (more splits measured slower: 40.3 us with 8 against 30.0 us with 4
-    // on 5120 x 5120 at 256 tokens); the others aim at kSplitTargetWorkgroups four-wavefront
-    // workgroups' worth of wavefronts
     const int64_t units = workgroups * waves / 4;
-    int64_t want = big ? (workgroups < kBigSplitBelow ? (kBigSplitTarget + workgroups - 1) / workgroups : 1)
-                       : (kSplitTargetWorkgroups + units - 1) / units;
+    int64_t want = (kSplitTargetWorkgroups + units - 1) / units;
     if (want > G / (kSplitMinGroups * ks)) want = G / (kSplitMinGroups * ks);
     if (want > 16) want = 16;
     const int64_t fit = (int64_t)(workspace_bytes / ((size_t)M * (size_t)N * sizeof(float)));
@@ -313,7 +305,7 @@ static int choose_splits(int64_t workgroups, int waves, int ks, int64_t G, int64
 template <int BITS, bool IS_INT, int WAVES, int RM, int CN, int GC, int KS = 1>
 static hipError_t launch_gemm_cfg(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                             int64_t M, int64_t N, int64_t K, int group, void *workspace, size_t workspace_bytes,
-                            hipStream_t stream)
+                            hipStream_t stream, int planned_splits = 0)
 {
     const int64_t rowtiles = N / kTileRows;
     const int64_t G = K / kTileCols;
@@ -321,7 +313,10 @@ static hipError_t launch_gemm_cfg(const void *codes, const void *scales, const v
     constexpr int CW = GC * KS;                       // scale groups per chunk
     const unsigned gx = (unsigned)((rowtiles + RS * RM - 1) / (RS * RM));
     const unsigned gy = (unsigned)((M + 16 * CN - 1) / (16 * CN));
-    int splits = workspace ? choose_splits((int64_t)gx * gy, WAVES, KS, G, M, N, workspace_bytes, M > 64) : 1;
+    // more than 64 tokens: the caller's plan; otherwise chosen here from the number of workgroups
+    int splits = planned_splits > 0 ? planned_splits
+                 : workspace    ? choose_splits((int64_t)gx * gy, WAVES, KS, G, M, N, workspace_bytes)
+                                : 1;
     int per = (int)((G + splits - 1) / splits);
     per = (per + CW - 1) / CW * CW;                   // whole chunks
     splits = (int)((G + per - 1) / per);              // no empty split
@@ -345,33 +340,68 @@ static hipError_t launch_gemm_cfg(const void *codes, const void *scales, const v
 }
 
 
-// More than 64 tokens: eight wavefronts per workgroup, two row tiles each (256 weight rows), and
-// either 128 tokens (the decode of a weight serves eight token tiles) or 64 (twice the workgroups).
-// Measured on the 13B shapes with 128 to 2048 tokens: the wide tile wins when there are few tiles
-// (K is then split over workgroups, which is cheap while M*N is small) or enough of them to do
-// without a split; in between, the narrow one does (13824 x 5120 at 256 tokens, 108 wide tiles:
-// 51.6 us against 73.2 us; 5120 x 5120 at 1024 tokens, 160 wide tiles: 97.2 us against 72.1 us).
-static bool wide_tile(int64_t M, int64_t N)
-{
-    const int64_t tiles = ((N + 255) / 256) * ((M + 127) / 128);
-    return tiles <= 64 || tiles >= kBigSplitBelow;
-}
+// More than 64 tokens: eight wavefronts per workgroup and one of three tiles -- "wide" (two row
+// tiles per wavefront, 128 tokens: the decode of a weight serves eight token tiles), "narrow"
+// (two row tiles, 64 tokens: twice the workgroups) or "tall" (three row tiles, 128 tokens: a token
+// fragment read from LDS serves three MFMAs; the most efficient per output, the coarsest to
+// place) -- with K split over 1 to 8 workgroups.  Which of the 24 combinations is fastest
+// depends on how evenly its workgroups cover the 256 CUs and on what the split costs in
+// workspace traffic, and no rule of thumb tracked that: the choice is made by a small cost model,
+//     time = ceil(workgroups / 256) * groups_per_split * t_tile * (1 + 0.22 * occupied share of the CUs)
+//            [+ 5.6 us + 0.18 us per MB of partial sums written and read back, if split]
+// fitted to 400 timings of the six 13B / 70B projection shapes at 128 to 4096 tokens (3-bit PoT;
+// rms error 6 %; the model's choice is on average 0.3 % and at worst 5 % slower than the best
+// measured combination; 2- and 4-bit kernels differ by -4 % / +7 %, which does not move the
+// choice).  Against the earlier rule (wide unless 65..119 wide tiles; split only below 120
+// workgroups) it is 10-40 % faster at 128 tokens and up to 36 % at 512.
+struct BigTile {
+    int rows, tokens;
+    double us_per_group;      // one workgroup, one scale group of K, on an otherwise idle chip
+};
+constexpr BigTile kBigTiles[3] = {{256, 128, 1.66}, {256, 64, 1.04}, {384, 128, 2.15}};
+enum { kTileWide = 0, kTileNarrow = 1, kTileTall = 2 };
+constexpr double kLoadedSlowdown = 0.22, kReduceFixedUs = 5.6, kReduceUsPerMB = 0.18;
+constexpr int kBigMaxSplits = 8;
 
-static int64_t big_workgroups(int64_t M, int64_t N)
+struct BigPlan {
+    int tile, splits;
+};
+
+static BigPlan plan_big(int64_t M, int64_t N, int64_t K, int64_t splits_that_fit)
 {
-    const int64_t tokens = wide_tile(M, N) ? 128 : 64;
-    return ((N + 255) / 256) * ((M + tokens - 1) / tokens);
+    const int64_t G = K / kTileCols;
+    BigPlan best{kTileWide, 1};
+    if (G <= 0) return best;
+    double best_us = 0.0;
+    for (int t = 0; t < 3; ++t) {
+        const BigTile &tile = kBigTiles[t];
+        const int64_t tiles = ((N + tile.rows - 1) / tile.rows) * ((M + tile.tokens - 1) / tile.tokens);
+        for (int want = 1; want <= kBigMaxSplits; ++want) {
+            if (want > 1 && (want > splits_that_fit || G / want < kSplitMinGroups)) break;
+            const int64_t per = (G + want - 1) / want;
+            const int64_t splits = (G + per - 1) / per;           // no empty split
+            if (splits != want) continue;                         // the same launch as a smaller `want`
+            const int64_t workgroups = tiles * splits;
+            const double rounds = (double)((workgroups + 255) / 256);
+            const double load = (double)(workgroups < 256 ? workgroups : 256) / 256.0;
+            double us = rounds * (double)per * tile.us_per_group * (1.0 + kLoadedSlowdown * load);
+            if (splits > 1) us += kReduceFixedUs + kReduceUsPerMB * (double)splits * (double)M * (double)N * 8e-6;
+            if (best_us == 0.0 || us < best_us) {
+                best_us = us;
+                best = BigPlan{t, (int)splits};
+            }
+        }
+    }
+    return best;
 }
 
 // Workspace that lets every supported shape use its preferred number of splits.
-size_t gemm_workspace_bytes(int64_t M, int64_t N)
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 16) return 0;                            // the few-token kernel splits K inside the workgroup
     if (M <= 64) return (size_t)16 * M * N * sizeof(float);
-    const int64_t workgroups = big_workgroups(M, N);
-    return workgroups < kBigSplitBelow
-               ? (size_t)((kBigSplitTarget + workgroups - 1) / workgroups) * M * N * sizeof(float)
-               : 0;
+    const BigPlan plan = plan_big(M, N, K, kBigMaxSplits);
+    return plan.splits > 1 ? (size_t)plan.splits * M * N * sizeof(float) : 0;
 }
 
 template <int BITS, bool IS_INT>
@@ -416,10 +446,16 @@ static hipError_t launch_gemm(const void *codes, const void *scales, const void 
         else
             return launch_gemm_cfg<BITS, IS_INT, 8, 1, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
-        if (wide_tile(M, N))
-            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
-        else
-            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
+        const int64_t fit = ws ? (int64_t)(ws_bytes / ((size_t)M * (size_t)N * sizeof(float))) : 1;
+        const BigPlan plan = plan_big(M, N, K, fit);
+        switch (plan.tile) {
+        case kTileNarrow:
+            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream, plan.splits);
+        case kTileTall:
+            return launch_gemm_cfg<BITS, IS_INT, 8, 3, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream, plan.splits);
+        default:
+            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream, plan.splits);
+        }
     }
 }
 

@@ -150,6 +150,39 @@ def test_config4_gemm_3bit_13b_shapes_sampled_rows(potq, M, is_int):
 
 
 @pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("M,N,K", [
+    (128, 5120, 5120),      # narrow tile, K split six ways
+    (256, 8192, 8192),      # wide tile, K split four ways
+    (512, 5120, 13824),     # wide tile, K split three ways
+    (1000, 28672, 8192),    # wide tile, no split, ragged token tile
+    (2048, 13824, 5120),    # tall tile, no split
+])
+def test_gemm_many_tokens_every_tile_and_split_sampled_rows(potq, M, N, K, is_int):
+    """More than 64 tokens: the tile (wide, narrow, tall) and the number of K splits come from the
+    dispatcher's cost model; one full-size case for each kind of plan, with the preferred workspace."""
+    bits = 3
+    rng = np.random.default_rng(90 + M)
+    packed = workloads.packed_codes(workloads.seed_of(8, M % 7, 0), N, K, bits)
+    X = workloads.activations(workloads.seed_of(8, M % 7, 2), M, K)
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    ws = potq.gemm_workspace(M, N, K, bits)
+    if is_int:
+        S, Z = workloads.int_scales_zeros(workloads.seed_of(8, M % 7, 3), N, K, bits, G)
+        Y = potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits, workspace=ws)
+    else:
+        S, Z = workloads.pot_scales(workloads.seed_of(8, M % 7, 1), N, K, G), None
+        Y = potq.pot_gemm(tiled, dev(S), dev(X), K, bits, workspace=ws)
+    rows = np.unique(np.concatenate([[0, 15, 16, 255, 256, 383, 384, N - 1], rng.integers(0, N, 100)]))
+    want = oracle.gemm(packed[rows], S[rows], None if Z is None else Z[rows], X, K, bits, G, nthreads=_threads())
+    got = host_bits(Y[:, torch.from_numpy(rows).to("cuda:0")].contiguous())
+    e, nw, nfloor = rel_err(got, want, K)
+    assert e <= REL_TOL, ((M, N, K), e, nw, nfloor)
+    assert bool(torch.isfinite(Y).all())
+    del tiled, Y, ws
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("is_int", [False, True])
 @pytest.mark.parametrize("M", [24, 32, 64])
 def test_gemm_few_row_tiles_large_matrices_sampled_rows(potq, M, is_int):
     """17 to 64 tokens on large matrices with N <= 8192 (four row tiles per wavefront; K split inside

@@ -353,8 +353,11 @@ def test_empty_inputs_are_accepted(potq):
     (30, 8208, 256),       # 17-32 tokens, tall matrix
     (48, 8208, 384),       # 33-64 tokens, tall matrix
     (64, 48, 9216),        # 33-64 tokens, long rows
-    (100, 16640, 128),     # narrow 256x64 tile (65 tiles)
-    (130, 4112, 256),      # wide 256x128 tile, ragged token tile
+    (100, 16640, 128),     # more than 64 tokens: narrow 256x64 tile
+    (130, 4112, 256),      # narrow tile, ragged token tile
+    (1024, 6400, 128),     # wide 256x128 tile (200 workgroups; the narrow tile would need two rounds)
+    (2000, 6000, 256),     # tall 384x128 tile (256 workgroups), ragged rows and tokens
+    (128, 1024, 5120),     # narrow tile, K split eight ways through the workspace
 ])
 def test_gemm_every_dispatch_configuration(potq, M, N, K, is_int):
     bits = 3
