@@ -41,7 +41,7 @@ RAMP_UP = 100                   # untimed launches before the timed region (the 
 # HBM bytes per launch of the headline kernel by code width, from rocprofv3 FETCH_SIZE (x 2.000) + WRITE_SIZE
 # (x 1.000), factors calibrated on a 256 MiB copy: measured once with the commands in the file named here, not
 # re-measured by this script
-PROFILED_TRAFFIC = {"bytes_per_launch": {2: 1938657618, 3: 2045654589},
+PROFILED_TRAFFIC = {"bytes_per_launch": {2: 1938671360, 3: 2045564477},
                     "source": "profiles/pot_dequant_batch_llama70b_layer.md"}
 
 
