@@ -154,14 +154,8 @@ void gemm_tile16_kernel(
         }
     };
 
-    auto process = [&](int stage, int g0) {
-        u32x4 *buf = smem + stage * (CW * 16 * MT);
-#pragma unroll
-        for (int i = 0; i < PPT; ++i) buf[xslot[i]] = xreg[kXStages == 2 ? stage : 0][i] & xmask[i];
-        __syncthreads();    // this buffer was last read two chunks ago, before the previous barrier
-        fetch_x(kXStages == 2 ? stage : 0, g0 + kXStages * CW);
-
-        uint32_t w[GC][RM][BITS], s[GC][RM], z[GC][RM];
+    // Hands lane (r, q) the words and scales of chunk g0 that `stage` holds in memory order.
+    auto permute_w = [&](int stage, int g0, uint32_t (&w)[GC][RM][BITS], uint32_t (&s)[GC][RM], uint32_t (&z)[GC][RM]) {
 #pragma unroll
         for (int gi = 0; gi < GC; ++gi) {
             const int gc = min(g0 + kpart * GC + gi, g_end - 1);
@@ -175,7 +169,42 @@ void gemm_tile16_kernel(
                 z[gi][rm] = IS_INT ? (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)zr[stage][gi][rm]) : 0u;
             }
         }
-        fetch_w(stage, g0 + 2 * CW);
+    };
+
+    // The big tiles run two wavefronts per SIMD, and the barrier puts both at the start of a chunk
+    // at the same time: whatever a wavefront must wait for there, the matrix pipe waits for too.
+    // So the cross-lane hand-over of a chunk's words happens during the MFMAs of the chunk before
+    // (`wn`, `sn`, `zn` carry the result across the barrier), and inside a chunk the token
+    // fragments of a step are requested from LDS before the MFMAs of the step before are issued.
+    // Both cost registers (15 and 32); they are on where the kernel still fits two wavefronts per
+    // SIMD without spilling: the 2- and 3-bit PoT wide tile (the uniform decoder's two tables and
+    // the 4-bit decoder's sign masks leave no room).
+    constexpr bool kAhead = CN == 8 && RM == 2 && GC == 1 && !IS_INT && BITS < 4;   // the hand-over
+    constexpr bool kFragAhead = kAhead;                                             // the token fragments
+    uint32_t wn[GC][RM][BITS], sn[GC][RM], zn[GC][RM];
+
+    auto process = [&](int stage, int g0) {
+        u32x4 *buf = smem + stage * (CW * 16 * MT);
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) buf[xslot[i]] = xreg[kXStages == 2 ? stage : 0][i] & xmask[i];
+        __syncthreads();    // this buffer was last read two chunks ago, before the previous barrier
+        fetch_x(kXStages == 2 ? stage : 0, g0 + kXStages * CW);
+
+        uint32_t w[GC][RM][BITS], s[GC][RM], z[GC][RM];
+        if constexpr (kAhead) {
+#pragma unroll
+            for (int gi = 0; gi < GC; ++gi)
+#pragma unroll
+                for (int rm = 0; rm < RM; ++rm) {
+#pragma unroll
+                    for (int j = 0; j < BITS; ++j) w[gi][rm][j] = wn[gi][rm][j];
+                    s[gi][rm] = sn[gi][rm];
+                    z[gi][rm] = zn[gi][rm];
+                }
+        } else {
+            permute_w(stage, g0, w, s, z);
+            fetch_w(stage, g0 + 2 * CW);
+        }
 
 #pragma unroll
         for (int gi = 0; gi < GC; ++gi) {
@@ -187,12 +216,21 @@ void gemm_tile16_kernel(
                 dec[rm].set_group(s[gi][rm], z[gi][rm]);
                 dec[rm].set_block(w[gi][rm]);
             }
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                half8_t b[CN];
+            half8_t b[kFragAhead ? 2 : 1][CN];
+            auto read_b = [&](int st, half8_t (&dst)[CN]) {
 #pragma unroll
                 for (int c = 0; c < CN; ++c)
-                    b[c] = __builtin_bit_cast(half8_t, xb[(st * 4 + q) * MT + 16 * c + ((r + 4 * st) & 15)]);
+                    dst[c] = __builtin_bit_cast(half8_t, xb[(st * 4 + q) * MT + 16 * c + ((r + 4 * st) & 15)]);
+            };
+            if constexpr (kFragAhead) read_b(0, b[0]);
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                half8_t(&bc)[CN] = b[kFragAhead ? (st & 1) : 0];
+                if constexpr (kFragAhead) {
+                    if (st < 3) read_b(st + 1, b[(st + 1) & 1]);
+                } else {
+                    read_b(st, bc);
+                }
 #pragma unroll
                 for (int rm = 0; rm < RM; ++rm) {
                     uint32_t a0, a1, a2, a3;
@@ -202,9 +240,15 @@ void gemm_tile16_kernel(
 #pragma unroll
                     for (int c = 0; c < CN; ++c)
                         acc[(st & (ACCS - 1))][rm][c] =
-                            __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[c], acc[(st & (ACCS - 1))][rm][c], 0, 0, 0);
+                            __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bc[c], acc[(st & (ACCS - 1))][rm][c], 0, 0, 0);
                 }
             }
+        }
+        if constexpr (kAhead) {
+            // the other register stage holds the next chunk's words (requested a chunk ago): hand them
+            // over now, then reuse the stage for the chunk after the one already in flight
+            permute_w(stage ^ 1, g0 + CW, wn, sn, zn);
+            fetch_w(stage ^ 1, g0 + 3 * CW);
         }
     };
 
@@ -212,6 +256,10 @@ void gemm_tile16_kernel(
     if (kXStages == 2) fetch_x(1, g_begin + CW);
     fetch_w(0, g_begin);
     fetch_w(1, g_begin + CW);
+    if constexpr (kAhead) {
+        permute_w(0, g_begin, wn, sn, zn);
+        fetch_w(0, g_begin + 2 * CW);
+    }
     int g = g_begin;
     for (; g + CW < g_end; g += 2 * CW) {
         process(0, g);
@@ -367,13 +415,13 @@ struct BigPlan {
     int tile, splits;
 };
 
-static BigPlan plan_big(int64_t M, int64_t N, int64_t K, int64_t splits_that_fit)
+static BigPlan plan_big(int64_t M, int64_t N, int64_t K, int64_t splits_that_fit, bool tall_allowed)
 {
     const int64_t G = K / kTileCols;
     BigPlan best{kTileWide, 1};
     if (G <= 0) return best;
     double best_us = 0.0;
-    for (int t = 0; t < 3; ++t) {
+    for (int t = 0; t < (tall_allowed ? 3 : 2); ++t) {
         const BigTile &tile = kBigTiles[t];
         const int64_t tiles = ((N + tile.rows - 1) / tile.rows) * ((M + tile.tokens - 1) / tile.tokens);
         for (int want = 1; want <= kBigMaxSplits; ++want) {
@@ -400,8 +448,11 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 16) return 0;                            // the few-token kernel splits K inside the workgroup
     if (M <= 64) return (size_t)16 * M * N * sizeof(float);
-    const BigPlan plan = plan_big(M, N, K, kBigMaxSplits);
-    return plan.splits > 1 ? (size_t)plan.splits * M * N * sizeof(float) : 0;
+    // enough for the plan with the tall tile (PoT) and for the one without it (uniform baseline)
+    const int with_tall = plan_big(M, N, K, kBigMaxSplits, true).splits;
+    const int without = plan_big(M, N, K, kBigMaxSplits, false).splits;
+    const int splits = with_tall > without ? with_tall : without;
+    return splits > 1 ? (size_t)splits * M * N * sizeof(float) : 0;
 }
 
 template <int BITS, bool IS_INT>
@@ -447,15 +498,16 @@ static hipError_t launch_gemm(const void *codes, const void *scales, const void 
             return launch_gemm_cfg<BITS, IS_INT, 8, 1, 4, 1, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream);
     } else {
         const int64_t fit = ws ? (int64_t)(ws_bytes / ((size_t)M * (size_t)N * sizeof(float))) : 1;
-        const BigPlan plan = plan_big(M, N, K, fit);
-        switch (plan.tile) {
-        case kTileNarrow:
-            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream, plan.splits);
-        case kTileTall:
-            return launch_gemm_cfg<BITS, IS_INT, 8, 3, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream, plan.splits);
-        default:
-            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream, plan.splits);
+        // the uniform decoder (two look-up tables per group) does not fit the tall tile's registers
+        // (it spills and runs at half speed), so its plans are made without that tile
+        const BigPlan plan = plan_big(M, N, K, fit, !IS_INT);
+        if constexpr (!IS_INT) {
+            if (plan.tile == kTileTall)
+                return launch_gemm_cfg<BITS, IS_INT, 8, 3, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream, plan.splits);
         }
+        if (plan.tile == kTileNarrow)
+            return launch_gemm_cfg<BITS, IS_INT, 8, 2, 4, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream, plan.splits);
+        return launch_gemm_cfg<BITS, IS_INT, 8, 2, 8, 1>(codes, scales, zeros, X, Y, M, N, K, group, ws, ws_bytes, stream, plan.splits);
     }
 }
 
