@@ -82,15 +82,17 @@ void gemm_tile16_kernel(
     }
     const int word_owner = (4 * r + q) * 4;           // ds_bpermute byte address of the lane holding word 4r + q
 
-    // X side: this thread's pieces of a chunk (16 tokens x 4 consecutive 8-value runs per wavefront)
-    const uint16_t *xsrc[PPT];
-    int xslot[PPT], xgrp[PPT];
-    bool xok[PPT];
+    // X side: this thread's pieces of a chunk (16 tokens x 4 consecutive 8-value runs per wavefront).
+    // A thread takes the same PG pieces of every scale group of the chunk, so addresses and LDS
+    // slots are kept for one group only; piece i belongs to group i / PG of the chunk.
+    constexpr int PG = (MT * 16) / THREADS;           // pieces per thread and scale group
+    static_assert((MT * 16) % THREADS == 0 && PPT == PG * CW, "a group's pieces must divide evenly over the workgroup");
+    const uint16_t *xsrc[PG];
+    int xslot[PG];
+    bool xok[PG];
 #pragma unroll
-    for (int i = 0; i < PPT; ++i) {
-        const int pc = tid + THREADS * i;             // piece index inside the chunk
-        xgrp[i] = pc / (MT * 16);                     // scale group inside the chunk
-        const int p = pc % (MT * 16);
+    for (int i = 0; i < PG; ++i) {
+        const int p = tid + THREADS * i;              // piece index inside the group
         const int st = p & 3;                         // run inside a 32-column block = MFMA step
         const int blk = p >> 6;
         const int m = ((p >> 2) & 15) + 16 * (blk % CN);   // four consecutive lanes read 64 contiguous bytes
@@ -99,7 +101,7 @@ void gemm_tile16_kernel(
         xsrc[i] = X + (int64_t)(xok[i] ? m0 + m : 0) * K + 32 * qq + 8 * st;
         // rotate the token index inside its 16-token tile by 4*st: the four lanes of a quad (same
         // token, st = 0..3) then write to four different LDS bank groups
-        xslot[i] = xgrp[i] * 16 * MT + (st * 4 + qq) * MT + (m & ~15) + ((m + 4 * st) & 15);
+        xslot[i] = (st * 4 + qq) * MT + (m & ~15) + ((m + 4 * st) & 15);
     }
 
     // with few output tiles per wavefront the MFMAs of one tile form a dependent chain:
@@ -121,15 +123,15 @@ void gemm_tile16_kernel(
     constexpr int kXStages = PPT <= 4 ? 2 : 1;
     uint32_t wr[2][GC][RM][BITS], sr[2][GC][RM], zr[2][GC][RM];
     u32x4 xreg[kXStages][PPT];
-    uint32_t xmask[PPT];
+    uint32_t xmask[PG];
 #pragma unroll
-    for (int i = 0; i < PPT; ++i) xmask[i] = xok[i] ? 0xFFFFFFFFu : 0u;
+    for (int i = 0; i < PG; ++i) xmask[i] = xok[i] ? 0xFFFFFFFFu : 0u;
 
     auto fetch_x = [&](int stage, int g0) {
 #pragma unroll
         for (int i = 0; i < PPT; ++i) {
-            const int gc = min(g0 + xgrp[i], g_end - 1);            // past the end: re-read the last group
-            xreg[stage][i] = *(const u32x4 *)(xsrc[i] + gc * kTileCols);
+            const int gc = min(g0 + i / PG, g_end - 1);             // past the end: re-read the last group
+            xreg[stage][i] = *(const u32x4 *)(xsrc[i % PG] + gc * kTileCols);
         }
     };
     auto fetch_w = [&](int stage, int g0) {
@@ -186,7 +188,8 @@ void gemm_tile16_kernel(
     auto process = [&](int stage, int g0) {
         u32x4 *buf = smem + stage * (CW * 16 * MT);
 #pragma unroll
-        for (int i = 0; i < PPT; ++i) buf[xslot[i]] = xreg[kXStages == 2 ? stage : 0][i] & xmask[i];
+        for (int i = 0; i < PPT; ++i)
+            buf[(i / PG) * 16 * MT + xslot[i % PG]] = xreg[kXStages == 2 ? stage : 0][i] & xmask[i % PG];
         __syncthreads();    // this buffer was last read two chunks ago, before the previous barrier
         fetch_x(kXStages == 2 ? stage : 0, g0 + kXStages * CW);
 
