@@ -403,7 +403,7 @@ static hipError_t launch_gemm_cfg(const void *codes, const void *scales, const v
 // fitted to 400 timings of the six 13B / 70B projection shapes at 128 to 4096 tokens (3-bit PoT;
 // rms error 6 %; the model's choice is on average 0.3 % and at worst 5 % slower than the best
 // measured combination; 2- and 4-bit kernels differ by -4 % / +7 %, which does not move the
-// choice).  Against the earlier rule (wide unless 65..119 wide tiles; split only below 120
+// choice).  Against a rule by tile count alone (wide unless 65..119 wide tiles; split only below 120
 // workgroups) it is 10-40 % faster at 128 tokens and up to 36 % at 512.
 struct BigTile {
     int rows, tokens;
