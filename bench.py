@@ -63,7 +63,7 @@ def _time_steps(torch, step, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
-def _time_pair(torch, step_a, step_b, steps, warmup, reps=3):
+def _time_pair(torch, step_a, step_b, steps, warmup, reps=5):
     """Median milliseconds per call of two alternatives measured alternately (a, b, a, b, ...): the first
     measurement after an idle phase runs a few per cent slow, which a single a-then-b pass would charge to a."""
     ta, tb = [], []
@@ -322,7 +322,7 @@ def main() -> int:
     extras["pot_dequant_7b_layer_2bit"] = dict(_hbm(l7.pot_bytes, ms_p7 * 1e3), int_us=round(ms_i7 * 1e3, 2),
                                                 int_GBps=round(l7.int_bytes / ms_i7 / 1e6, 1),
                                                 pot_speedup_vs_int=round(ms_i7 / ms_p7, 4),
-                                                note="PoT and INT measured alternately, three times each, medians")
+                                                note="PoT and INT measured alternately, five times each, medians")
     one = l7.pot_items[0]
     ms_res = _time_steps(torch, lambda: check(lib.pot_dequant_batch(one, 7, 2, G, stream)), 200, 20)
     extras["pot_dequant_7b_layer_2bit_cache_resident_codes"] = dict(
