@@ -370,6 +370,23 @@ def test_gemm_every_dispatch_configuration(potq, M, N, K, is_int):
         assert e <= REL_TOL, (use_ws, e, nw, nfloor)
 
 
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("M,N,K", [
+    (1900, 6000, 128),     # tall tile (PoT) / wide tile (uniform), ragged rows and tokens
+    (520, 3344, 256),      # wide tile with its prefetches (2-bit PoT), ragged
+])
+def test_gemm_many_token_tiles_other_widths_and_groups(potq, bits, group, M, N, K):
+    """The tiles above 64 tokens at the code widths and the group size the other tests leave out."""
+    for is_int in (False, True):
+        packed, S, Z = _gemv_inputs(3000 + M + bits + group, N, K, bits, is_int, group)
+        X = workloads.activations(3100 + M, M, K)
+        want = oracle.gemm(packed, S, Z, X, K, bits, group, nthreads=8)
+        got = _run_gemm(potq, packed, S, Z, X, K, bits, group=group)
+        e, nw, nfloor = rel_err(got, want, K)
+        assert e <= REL_TOL, (is_int, e, nw, nfloor)
+
+
 @pytest.mark.parametrize("is_int", [False, True])
 @pytest.mark.parametrize("K", [32768, 53248, 76672])
 def test_gemv_rows_beyond_64_kib_of_lds(potq, K, is_int):
