@@ -169,9 +169,13 @@ def test_gemm_many_tokens_every_tile_and_split_sampled_rows(potq, M, N, K, is_in
     if is_int:
         S, Z = workloads.int_scales_zeros(workloads.seed_of(8, M % 7, 3), N, K, bits, G)
         Y = potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits, workspace=ws)
+        again = potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits, workspace=ws)
     else:
         S, Z = workloads.pot_scales(workloads.seed_of(8, M % 7, 1), N, K, G), None
         Y = potq.pot_gemm(tiled, dev(S), dev(X), K, bits, workspace=ws)
+        again = potq.pot_gemm(tiled, dev(S), dev(X), K, bits, workspace=ws)
+    assert torch.equal(Y, again)                      # fixed summation order: bit-identical reruns
+    del again
     rows = np.unique(np.concatenate([[0, 15, 16, 255, 256, 383, 384, N - 1], rng.integers(0, N, 100)]))
     want = oracle.gemm(packed[rows], S[rows], None if Z is None else Z[rows], X, K, bits, G, nthreads=_threads())
     got = host_bits(Y[:, torch.from_numpy(rows).to("cuda:0")].contiguous())
