@@ -161,9 +161,10 @@ int potq_repack(const void *src, void *dst, int64_t N, int64_t K, int bits,
  * Large 2- and 3-bit matrices (potq_gemv_exponent_form() tells which) are served
  * in the exponent form of the product (Sec. 4.2, additivity of exponents):
  *   y[n] = sum_g scale[n,g] * sum_{k in g} (+-2^E[n,k]) x[k],
- * the inner sums in exact integer arithmetic on x in 32-bit fixed point (exact
- * for every x[k] within 2^19 of the largest |x|, rounded to 2^-30 of it below),
- * one fp32 rounding per group.  For scales inside the domain of pot_dequant
+ * the inner sums in exact integer arithmetic on x in 32-bit fixed point, every
+ * group of 128 activations against its own largest exponent (exact for every
+ * x[k] within 2^19 of the largest |x| of its group, rounded to 2^-30 of it
+ * below), one fp32 rounding per group.  For scales inside the domain of pot_dequant
  * this is the same sum; for scales outside it (pot_check_scales() finds them,
  * pot_quantize() never produces them) this form multiplies by 2^E where the
  * other adds into the exponent field, and the results differ.  Activations

@@ -8,17 +8,18 @@
 // look-up per four codes in a table that is the same for every group (no
 // per-group table, no merge with the scale's low byte: the vector ALU, the
 // scarce unit of the fp16 GEMV, does about 40 % less).  The activations are
-// turned, once per workgroup, into 32-bit fixed point against the largest
-// exponent in x and cut into four signed 8-bit digits, x = 2^-k sum_p 256^p d_p;
+// turned, once per workgroup, into 32-bit fixed point -- every scale group
+// against the largest exponent among its own 128 activations -- and cut into
+// four signed 8-bit digits, x = 2^-k sum_p 256^p d_p;
 // digit sums run on the matrix pipe (v_mfma_i32_16x16x64_i8, exact).  The
 // digits of the four groups a wavefront works on sit block-diagonally in the A
 // operand -- row 4q + p holds digit p of the group of lane group q in k-slice q
 // and zeros elsewhere -- so lane (r, q) receives the four digit sums of row r
 // of its own group, recombines them and multiplies by its own scale.
 //
-// Exactness: every fp16 activation within 2^19 of the largest one is
-// represented exactly (smaller ones are rounded to 2^-30 of the largest); the
-// digit sums are exact; one fp32 rounding per group in the recombination and
+// Exactness: every fp16 activation within 2^19 of the largest one of its group
+// is represented exactly (smaller ones are rounded to 2^-30 of that largest
+// one); the digit sums are exact; one fp32 rounding per group in the recombination and
 // one in the accumulation, as many as the fp16 form has per four MFMA steps.
 // The scale must lie in the domain on which the integer add of Sec. 4.2 is the
 // multiplication by 2^E (every scale pot_quantize produces does).
@@ -148,6 +149,18 @@ __device__ __forceinline__ float exp_blocks_plain(const u32x4 (&L)[BITS], const 
     return sum;
 }
 
+// The largest of a value over the 16 lanes of a row (lanes 16j .. 16j+15), in every lane of the
+// row: four data-parallel-primitive steps on the vector ALU (lane pairs, quads, the two quads
+// of a half row, the two half rows), no trip through the LDS crossbar.
+__device__ __forceinline__ uint32_t row_max_u32(uint32_t v)
+{
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true));   // row_half_mirror
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true));   // row_mirror
+    return v;
+}
+
 // Eight fp16 activations (columns 8i .. 8i+7) -> fixed point m = rne(x * 2^k), each m cut into
 // four signed digits (m + 0x00808080 makes the three low bytes excess-128), the digits stored
 // per digit plane in the order the selectors deliver the weights: (c0, c2, c1, c3, c4, c6, c5, c7).
@@ -198,7 +211,8 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
     u32x4 *pieces = smem;                               // [group][digit] runs of kPieceRun uint4
     u32x4 *zero_block = smem + G * 4 * kPieceRun;       // 8 uint4 of zeros
     float *red = (float *)(zero_block + 8);             // 2 x WAVES x 16 partial sums
-    uint32_t *amax_part = (uint32_t *)(red + 2 * WAVES * kTileRows);
+    uint32_t *nonfinite_part = (uint32_t *)(red + 2 * WAVES * kTileRows);   // per wavefront: saw an infinity or NaN
+    float *group_unit = (float *)(nonfinite_part + WAVES);                  // per scale group: 2^-k of its fixed point
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -264,32 +278,42 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
     bool more = advance();
     (void)more;
 
-    // --- activations: largest exponent, then fixed point digits into LDS ---
+    // --- activations: fixed point digits into LDS, every scale group against its own largest exponent ---
+    // The sixteen octets of a group sit in sixteen consecutive lanes, so the group's largest
+    // exponent is four cross-lane steps away and nothing waits for the rest of the vector: one
+    // barrier between the loads of x and the first MFMA (a common exponent for the whole vector
+    // needs a second one, behind a reduction over the workgroup, which cost 5-12 % of the launch
+    // on the 13B to 70B shapes).  |x| < 2^(e-14) with e = max(exponent field, 1): k = 44 - e puts
+    // every |m| below 2^30; the group's sums are in units of 2^-k, kept per group in LDS.
     const int octets = K / 8;
-    u32x4 xv[kExpOctetsPerThread];
-    uint32_t am = 0u;
+    bool saw_nonfinite = false;
 #pragma unroll
     for (int n = 0; n < kExpOctetsPerThread; ++n) {
+        if (n * (WAVES * kWave) >= octets) break;       // uniform: no thread has an octet in this pass
         const int i = tid + n * (WAVES * kWave);
-        xv[n] = i < octets ? x[i] : u32x4{0u, 0u, 0u, 0u};
+        const u32x4 xv = i < octets ? x[i] : u32x4{0u, 0u, 0u, 0u};
+        uint32_t am = 0u;
 #pragma unroll
         for (int w = 0; w < 4; ++w)
             am = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, am),
-                                                                        __builtin_bit_cast(ushort2_t, xv[n][w] & 0x7FFF7FFFu)));
+                                                                        __builtin_bit_cast(ushort2_t, xv[w] & 0x7FFF7FFFu)));
+        am = max(am & 0xFFFFu, am >> 16);
+        am = row_max_u32(am);
+        const int e = max((int)(am >> 10), 1);
+        saw_nonfinite = saw_nonfinite || e == 31;
+        const int k = 44 - e;
+        if (i < octets) {
+            stage_digits(xv, pieces, i, __builtin_bit_cast(float, (uint32_t)(k + 127) << 23));
+            if ((i & 15) == 0) group_unit[i >> 4] = __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
+        }
     }
-    am = max(am & 0xFFFFu, am >> 16);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) am = max(am, (uint32_t)__shfl_xor((int)am, off, kWave));
-    if (lane == 0) amax_part[wave] = am;
+    const bool wave_saw_nonfinite = __builtin_amdgcn_ballot_w64(saw_nonfinite) != 0;
+    if (lane == 0) nonfinite_part[wave] = wave_saw_nonfinite ? 1u : 0u;
     if (tid < 8) zero_block[tid] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
+    uint32_t nonfinite = 0u;
 #pragma unroll
-    for (int p = 0; p < WAVES; ++p) am = max(am, amax_part[p]);
-    // |x| < 2^(e-14) with e = max(exponent field, 1): k = 44 - e puts every |m| below 2^30
-    const int e = max((int)(am >> 10), 1);
-    const int k = 44 - e;
-    const float two_k = __builtin_bit_cast(float, (uint32_t)(k + 127) << 23);
-    const float two_mk = __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
+    for (int p = 0; p < WAVES; ++p) nonfinite |= nonfinite_part[p];
 
     // lane (r, t) holds the groups of lane group t of row r: add the lane groups, then the
     // wavefronts of the slot, in a fixed order.  The buffer alternates between tile sets, so one
@@ -313,7 +337,7 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
 
     // An infinity or NaN among the activations (the same for every workgroup of the launch):
     // plain binary32 products, same tiles, same reduction.
-    if (e == 31) {
+    if (nonfinite) {
         int it = 0;
         for (int64_t q = first; q * SLOTS < rowtiles; q += stride, ++it) {
             float row_sum = 0.f;
@@ -340,13 +364,6 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
         return;
     }
 
-#pragma unroll
-    for (int n = 0; n < kExpOctetsPerThread; ++n) {
-        const int i = tid + n * (WAVES * kWave);
-        if (i < octets) stage_digits(xv[n], pieces, i, two_k);
-    }
-    __syncthreads();
-
     // The A operand: lanes on the block diagonal carry digit (lane % 4) of their own group; the
     // others hold zeros from here on (lds_read_keep never writes them).
     const uint64_t diagonal_lanes = __builtin_amdgcn_ballot_w64((r >> 2) == t);
@@ -371,6 +388,7 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
                 advance();
             }
             const int g = round * kStep + part * 4 + t;
+            const float unit = group_unit[min(g, G - 1)];
             // a lane past the end of the row multiplies the (valid) last group by zeros
             lds_read_keep(xa, g < G ? pieces_at + (uint32_t)((g * 4 + (lane & 3)) * (kPieceRun * 16)) : zeros_at,
                           diagonal_lanes, consumed);
@@ -379,23 +397,24 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
                 int4_t d0{0, 0, 0, 0}, d1{0, 0, 0, 0};
                 exp_blocks<BITS>(L, xa, 0, 2, d0);
                 exp_blocks<BITS>(L, xa, 2, 4, d1);
-                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s & 0xFFFFu)), exp_recombine(d0),
-                                         row_sum);
-                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s >> 16)), exp_recombine(d1),
-                                         row_sum);
+                // scale * 2^-k is exact (a power of two times an fp16, far inside binary32's range)
+                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s & 0xFFFFu)) * unit,
+                                         exp_recombine(d0), row_sum);
+                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s >> 16)) * unit,
+                                         exp_recombine(d1), row_sum);
             } else {
                 const uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)s);
                 lds_wait(xa);
                 int4_t d{0, 0, 0, 0};
                 exp_blocks<BITS>(L, xa, 0, 4, d);
-                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)so), exp_recombine(d), row_sum);
+                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)so) * unit, exp_recombine(d), row_sum);
             }
             consumed = row_sum;
 #pragma unroll
             for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
             s = sn;
         }
-        finish_tiles(q, it, row_sum * two_mk);
+        finish_tiles(q, it, row_sum);
     }
 }
 
@@ -410,7 +429,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_kernel(
 // ---------------------------------------------------------------------------
 // Two to four activation vectors at once (a GEMM with two to four tokens), group size 128:
 // the matrix is decoded once per step and every vector costs one more MFMA per step and its
-// own digit planes in LDS (each vector has its own fixed-point exponent).  Here all lanes read
+// own digit planes in LDS (its own fixed-point exponent per scale group).  Here all lanes read
 // LDS -- the off-diagonal ones a block of zeros -- so the A operands need no registers of their
 // own between steps.  Vectors past `tokens` count as zero.  Results y[m * ystride + n].
 // ---------------------------------------------------------------------------
@@ -427,7 +446,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
     u32x4 *pieces = smem;                               // [vector][group][digit] runs of kPieceRun uint4
     u32x4 *zero_block = smem + MT * G * 4 * kPieceRun;  // 8 uint4 of zeros
     float *red = (float *)(zero_block + 8);             // 2 x WAVES x MT x 16 partial sums
-    uint32_t *amax_part = (uint32_t *)(red + 2 * WAVES * MT * kTileRows);   // WAVES x MT
+    uint32_t *nonfinite_part = (uint32_t *)(red + 2 * WAVES * MT * kTileRows);   // per wavefront: saw an infinity or NaN
+    float *group_unit = (float *)(nonfinite_part + WAVES);                        // [vector][group]: 2^-k of its fixed point
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -470,48 +490,38 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
     fetch(tile_of(fq), fround, true, L, s);
     advance();
 
-    // --- activations: per vector the largest exponent, then fixed point digits into LDS ---
+    // --- activations: fixed point digits into LDS, every scale group of every vector against its
+    // own largest exponent (see gemv_exp_body: the sixteen lanes of a row hold one group) ---
     const int per = K / 8;                              // octets per vector
     const int octets = MT * per;
-    u32x4 xv[kExpOctetsPerThread];
-    int vec[kExpOctetsPerThread];
-    uint32_t am[MT];
-#pragma unroll
-    for (int m = 0; m < MT; ++m) am[m] = 0u;
+    bool saw_nonfinite = false;
 #pragma unroll
     for (int n = 0; n < kExpOctetsPerThread; ++n) {
+        if (n * THREADS >= octets) break;               // uniform: no thread has an octet in this pass
         const int i = tid + n * THREADS;
-        vec[n] = i / per;
-        xv[n] = (i < octets && vec[n] < tokens) ? x[i] : u32x4{0u, 0u, 0u, 0u};
+        const int vec = i / per, o = i - vec * per;     // vector, octet inside the vector
+        const u32x4 xv = (i < octets && vec < tokens) ? x[i] : u32x4{0u, 0u, 0u, 0u};
         uint32_t a = 0u;
 #pragma unroll
         for (int w = 0; w < 4; ++w)
             a = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a),
-                                                                       __builtin_bit_cast(ushort2_t, xv[n][w] & 0x7FFF7FFFu)));
-        a = max(a & 0xFFFFu, a >> 16);
-#pragma unroll
-        for (int m = 0; m < MT; ++m) am[m] = vec[n] == m ? max(am[m], a) : am[m];
+                                                                       __builtin_bit_cast(ushort2_t, xv[w] & 0x7FFF7FFFu)));
+        a = row_max_u32(max(a & 0xFFFFu, a >> 16));
+        const int e = max((int)(a >> 10), 1);
+        saw_nonfinite = saw_nonfinite || e == 31;
+        const int k = 44 - e;
+        if (i < octets) {
+            stage_digits(xv, pieces + vec * G * 4 * kPieceRun, o, __builtin_bit_cast(float, (uint32_t)(k + 127) << 23));
+            if ((o & 15) == 0) group_unit[vec * G + (o >> 4)] = __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
+        }
     }
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) am[m] = max(am[m], (uint32_t)__shfl_xor((int)am[m], off, kWave));
-        if (lane == 0) amax_part[wave * MT + m] = am[m];
-    }
+    const bool wave_saw_nonfinite = __builtin_amdgcn_ballot_w64(saw_nonfinite) != 0;
+    if (lane == 0) nonfinite_part[wave] = wave_saw_nonfinite ? 1u : 0u;
     if (tid < 8) zero_block[tid] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
-    float two_k[MT], two_mk[MT];
-    bool non_finite = false;
+    uint32_t non_finite = 0u;
 #pragma unroll
-    for (int m = 0; m < MT; ++m) {
-#pragma unroll
-        for (int p = 0; p < WAVES; ++p) am[m] = max(am[m], amax_part[p * MT + m]);
-        const int e = max((int)(am[m] >> 10), 1);
-        const int k = 44 - e;
-        non_finite |= e == 31;
-        two_k[m] = __builtin_bit_cast(float, (uint32_t)(k + 127) << 23);
-        two_mk[m] = __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
-    }
+    for (int p = 0; p < WAVES; ++p) non_finite |= nonfinite_part[p];
 
     auto finish_tiles = [&](int64_t q, int it, const float (&row_sum)[MT]) {
         float *red_it = red + (it & 1) * (WAVES * MT * kTileRows);
@@ -564,18 +574,6 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
         return;
     }
 
-#pragma unroll
-    for (int n = 0; n < kExpOctetsPerThread; ++n) {
-        const int i = tid + n * THREADS;
-        if (i < octets) {
-            float scale = two_k[0];
-#pragma unroll
-            for (int m = 1; m < MT; ++m) scale = vec[n] == m ? two_k[m] : scale;
-            stage_digits(xv[n], pieces + vec[n] * G * 4 * kPieceRun, i - vec[n] * per, scale);
-        }
-    }
-    __syncthreads();
-
     const bool diagonal = (r >> 2) == t;
     int it = 0;
     for (int64_t q = first; q * SLOTS < rowtiles; q += stride, ++it) {
@@ -615,13 +613,12 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
             }
             const float sf = (float)__builtin_bit_cast(_Float16, (uint16_t)so);
 #pragma unroll
-            for (int m = 0; m < MT; ++m) row_sum[m] = __builtin_fmaf(sf, exp_recombine(d[m]), row_sum[m]);
+            for (int m = 0; m < MT; ++m)     // scale * 2^-k is exact
+                row_sum[m] = __builtin_fmaf(sf * group_unit[m * G + min(g, G - 1)], exp_recombine(d[m]), row_sum[m]);
 #pragma unroll
             for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
             s = sn;
         }
-#pragma unroll
-        for (int m = 0; m < MT; ++m) row_sum[m] *= two_mk[m];
         finish_tiles(q, it, row_sum);
     }
 }
@@ -652,7 +649,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_batch_kernel(const Exp
 static size_t exp_lds_bytes(int64_t K, int waves)
 {
     return (size_t)(K / kTileCols) * 4 * kPieceRun * 16 + 8 * 16 + 2 * (size_t)waves * kTileRows * sizeof(float) +
-           (size_t)waves * sizeof(uint32_t);
+           (size_t)waves * sizeof(uint32_t) + (size_t)(K / kTileCols) * sizeof(float);
 }
 
 // Workgroups per launch: what the chip holds at once (two per compute unit at this register
@@ -802,7 +799,8 @@ hipError_t run_gemv_exp_batch(int count, const void *const *codes, const void *c
 static size_t exp_multi_lds_bytes(int64_t K, int waves, int mt)
 {
     return (size_t)mt * (K / kTileCols) * 4 * kPieceRun * 16 + 8 * 16 +
-           2 * (size_t)waves * mt * kTileRows * sizeof(float) + (size_t)waves * mt * sizeof(uint32_t);
+           2 * (size_t)waves * mt * kTileRows * sizeof(float) + (size_t)waves * sizeof(uint32_t) +
+           (size_t)mt * (K / kTileCols) * sizeof(float);
 }
 
 // eight wavefronts while two workgroups fit the LDS of a compute unit together, else sixteen

@@ -5,9 +5,10 @@ Checked here, without a GPU and in exact integer arithmetic:
   * inside the scale domain the oracle's de-quantised weights satisfy W~ = +-2^E * s exactly, so
     sum_g s_g * sum_{k in g} (+-2^E) x_k is the very sum the fused GEMV is defined by;
   * outside the domain it is not (the library's header says the two forms differ there);
-  * the fixed-point representation the kernel uses for x: k = 44 - max(exponent field, 1) keeps
-    |x * 2^k| below 2^30, is exact for every element within 2^19 of the largest one, and the
-    signed base-256 digits obtained by adding 0x00808080 reproduce the integer."""
+  * the fixed-point representation the kernel uses for the activations of a scale group:
+    k = 44 - max(largest exponent field of the group, 1) keeps |x * 2^k| below 2^30, is exact for
+    every element within 2^19 of the group's largest one, and the signed base-256 digits obtained
+    by adding 0x00808080 reproduce the integer."""
 from fractions import Fraction
 
 import numpy as np
@@ -63,6 +64,13 @@ def test_fixed_point_digits_of_the_activations(seed):
     rng = np.random.default_rng(seed)
     x = (rng.standard_normal(4096) * np.exp2(rng.integers(-22, 6, 4096))).astype(np.float16)
     x[7] = np.float16(65504.0) if seed == 0 else x[7]
+    for g in range(0, 4096, 128):                           # every scale group against its own largest exponent
+        _check_fixed_point_of_a_group(x[g:g + 128])
+    _check_fixed_point_of_a_group(np.zeros(128, np.float16))             # exponent field 0 counts as 1
+    _check_fixed_point_of_a_group(np.full(128, 6e-8, np.float16))        # subnormals only
+
+
+def _check_fixed_point_of_a_group(x):
     bits16 = x.view(np.uint16)
     e = max(int((bits16 & 0x7FFF).max()) >> 10, 1)
     k = 44 - e
