@@ -669,14 +669,22 @@ static int exp_waves(int64_t K, bool batch) { return batch && exp_lds_bytes(K, 8
 
 // Whether the exponent form serves this PoT GEMV: signed-byte weights (2 or 3 bits), rows long
 // enough for eight wavefronts per tile, the digits of x within LDS and within the staging
-// registers of a thread, and a matrix large enough for the conversion of x to pay: below
-// about 60 M weights the fp16 form measured equal or faster (4096 x 11008, 3 bits: 7.2 us
-// against 7.5 us), above slower (28672 x 8192: 22 us against 17 us).
+// registers of a thread, and a matrix large enough for the conversion of x to pay.  From
+// about 60 M weights up it always does (28672 x 8192: 22 us in the fp16 form against 17 us).
+// Below, down to 24 M, it does where a row takes at least two rounds of 32 groups, so that the
+// conversion is spread over more decode work, and there are rows for 160 workgroups
+// (5120 x 5120: 6.0 against 6.6 us, 6656 x 6656: 7.0 against 7.4 us); shapes with one round
+// (11008 x 4096: 7.1 against 6.7 us) or few rows (4096 x 11008: 8.4 against 7.1 us) and the
+// smaller ones (4096 x 4096: 5.8 against 4.4 us) stay on the fp16 form.
+constexpr int64_t kExpMinWeightsTwoRounds = 24ll << 20, kExpMinRowsTwoRounds = 5120;
 bool gemv_exp_ok(int64_t N, int64_t K, int bits)
 {
     const int64_t G = K / kTileCols;
     if (bits != 2 && bits != 3) return false;
-    if (G < 32 || N * K < kExpMinWeights) return false;
+    if (G < 32) return false;
+    const bool large = N * K >= kExpMinWeights;
+    const bool two_rounds = N * K >= kExpMinWeightsTwoRounds && G > 32 && N >= kExpMinRowsTwoRounds;
+    if (!large && !two_rounds) return false;
     // (the eight-wavefront variant is only used where its footprint is smaller still)
     if (K > (int64_t)kExpOctetsPerThread * 16 * kWave * 8) return false;
     return exp_lds_bytes(K, 16) <= kExpLdsLarge;
