@@ -49,6 +49,26 @@ __device__ __forceinline__ void quad_octets(const uint32_t *__restrict__ p, uint
     }
 }
 
+// Sum of a value over the 64 lanes of a wavefront, valid in lane 63: six data-parallel-primitive
+// adds on the vector ALU (lane pairs, quads, half rows, rows of 16, then lane 15 of rows 0 and 2
+// into rows 1 and 3, then lane 31 into rows 2 and 3) instead of six trips through the LDS
+// crossbar, each of which a row's single wavefront would wait out.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ float dpp_or_zero(float x)      // x of the lane CTRL names; 0 in rows outside ROWS and for lanes without a source
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROWS, 0xF, ROWS == 0xF));
+}
+__device__ __forceinline__ float wave_sum_in_lane_63(float v)
+{
+    v += dpp_or_zero<0xB1, 0xF>(v);      // quad_perm [1,0,3,2]
+    v += dpp_or_zero<0x4E, 0xF>(v);      // quad_perm [2,3,0,1]
+    v += dpp_or_zero<0x141, 0xF>(v);     // row_half_mirror
+    v += dpp_or_zero<0x140, 0xF>(v);     // row_mirror: every lane holds its row's sum
+    v += dpp_or_zero<0x142, 0xA>(v);     // row_bcast15 into rows 1 and 3
+    v += dpp_or_zero<0x143, 0xC>(v);     // row_bcast31 into rows 2 and 3
+    return v;
+}
+
 template <int BITS, bool IS_INT>
 __global__ __launch_bounds__(kCanonWaves * kWave) void gemv_canonical_kernel(
     const uint32_t *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
@@ -91,9 +111,8 @@ __global__ __launch_bounds__(kCanonWaves * kWave) void gemv_canonical_kernel(
                 for (int m = 0; m < 4; ++m) sum = __builtin_amdgcn_fdot2(as_half2(w[m]), as_half2(xv[m]), sum, false);
             }
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);
-        if (lane == 0) y[n] = __builtin_bit_cast(uint16_t, (_Float16)sum);
+        sum = wave_sum_in_lane_63(sum);
+        if (lane == kWave - 1) y[n] = __builtin_bit_cast(uint16_t, (_Float16)sum);
     }
 }
 
