@@ -698,12 +698,16 @@ static hipError_t launch_gemv_walk(const void *codes, const void *scales, const 
                            (const u32x4 *)codes, (const uint16_t *)scales, (const uint16_t *)zeros,               \
                            (const u32x4 *)x, (uint16_t *)y, rowtiles, (int)K);                                    \
     } while (0)
+    // 2- and 3-bit PoT matrices only come here with rows too long for the exponent form
+    // (K > 32768), which always take the column-0 fetch: the other instances are not built
+    constexpr bool kShortRowsPossible = IS_INT || BITS == 4;
+    const bool col0 = !kShortRowsPossible || gemv_col0_fetch(K);
     if (group == 64) {
-        if (gemv_col0_fetch(K)) POTQ_LAUNCH_WALK(true, true);
-        else POTQ_LAUNCH_WALK(true, false);
+        if (col0) POTQ_LAUNCH_WALK(true, true);
+        else if constexpr (kShortRowsPossible) POTQ_LAUNCH_WALK(true, false);
     } else {
-        if (gemv_col0_fetch(K)) POTQ_LAUNCH_WALK(false, true);
-        else POTQ_LAUNCH_WALK(false, false);
+        if (col0) POTQ_LAUNCH_WALK(false, true);
+        else if constexpr (kShortRowsPossible) POTQ_LAUNCH_WALK(false, false);
     }
 #undef POTQ_LAUNCH_WALK
     return hipGetLastError();

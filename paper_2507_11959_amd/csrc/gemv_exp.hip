@@ -700,9 +700,10 @@ template <int BITS, bool G64, int WAVES, bool SKIP_LAST, bool BATCH>
 static hipError_t exp_allow_lds(size_t lds)
 {
     static std::atomic<uint64_t> raised{0};           // one flag word per kernel instantiation
-    const void *kernel = BATCH ? (const void *)gemv_exp_batch_kernel<BITS, G64, WAVES, SKIP_LAST>
-                               : (const void *)gemv_exp_kernel<BITS, G64, WAVES, SKIP_LAST>;
-    return allow_large_lds(kernel, lds, raised);
+    if constexpr (BATCH)
+        return allow_large_lds((const void *)gemv_exp_batch_kernel<BITS, G64, WAVES, SKIP_LAST>, lds, raised);
+    else
+        return allow_large_lds((const void *)gemv_exp_kernel<BITS, G64, WAVES, SKIP_LAST>, lds, raised);
 }
 
 // Workgroups for a matrix of `sets` tile sets when it may use `cap` of them: equal shares of sets.

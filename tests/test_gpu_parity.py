@@ -374,7 +374,7 @@ def test_gemm_every_dispatch_configuration(potq, M, N, K, is_int):
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("M,N,K", [
     (1900, 6000, 128),     # tall tile (PoT) / wide tile (uniform), ragged rows and tokens
-    (520, 3344, 256),      # wide tile with its prefetches (2-bit PoT), ragged
+    (1000, 6384, 128),     # wide tile (with its prefetches at 2 bits, PoT), ragged
 ])
 def test_gemm_many_token_tiles_other_widths_and_groups(potq, bits, group, M, N, K):
     """The tiles above 64 tokens at the code widths and the group size the other tests leave out."""
