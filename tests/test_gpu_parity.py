@@ -370,6 +370,31 @@ def test_gemm_every_dispatch_configuration(potq, M, N, K, is_int):
         assert e <= REL_TOL, (use_ws, e, nw, nfloor)
 
 
+@pytest.mark.parametrize("is_int", [False, True])
+@pytest.mark.parametrize("M,N,K", [(128, 1024, 5120), (200, 1024, 2048), (256, 2048, 8192), (130, 4112, 256)])
+def test_gemm_plan_does_not_depend_on_spare_workspace(potq, M, N, K, is_int):
+    """Above 64 tokens the workspace query returns what the preferred plan needs; a larger workspace must
+    not change the plan (same bits), a missing one only removes the K split (same tolerance)."""
+    bits = 3
+    packed, S, Z = _gemv_inputs(5000 + M + N, N, K, bits, is_int)
+    X = workloads.activations(5100 + M, M, K)
+    tiled = potq.potq_repack(dev(packed), K, bits)
+    need = potq.gemm_workspace(M, N, K, bits)
+    spare = torch.empty(((0 if need is None else need.numel()) * 3 + (64 << 20),), dtype=torch.uint8, device="cuda:0")
+
+    def run(ws):
+        if is_int:
+            return host_bits(potq.int_gemm(tiled, dev(S), dev(Z), dev(X), K, bits, workspace=ws))
+        return host_bits(potq.pot_gemm(tiled, dev(S), dev(X), K, bits, workspace=ws))
+
+    preferred, larger, none = run(need), run(spare), run(None)
+    assert np.array_equal(preferred, larger)
+    want = oracle.gemm(packed, S, Z, X, K, bits, 128, nthreads=8)
+    for got in (preferred, none):
+        e, nw, nfloor = rel_err(got, want, K)
+        assert e <= REL_TOL, (e, nw, nfloor)
+
+
 @pytest.mark.parametrize("group", [64, 128])
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("M,N,K", [
