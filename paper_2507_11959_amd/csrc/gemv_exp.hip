@@ -23,6 +23,8 @@
 // one in the accumulation, as many as the fp16 form has per four MFMA steps.
 // The scale must lie in the domain on which the integer add of Sec. 4.2 is the
 // multiplication by 2^E (every scale pot_quantize produces does).
+#include <type_traits>
+
 #include "potq_device.hpp"
 #include "potq_launch.hpp"
 
@@ -197,7 +199,7 @@ __device__ __forceinline__ void stage_digits(const u32x4 xv, u32x4 *__restrict__
 // 4p + t + 32, ...).  The codes of the next step -- the next round of the tile or the first round
 // of the next tile -- are requested before the current ones are expanded (requests two or three
 // steps ahead measured slower), and the very first request goes out before x is staged.
-template <int BITS, bool G64, int WAVES, bool SKIP_LAST>
+template <int BITS, bool G64, int WAVES>
 __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales,
                                               const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int K,
                                               int64_t rowtiles, int64_t first, int64_t stride)
@@ -230,29 +232,21 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
     // Codes of (tile, round) for lane (r, t); scales in memory order (lane l: row l/4, group
     // first + l%4; handed to their owners by a permute) or, for group size 64, the lane's own pair.
     // Indices past the end of the row are clamped into it: valid memory, multiplied by zeros.
-    // Every round requests the codes of the next step.  After a wavefront's last step there is
-    // nothing left to request; the request is still issued (a branch around it measured no
-    // better), either for the last step once more -- 3 KB fetched again for nothing, since the
-    // loads are non-temporal -- or, with `live` = false, with every lane pointed at the first 16
-    // bytes of each slab of the tile and at its first scale, a handful of 64-byte requests.
-    // SKIP_LAST chooses: with one or two tile sets per workgroup the repeat is a large share
-    // of the traffic and skipping it wins (8192 x 8192: 8.1 against 8.55 us, 8192 x 28672: 18.7
-    // against 19.6 us); with four or more the variant without the choice is scheduled better by
-    // the compiler and wins by more than the traffic costs (28672 x 8192: 17.0 against 18.1 us,
-    // 128256 x 4096: 32.4 against 36.3 us).
-    auto fetch = [&](int64_t tile, int round, bool live, u32x4 (&Lx)[BITS], uint32_t &sx) {
+    // Every step requests the codes of the next one; the wavefront's last step, which has none
+    // to request, is taken out of the loop (see `step` below).
+    auto fetch = [&](int64_t tile, int round, u32x4 (&Lx)[BITS], uint32_t &sx) {
         const int g0 = round * kStep + part * 4;                        // uniform
         const int gc = min(g0 + t, G - 1);
         const u32x4 *tile_codes = codes + tile * G * (BITS * 16);       // uniform
-        const uint32_t at = live ? (uint32_t)(gc * (BITS * 16) + r) : 0u;
+        const uint32_t at = (uint32_t)(gc * (BITS * 16) + r);
 #pragma unroll
         for (int j = 0; j < BITS; ++j) Lx[j] = __builtin_nontemporal_load(tile_codes + at + 16 * j);
         if (gs) {
             const uint32_t *tile_scales = (const uint32_t *)(scales + tile * kTileRows * (int64_t)(2 * G));
-            sx = tile_scales[live ? (uint32_t)(r * G + gc) : 0u];
+            sx = tile_scales[(uint32_t)(r * G + gc)];
         } else {
             const uint16_t *tile_scales = scales + tile * kTileRows * (int64_t)G;
-            sx = tile_scales[live ? (uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1)) : 0u];
+            sx = tile_scales[(uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1))];
         }
     };
 
@@ -274,9 +268,8 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
     };
     u32x4 L[BITS];
     uint32_t s;
-    fetch(tile_of(fq), fround, true, L, s);
-    bool more = advance();
-    (void)more;
+    fetch(tile_of(fq), fround, L, s);
+    advance();
 
     // --- activations: fixed point digits into LDS, every scale group against its own largest exponent ---
     // The sixteen octets of a group sit in sixteen consecutive lanes, so the group's largest
@@ -344,7 +337,7 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
             for (int round = 0; round < my_rounds; ++round) {
                 u32x4 Lp[BITS];
                 uint32_t sp;
-                fetch(tile_of(q), round, true, Lp, sp);
+                fetch(tile_of(q), round, Lp, sp);
                 const int g = round * kStep + part * 4 + t;
                 const uint16_t *xg = (const uint16_t *)x + (size_t)min(g, G - 1) * kTileCols;
                 if (gs) {
@@ -375,55 +368,65 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
 
     int it = 0;
     float consumed = 0.f;       // the latest value computed from MFMA results: orders lds_read_keep behind them
-    for (int64_t q = first; q * SLOTS < rowtiles; q += stride, ++it) {
-        float row_sum = 0.f;
-        for (int round = 0; round < my_rounds; ++round) {
-            u32x4 Ln[BITS];
-            uint32_t sn;
-            if constexpr (SKIP_LAST) {
-                fetch(tile_of(fq), fround, more, Ln, sn);
-                more = more && advance();
-            } else {
-                fetch(tile_of(fq), fround, true, Ln, sn);
-                advance();
-            }
-            const int g = round * kStep + part * 4 + t;
-            const float unit = group_unit[min(g, G - 1)];
-            // a lane past the end of the row multiplies the (valid) last group by zeros
-            lds_read_keep(xa, g < G ? pieces_at + (uint32_t)((g * 4 + (lane & 3)) * (kPieceRun * 16)) : zeros_at,
-                          diagonal_lanes, consumed);
-            if (gs) {
-                lds_wait(xa);
-                int4_t d0{0, 0, 0, 0}, d1{0, 0, 0, 0};
-                exp_blocks<BITS>(L, xa, 0, 2, d0);
-                exp_blocks<BITS>(L, xa, 2, 4, d1);
-                // scale * 2^-k is exact (a power of two times an fp16, far inside binary32's range)
-                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s & 0xFFFFu)) * unit,
-                                         exp_recombine(d0), row_sum);
-                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s >> 16)) * unit,
-                                         exp_recombine(d1), row_sum);
-            } else {
-                const uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)s);
-                lds_wait(xa);
-                int4_t d{0, 0, 0, 0};
-                exp_blocks<BITS>(L, xa, 0, 4, d);
-                row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)so) * unit, exp_recombine(d), row_sum);
-            }
-            consumed = row_sum;
+    // One step: the codes in L against the digits of the step's groups; `request` says whether the
+    // codes of the next step are asked for first.  It is a compile-time choice: the loop below
+    // takes the wavefront's very last step out of the steady state, which then neither tests for
+    // it nor fetches anything twice.  (Fetching the last step's 3 KB once more instead cost 8 %
+    // more HBM reads on 28672 x 8192; a test inside the loop, or a request redirected to a dummy
+    // address, was scheduled worse by the compiler than the reads cost on tall matrices.  Peeled:
+    // 13824 x 5120 8.8 -> 8.3 us, 8192 x 8192 7.6 -> 7.2, 28672 x 8192 16.7 -> 16.4, at 2 bits 14.7 -> 13.8.)
+    auto step = [&](int round, auto request, float &row_sum) {
+        u32x4 Ln[BITS];
+        uint32_t sn = 0u;
+        if constexpr (decltype(request)::value) {
+            fetch(tile_of(fq), fround, Ln, sn);
+            advance();
+        }
+        const int g = round * kStep + part * 4 + t;
+        const float unit = group_unit[min(g, G - 1)];
+        // a lane past the end of the row multiplies the (valid) last group by zeros
+        lds_read_keep(xa, g < G ? pieces_at + (uint32_t)((g * 4 + (lane & 3)) * (kPieceRun * 16)) : zeros_at,
+                      diagonal_lanes, consumed);
+        if (gs) {
+            lds_wait(xa);
+            int4_t d0{0, 0, 0, 0}, d1{0, 0, 0, 0};
+            exp_blocks<BITS>(L, xa, 0, 2, d0);
+            exp_blocks<BITS>(L, xa, 2, 4, d1);
+            // scale * 2^-k is exact (a power of two times an fp16, far inside binary32's range)
+            row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s & 0xFFFFu)) * unit,
+                                     exp_recombine(d0), row_sum);
+            row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)(s >> 16)) * unit,
+                                     exp_recombine(d1), row_sum);
+        } else {
+            const uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)s);
+            lds_wait(xa);
+            int4_t d{0, 0, 0, 0};
+            exp_blocks<BITS>(L, xa, 0, 4, d);
+            row_sum = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)so) * unit, exp_recombine(d), row_sum);
+        }
+        consumed = row_sum;
+        if constexpr (decltype(request)::value) {
 #pragma unroll
             for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
             s = sn;
         }
+    };
+    for (int64_t q = first; q * SLOTS < rowtiles; q += stride, ++it) {
+        float row_sum = 0.f;
+        const bool last_set = (q + stride) * SLOTS >= rowtiles;
+        const int requesting = last_set ? my_rounds - 1 : my_rounds;
+        for (int round = 0; round < requesting; ++round) step(round, std::true_type{}, row_sum);
+        if (last_set) step(my_rounds - 1, std::false_type{}, row_sum);
         finish_tiles(q, it, row_sum);
     }
 }
 
-template <int BITS, bool G64, int WAVES, bool SKIP_LAST>
+template <int BITS, bool G64, int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_kernel(
     const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const u32x4 *__restrict__ x,
     uint16_t *__restrict__ y, int K, int64_t rowtiles)
 {
-    gemv_exp_body<BITS, G64, WAVES, SKIP_LAST>(codes, scales, x, y, K, rowtiles, blockIdx.x, gridDim.x);
+    gemv_exp_body<BITS, G64, WAVES>(codes, scales, x, y, K, rowtiles, blockIdx.x, gridDim.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -461,15 +464,15 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
     const int64_t first = blockIdx.x, stride = gridDim.x;
     auto tile_of = [&](int64_t q) { return min(q * SLOTS + slot, rowtiles - 1); };
 
-    auto fetch = [&](int64_t tile, int round, bool live, u32x4 (&Lx)[BITS], uint32_t &sx) {   // as in gemv_exp_body
+    auto fetch = [&](int64_t tile, int round, u32x4 (&Lx)[BITS], uint32_t &sx) {   // as in gemv_exp_body
         const int g0 = round * kStep + part * 4;
         const int gc = min(g0 + t, G - 1);
         const u32x4 *tile_codes = codes + tile * G * (BITS * 16);
-        const uint32_t at = live ? (uint32_t)(gc * (BITS * 16) + r) : 0u;
+        const uint32_t at = (uint32_t)(gc * (BITS * 16) + r);
 #pragma unroll
         for (int j = 0; j < BITS; ++j) Lx[j] = __builtin_nontemporal_load(tile_codes + at + 16 * j);
         const uint16_t *tile_scales = scales + tile * kTileRows * (int64_t)G;
-        sx = tile_scales[live ? (uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1)) : 0u];
+        sx = tile_scales[(uint32_t)((lane >> 2) * G + min(g0 + (lane & 3), G - 1))];
     };
     int64_t fq = first;
     int fround = 0;
@@ -487,7 +490,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
     };
     u32x4 L[BITS];
     uint32_t s;
-    fetch(tile_of(fq), fround, true, L, s);
+    fetch(tile_of(fq), fround, L, s);
     advance();
 
     // --- activations: fixed point digits into LDS, every scale group of every vector against its
@@ -555,7 +558,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
             for (int round = 0; round < my_rounds; ++round) {
                 u32x4 Lp[BITS];
                 uint32_t sp;
-                fetch(tile_of(q), round, true, Lp, sp);
+                fetch(tile_of(q), round, Lp, sp);
                 const int g = round * kStep + part * 4 + t;
                 const float sf = (float)__builtin_bit_cast(_Float16, (uint16_t)__builtin_amdgcn_ds_bpermute(scale_owner, (int)sp));
 #pragma unroll 1
@@ -580,11 +583,15 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
         float row_sum[MT];
 #pragma unroll
         for (int m = 0; m < MT; ++m) row_sum[m] = 0.f;
-        for (int round = 0; round < my_rounds; ++round) {
+        // as in gemv_exp_body: the wavefront's last step, which has no successor to request, is
+        // taken out of the steady-state loop
+        auto step = [&](int round, auto request) {
             u32x4 Ln[BITS];
-            uint32_t sn;
-            fetch(tile_of(fq), fround, true, Ln, sn);      // after the last step: the last one again (never used)
-            advance();
+            uint32_t sn = 0u;
+            if constexpr (decltype(request)::value) {
+                fetch(tile_of(fq), fround, Ln, sn);
+                advance();
+            }
             const int g = round * kStep + part * 4 + t;
             const bool mine = diagonal && g < G;
             const u32x4 *xq[MT];
@@ -615,10 +622,16 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
 #pragma unroll
             for (int m = 0; m < MT; ++m)     // scale * 2^-k is exact
                 row_sum[m] = __builtin_fmaf(sf * group_unit[m * G + min(g, G - 1)], exp_recombine(d[m]), row_sum[m]);
+            if constexpr (decltype(request)::value) {
 #pragma unroll
-            for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
-            s = sn;
-        }
+                for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
+                s = sn;
+            }
+        };
+        const bool last_set = (q + stride) * SLOTS >= rowtiles;
+        const int requesting = last_set ? my_rounds - 1 : my_rounds;
+        for (int round = 0; round < requesting; ++round) step(round, std::true_type{});
+        if (last_set) step(my_rounds - 1, std::false_type{});
         finish_tiles(q, it, row_sum);
     }
 }
@@ -635,13 +648,13 @@ struct ExpBatch {
     int count;
 };
 
-template <int BITS, bool G64, int WAVES, bool SKIP_LAST>
+template <int BITS, bool G64, int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_batch_kernel(const ExpBatch batch,
                                                                        const u32x4 *__restrict__ x, int K)
 {
     int i = 0;
     while (i + 1 < batch.count && blockIdx.x >= batch.first_block[i + 1]) ++i;   // uniform: scalar code
-    gemv_exp_body<BITS, G64, WAVES, SKIP_LAST>(batch.codes[i], batch.scales[i], x, batch.y[i], K, batch.rowtiles[i],
+    gemv_exp_body<BITS, G64, WAVES>(batch.codes[i], batch.scales[i], x, batch.y[i], K, batch.rowtiles[i],
                                     blockIdx.x - batch.first_block[i],
                                     batch.first_block[i + 1] - batch.first_block[i]);
 }
@@ -696,14 +709,14 @@ bool gemv_exp_batch_ok(int count, int64_t rows_total, int64_t K, int bits)
     return count <= kMaxExpBatch && gemv_exp_ok(rows_total, K, bits);
 }
 
-template <int BITS, bool G64, int WAVES, bool SKIP_LAST, bool BATCH>
+template <int BITS, bool G64, int WAVES, bool BATCH>
 static hipError_t exp_allow_lds(size_t lds)
 {
     static std::atomic<uint64_t> raised{0};           // one flag word per kernel instantiation
     if constexpr (BATCH)
-        return allow_large_lds((const void *)gemv_exp_batch_kernel<BITS, G64, WAVES, SKIP_LAST>, lds, raised);
+        return allow_large_lds((const void *)gemv_exp_batch_kernel<BITS, G64, WAVES>, lds, raised);
     else
-        return allow_large_lds((const void *)gemv_exp_kernel<BITS, G64, WAVES, SKIP_LAST>, lds, raised);
+        return allow_large_lds((const void *)gemv_exp_kernel<BITS, G64, WAVES>, lds, raised);
 }
 
 // Workgroups for a matrix of `sets` tile sets when it may use `cap` of them: equal shares of sets.
@@ -714,21 +727,17 @@ static int64_t exp_groups(int64_t sets, int64_t cap)
     return (sets + per_group - 1) / per_group;
 }
 
-// Tile sets a workgroup walks at most; up to two, the variant that skips the repeated last request serves.
-static int64_t exp_sets_per_group(int64_t sets, int64_t cap) { return (sets + (cap < 1 ? 1 : cap) - 1) / (cap < 1 ? 1 : cap); }
-constexpr int64_t kSkipLastUpTo = 2;
-
-template <int BITS, bool G64, int WAVES, bool SKIP_LAST>
+template <int BITS, bool G64, int WAVES>
 static hipError_t launch_exp(const void *codes, const void *scales, const void *x, void *y, int64_t N, int64_t K,
                              hipStream_t stream)
 {
     const size_t lds = exp_lds_bytes(K, WAVES);
-    const hipError_t e = exp_allow_lds<BITS, G64, WAVES, SKIP_LAST, false>(lds);
+    const hipError_t e = exp_allow_lds<BITS, G64, WAVES, false>(lds);
     if (e != hipSuccess) return e;
     constexpr int SLOTS = WAVES / kExpSplit;
     const int64_t rowtiles = N / kTileRows;
     const dim3 grid((unsigned)exp_groups((rowtiles + SLOTS - 1) / SLOTS, kExpGroups / SLOTS)), block(WAVES * kWave);
-    hipLaunchKernelGGL((gemv_exp_kernel<BITS, G64, WAVES, SKIP_LAST>), grid, block, lds, stream, (const u32x4 *)codes,
+    hipLaunchKernelGGL((gemv_exp_kernel<BITS, G64, WAVES>), grid, block, lds, stream, (const u32x4 *)codes,
                        (const uint16_t *)scales, (const u32x4 *)x, (uint16_t *)y, (int)K, rowtiles);
     return hipGetLastError();
 }
@@ -736,15 +745,12 @@ static hipError_t launch_exp(const void *codes, const void *scales, const void *
 hipError_t run_gemv_exp(const void *codes, const void *scales, const void *x, void *y, int64_t N, int64_t K, int bits,
                         int group, hipStream_t stream)
 {
-    const bool g64 = group == 64;
-    constexpr int WAVES = 16, SLOTS = WAVES / kExpSplit;
-    const bool skip = exp_sets_per_group((N / kTileRows + SLOTS - 1) / SLOTS, kExpGroups / SLOTS) <= kSkipLastUpTo;
-#define POTQ_LAUNCH_EXP(BITS, G64)                                                                \
-    (skip ? launch_exp<BITS, G64, WAVES, true>(codes, scales, x, y, N, K, stream)                 \
-          : launch_exp<BITS, G64, WAVES, false>(codes, scales, x, y, N, K, stream))
-    if (bits == 3) return g64 ? POTQ_LAUNCH_EXP(3, true) : POTQ_LAUNCH_EXP(3, false);
-    return g64 ? POTQ_LAUNCH_EXP(2, true) : POTQ_LAUNCH_EXP(2, false);
-#undef POTQ_LAUNCH_EXP
+    constexpr int WAVES = 16;
+    if (group == 64)
+        return bits == 3 ? launch_exp<3, true, WAVES>(codes, scales, x, y, N, K, stream)
+                         : launch_exp<2, true, WAVES>(codes, scales, x, y, N, K, stream);
+    return bits == 3 ? launch_exp<3, false, WAVES>(codes, scales, x, y, N, K, stream)
+                     : launch_exp<2, false, WAVES>(codes, scales, x, y, N, K, stream);
 }
 
 
@@ -758,7 +764,6 @@ static hipError_t launch_exp_batch(int count, const void *const *codes, const vo
     for (int i = 0; i < count; ++i) sets_total += (N[i] / kTileRows + SLOTS - 1) / SLOTS;
     ExpBatch b;
     uint64_t blocks = 0;
-    int64_t sets_per_group = 0;
     for (int i = 0; i < kMaxExpBatch; ++i) {
         const bool live = i < count;
         b.codes[i] = live ? (const u32x4 *)codes[i] : nullptr;
@@ -771,23 +776,14 @@ static hipError_t launch_exp_batch(int count, const void *const *codes, const vo
             const int64_t sets = (b.rowtiles[i] + SLOTS - 1) / SLOTS;
             const int64_t cap = (kExpGroups / SLOTS) * sets / sets_total;
             blocks += (uint64_t)exp_groups(sets, cap);
-            if (exp_sets_per_group(sets, cap) > sets_per_group) sets_per_group = exp_sets_per_group(sets, cap);
         }
     }
     b.first_block[kMaxExpBatch] = (uint32_t)blocks;
     b.count = count;
     const dim3 grid((unsigned)blocks), block(WAVES * kWave);
-    if (sets_per_group <= kSkipLastUpTo) {
-        const hipError_t e = exp_allow_lds<BITS, G64, WAVES, true, true>(lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((gemv_exp_batch_kernel<BITS, G64, WAVES, true>), grid, block, lds, stream, b, (const u32x4 *)x,
-                           (int)K);
-    } else {
-        const hipError_t e = exp_allow_lds<BITS, G64, WAVES, false, true>(lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((gemv_exp_batch_kernel<BITS, G64, WAVES, false>), grid, block, lds, stream, b, (const u32x4 *)x,
-                           (int)K);
-    }
+    const hipError_t e = exp_allow_lds<BITS, G64, WAVES, true>(lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((gemv_exp_batch_kernel<BITS, G64, WAVES>), grid, block, lds, stream, b, (const u32x4 *)x, (int)K);
     return hipGetLastError();
 }
 

@@ -165,8 +165,8 @@ def test_gemm_four_row_tiles_other_widths(potq, M, N, K, bits, is_int):
 
 # ---------------------------------------------------------------------------
 # The exponent form: group size 64 with many tile sets per workgroup, the shared-activation
-# launch in its four shapes (eight or sixteen wavefronts by row length; with or without the
-# repeated last request by tile sets per workgroup), and the kernel for two to four vectors.
+# launch in its four shapes (eight or sixteen wavefronts by row length; one to three tile sets
+# per workgroup), and the kernel for two to four vectors.
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("bits", [2, 3])
 def test_exponent_form_group_64_many_tile_sets(potq, bits):
