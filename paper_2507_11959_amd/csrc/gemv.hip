@@ -12,6 +12,8 @@
 //
 // The same file holds the fused GEMM for up to 16 tokens (gemm_fewtok_kernel),
 // which keeps this lane-owns-a-group scheme and makes the tokens the B operand.
+#include <type_traits>
+
 #include "potq_device.hpp"
 #include "potq_launch.hpp"
 
@@ -156,15 +158,16 @@ __device__ __forceinline__ void gemv_tile16_body(
     float4_t acc[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = float4_t{0.f, 0.f, 0.f, 0.f};
-    for (int round = 0; round < rounds; ++round) {
-        // a wavefront whose four groups of this round all lie past the end of the row is done
-        // (wave-uniform; K = 5120 has 40 groups for 64 slots of two rounds)
-        if (round * kStep + part * 4 >= G) break;
+    // One round; `request` says whether the codes of the next round are asked for first.  The
+    // wavefront's last round has no successor: it is taken out of the loop, so that a launch
+    // whose wavefronts have a single round (K = 4096) issues no second request at all -- a
+    // request nobody consumes still keeps the wavefront alive until it returns.
+    auto step = [&](int round, auto request) {
         const int gn = g + kStep;
         u32x4 Ln[BITS];
         uint32_t sn = 0, zn = 0;
-        {
-            const int gc = gn < G ? gn : G - 1;         // past the end: re-read the last group, never used
+        if constexpr (decltype(request)::value) {
+            const int gc = gn < G ? gn : G - 1;         // a lane past the end of the row: the last group, times zeros
 #pragma unroll
             for (int j = 0; j < BITS; ++j)
                 Ln[j] = __builtin_nontemporal_load(tile0 + (int64_t)gc * (BITS * 16) + 16 * j);
@@ -201,11 +204,18 @@ __device__ __forceinline__ void gemv_tile16_body(
         gemv_group<BITS, IS_INT, (MT > 1 ? MT : (COL0 ? 1 : 0))>(L, so, zo, so_hi, zo_hi, gs != 0,
                                                                [&](int j) { return xg[j]; }, acc);
         g = gn;
+        if constexpr (decltype(request)::value) {
 #pragma unroll
-        for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
-        s = sn;
-        z = zn;
-    }
+            for (int j = 0; j < BITS; ++j) L[j] = Ln[j];
+            s = sn;
+            z = zn;
+        }
+    };
+    // rounds in which this wavefront has a group (wave-uniform; K = 5120 has 40 groups for 64 slots
+    // of two rounds: the wavefronts of parts 2..7 have one round)
+    const int my_rounds = min(rounds, (G - part * 4 + kStep - 1) / kStep);
+    for (int round = 0; round + 1 < my_rounds; ++round) step(round, std::true_type{});
+    if (my_rounds > 0) step(my_rounds - 1, std::false_type{});
 
     // The MFMA already summed the four lane groups.  Lane (c, q) holds rows 4q..4q+3
     // (identical in every column c); combine the S wavefronts of a tile in a fixed order.
