@@ -493,9 +493,9 @@ __global__ __launch_bounds__(kFewWaves * kWave) void gemm_fewtok_kernel(
     for (int k = 0; k < 4; ++k) xq[k] = smem + (part * 4 + t) * 256 + ((r + 4 * k) & 15);
 
     Fetched q[kFewDepth];                               // rounds of codes in flight ahead of the arithmetic
+    fetch_x(0);
 #pragma unroll
     for (int d = 0; d < kFewDepth; ++d) fetch(d, q[d]);
-    fetch_x(0);
 
     float4_t acc[4];
 #pragma unroll
@@ -505,9 +505,11 @@ __global__ __launch_bounds__(kFewWaves * kWave) void gemm_fewtok_kernel(
 #pragma unroll
         for (int i = 0; i < kFewPieces; ++i) smem[xslot[i]] = xr[i];
         __syncthreads();
+        // X first: loads return in order, and the chunk (from L2) is wanted at the top of the next round,
+        // before the codes (from HBM) are
+        fetch_x(round + 1);                             // past the end: clamped addresses, zeros, never used
         Fetched nx;
         fetch(round + kFewDepth, nx);
-        fetch_x(round + 1);                             // past the end: clamped addresses, zeros, never used
         const Fetched &cur = q[0];
 
         const int g = round * kFewChunk + part * 4 + t;
