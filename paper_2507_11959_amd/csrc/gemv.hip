@@ -125,6 +125,26 @@ __device__ __forceinline__ void gemv_tile16_body(
     u32x4 *zero_block = smem + MT * (K / kTileCols) * kXRun;   // 16 uint4 of zeros
     float *red = (float *)(zero_block + 16);            // 8 wavefronts x MT x 16 partial sums
 
+    // Activations first: loads return in order, and x (from the L2) has to be in LDS before the
+    // barrier, while the codes (from HBM) are not needed until after it.  The first pieces of
+    // every thread (all of x up to K = 8192) are requested here and written once the codes of
+    // the first round have been requested too; longer rows take the rest afterwards.
+    // Vector m occupies runs m*G .. m*G + G-1; vectors past `tokens` count as zero.
+    constexpr int kXFirst = 2;
+    constexpr int kThreads = kGemvWaves * kWave;
+    const int per = K / 8, pieces = MT * per;
+    auto x_piece = [&](int i) {
+        const int m = MT == 1 ? 0 : i / per;
+        return (i < pieces && m < tokens) ? x[i] : u32x4{0u, 0u, 0u, 0u};
+    };
+    auto x_slot = [&](int i) {
+        const int m = MT == 1 ? 0 : i / per, o = i - m * per;
+        return (m * G + (o >> 4)) * kXRun + (o & 15);
+    };
+    u32x4 xfirst[kXFirst];
+#pragma unroll
+    for (int u = 0; u < kXFirst; ++u) xfirst[u] = x_piece(tid + u * kThreads);
+
     int g = part * 4 + t;
     u32x4 L[BITS];
     uint32_t s, z = 0;       // raw loads (memory order); permuted to their owners when consumed
@@ -142,16 +162,10 @@ __device__ __forceinline__ void gemv_tile16_body(
         }
     }
 
-    if (MT == 1) {
-        for (int i = tid; i < K / 8; i += kGemvWaves * kWave) xs[(i >> 4) * kXRun + (i & 15)] = x[i];
-    } else {
-        // vector m occupies runs m*G .. m*G + G-1; vectors past `tokens` count as zero
-        const int per = K / 8;
-        for (int i = tid; i < MT * per; i += kGemvWaves * kWave) {
-            const int m = i / per, o = i - m * per;
-            xs[(m * G + (o >> 4)) * kXRun + (o & 15)] = m < tokens ? x[i] : u32x4{0u, 0u, 0u, 0u};
-        }
-    }
+#pragma unroll
+    for (int u = 0; u < kXFirst; ++u)
+        if (tid + u * kThreads < pieces) xs[x_slot(tid + u * kThreads)] = xfirst[u];
+    for (int i = tid + kXFirst * kThreads; i < pieces; i += kThreads) xs[x_slot(i)] = x_piece(i);
     if (tid < 16) zero_block[tid] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
