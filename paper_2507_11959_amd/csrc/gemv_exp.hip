@@ -266,6 +266,15 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
         }
         return false;
     };
+    // x is requested before the codes of the first step: loads return in order, x comes from the
+    // L2 and its conversion can run while the codes are on their way from HBM.
+    const int octets = K / 8;
+    u32x4 xin[kExpOctetsPerThread];
+#pragma unroll
+    for (int n = 0; n < kExpOctetsPerThread; ++n) {
+        const int i = tid + n * (WAVES * kWave);
+        xin[n] = i < octets ? x[i] : u32x4{0u, 0u, 0u, 0u};
+    }
     u32x4 L[BITS];
     uint32_t s;
     fetch(tile_of(fq), fround, L, s);
@@ -278,13 +287,12 @@ __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, c
     // needs a second one, behind a reduction over the workgroup, which cost 5-12 % of the launch
     // on the 13B to 70B shapes).  |x| < 2^(e-14) with e = max(exponent field, 1): k = 44 - e puts
     // every |m| below 2^30; the group's sums are in units of 2^-k, kept per group in LDS.
-    const int octets = K / 8;
     bool saw_nonfinite = false;
 #pragma unroll
     for (int n = 0; n < kExpOctetsPerThread; ++n) {
         if (n * (WAVES * kWave) >= octets) break;       // uniform: no thread has an octet in this pass
         const int i = tid + n * (WAVES * kWave);
-        const u32x4 xv = i < octets ? x[i] : u32x4{0u, 0u, 0u, 0u};
+        const u32x4 xv = xin[n];
         uint32_t am = 0u;
 #pragma unroll
         for (int w = 0; w < 4; ++w)
@@ -488,6 +496,15 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
         }
         return false;
     };
+    // x before the codes of the first step, as in gemv_exp_body
+    const int per = K / 8;                              // octets per vector
+    const int octets = MT * per;
+    u32x4 xin[kExpOctetsPerThread];
+#pragma unroll
+    for (int n = 0; n < kExpOctetsPerThread; ++n) {
+        const int i = tid + n * THREADS;
+        xin[n] = (i < octets && i / per < tokens) ? x[i] : u32x4{0u, 0u, 0u, 0u};
+    }
     u32x4 L[BITS];
     uint32_t s;
     fetch(tile_of(fq), fround, L, s);
@@ -495,15 +512,13 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_exp_multi_kernel(
 
     // --- activations: fixed point digits into LDS, every scale group of every vector against its
     // own largest exponent (see gemv_exp_body: the sixteen lanes of a row hold one group) ---
-    const int per = K / 8;                              // octets per vector
-    const int octets = MT * per;
     bool saw_nonfinite = false;
 #pragma unroll
     for (int n = 0; n < kExpOctetsPerThread; ++n) {
         if (n * THREADS >= octets) break;               // uniform: no thread has an octet in this pass
         const int i = tid + n * THREADS;
         const int vec = i / per, o = i - vec * per;     // vector, octet inside the vector
-        const u32x4 xv = (i < octets && vec < tokens) ? x[i] : u32x4{0u, 0u, 0u, 0u};
+        const u32x4 xv = xin[n];
         uint32_t a = 0u;
 #pragma unroll
         for (int w = 0; w < 4; ++w)
