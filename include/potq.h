@@ -181,13 +181,19 @@ int int_gemv(const void *codes, const void *scales, const void *zeros, const voi
 
 /*
  * 1 if pot_gemv (and pot_gemm with one token) serves an N x K matrix of this
- * width in the exponent form described above, else 0.  For pot_gemv_batch pass
- * the total number of rows of the matrices that share the launch.  pot_gemm
- * with two to four tokens uses the same form (every token with its own
- * fixed-point exponent) on a subset of these shapes: group size 128 and more
- * than 8192 rows (two tokens) or at least 16384 (three, four).
+ * width in the exponent form described above, else 0.  pot_gemm with two to
+ * four tokens uses the same form (every token with its own fixed-point
+ * exponents) on a subset of these shapes: group size 128 and more than 8192
+ * rows (two tokens) or at least 16384 (three, four).
  */
 int potq_gemv_exponent_form(int64_t N, int64_t K, int bits);
+
+/*
+ * The same question for pot_gemv_batch with `count` matrices of row length K:
+ * matrices that share x share its conversion, so a batch takes the exponent
+ * form at every size the form can serve (2 or 3 bits, 4096 <= K <= 32768).
+ */
+int potq_gemv_batch_exponent_form(int count, int64_t K, int bits);
 
 /*
  * pot_gemv_batch / int_gemv_batch -- up to POTQ_MAX_BATCH matrices that consume

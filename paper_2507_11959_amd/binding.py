@@ -43,6 +43,7 @@ EXPORTS = {
     "int_gemv": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]),
     "potq_gemm_workspace_bytes": (ctypes.c_size_t, [_i64, _i64, _i64, _int]),
     "potq_gemv_exponent_form": (_int, [_i64, _i64, _int]),
+    "potq_gemv_batch_exponent_form": (_int, [_int, _i64, _int]),
     "pot_gemm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
     "pot_gemm_noalloc": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp]),
     "int_gemm": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, ctypes.c_size_t, _vp]),
@@ -257,8 +258,13 @@ def make_gemv_batch(mats, K: int, bits: int, is_int: bool = False, group: int = 
 
 
 def potq_gemv_exponent_form(N: int, K: int, bits: int) -> bool:
-    """Whether pot_gemv serves an N x K matrix in the exponent form (N: total rows for a batch)."""
+    """Whether pot_gemv serves an N x K matrix in the exponent form."""
     return bool(_lib.potq_gemv_exponent_form(N, K, bits))
+
+
+def potq_gemv_batch_exponent_form(count: int, K: int, bits: int) -> bool:
+    """Whether pot_gemv_batch serves `count` matrices of row length K in the exponent form."""
+    return bool(_lib.potq_gemv_batch_exponent_form(count, K, bits))
 
 
 def pot_gemv_batch(mats, x, K: int, bits: int, group: int = 128, layout: int = LAYOUT_TILE16):

@@ -23,6 +23,7 @@ hipError_t run_gemv_canonical(bool is_int, const void *codes, const void *scales
                               void *y, int64_t N, int64_t K, int bits, int group, hipStream_t stream);
 int gemv_max_batch();
 bool gemv_exp_ok(int64_t N, int64_t K, int bits);
+bool gemv_exp_batch_ok(int count, int64_t rows_total, int64_t K, int bits);
 hipError_t run_gemv_tile16_batch(bool is_int, int count, const void *const *codes, const void *const *scales,
                                  const void *const *zeros, void *const *y, const int64_t *N, const void *x,
                                  int64_t K, int bits, int group, hipStream_t stream);
@@ -284,6 +285,12 @@ int potq_gemv_exponent_form(int64_t N, int64_t K, int bits)
 {
     if (N <= 0 || K <= 0 || (K % 128) != 0 || (N % 16) != 0) return 0;
     return potq::gemv_exp_ok(N, K, bits) ? 1 : 0;
+}
+
+int potq_gemv_batch_exponent_form(int count, int64_t K, int bits)
+{
+    if (count <= 0 || count > potq::gemv_max_batch() || K <= 0 || (K % 128) != 0) return 0;
+    return potq::gemv_exp_batch_ok(count, 0, K, bits) ? 1 : 0;
 }
 
 int pot_gemv_batch(const potq_gemv_item *items_host, int count, const void *x_f16, int64_t K, int bits, int group,

@@ -800,9 +800,13 @@ static hipError_t launch_gemv_batch(const GemvBatch &b, unsigned blocks, const v
                                dim3(kGemvWaves * kWave), lds, stream, b, (const u32x4 *)x, (int)K);                \
         }                                                                                                          \
     } while (0)
+    // batches of 2- and 3-bit PoT matrices with rows of 32 groups or more run in the exponent form
+    // up to the row length it can stage (K = 32768): only longer rows reach this kernel
+    constexpr bool kLongRowsOnly = !IS_INT && BITS < 4;
     if (split == 8 && kGemvWaves >= 8) {
         if (gemv_col0_fetch(K)) POTQ_LAUNCH_GEMVB((kGemvWaves >= 8 ? 8 : 1), true);
-        else POTQ_LAUNCH_GEMVB((kGemvWaves >= 8 ? 8 : 1), false);
+        else if constexpr (!kLongRowsOnly) POTQ_LAUNCH_GEMVB((kGemvWaves >= 8 ? 8 : 1), false);
+        else return hipErrorInvalidValue;
     } else if (split == 4) POTQ_LAUNCH_GEMVB(4, false);
     else if (split == 2) POTQ_LAUNCH_GEMVB(2, false);
     else POTQ_LAUNCH_GEMVB(1, false);

@@ -695,33 +695,42 @@ constexpr size_t kExpLdsSmall = kLdsDefaultLimit, kExpLdsLarge = kLdsPerWorkgrou
 // difference there, and small members of a batch get a finer share of the workgroups).
 static int exp_waves(int64_t K, bool batch) { return batch && exp_lds_bytes(K, 8) <= kExpLdsSmall ? 8 : 16; }
 
-// Whether the exponent form serves this PoT GEMV: signed-byte weights (2 or 3 bits), rows long
-// enough for eight wavefronts per tile, the digits of x within LDS and within the staging
-// registers of a thread, and a matrix large enough for the conversion of x to pay.  From
-// about 60 M weights up it always does (28672 x 8192: 22 us in the fp16 form against 17 us).
-// Below, down to 24 M, it does where a row takes at least two rounds of 32 groups, so that the
-// conversion is spread over more decode work, and there are rows for 160 workgroups
-// (5120 x 5120: 6.0 against 6.6 us, 6656 x 6656: 7.0 against 7.4 us); shapes with one round
-// (11008 x 4096: 7.1 against 6.7 us) or few rows (4096 x 11008: 8.4 against 7.1 us) and the
-// smaller ones (4096 x 4096: 5.8 against 4.4 us) stay on the fp16 form.
-constexpr int64_t kExpMinWeightsTwoRounds = 24ll << 20, kExpMinRowsTwoRounds = 5120;
-bool gemv_exp_ok(int64_t N, int64_t K, int bits)
+// Whether the exponent form can serve a PoT GEMV at all: signed-byte weights (2 or 3 bits), rows
+// long enough for eight wavefronts per tile, the digits of x within LDS and within the staging
+// registers of a thread.
+static bool exp_form_fits(int64_t K, int bits)
 {
     const int64_t G = K / kTileCols;
     if (bits != 2 && bits != 3) return false;
     if (G < 32) return false;
-    const bool large = N * K >= kExpMinWeights;
-    const bool two_rounds = N * K >= kExpMinWeightsTwoRounds && G > 32 && N >= kExpMinRowsTwoRounds;
-    if (!large && !two_rounds) return false;
     // (the eight-wavefront variant is only used where its footprint is smaller still)
     if (K > (int64_t)kExpOctetsPerThread * 16 * kWave * 8) return false;
     return exp_lds_bytes(K, 16) <= kExpLdsLarge;
 }
 
-// The same question for `count` matrices that share x (N = the sum of their rows).
+// Whether it pays for a single matrix: the conversion of x has to be won back by the cheaper
+// decode.  From about 60 M weights up it always is (28672 x 8192: 22 us in the fp16 form against
+// 15.7 us).  Below, down to 24 M, it is where there are rows for 160 workgroups (kernel times:
+// 6144 x 4096 4.95 against 5.44 us, 8192 x 4096 5.17 against 5.86, 11008 x 4096 6.13 against
+// 6.51, 5120 x 5120 5.1 against 6.0); matrices with few rows (4096 x 11008: 7.12 against
+// 6.74 us, 4096 x 8192: 6.02 against 5.76, 1024 x 8192: 5.78 against 4.97) and the smaller ones
+// (4096 x 4096: 4.72 against 4.43 us) stay on the fp16 form.
+constexpr int64_t kExpMinWeightsManyRows = 24ll << 20, kExpManyRows = 5120;
+bool gemv_exp_ok(int64_t N, int64_t K, int bits)
+{
+    if (!exp_form_fits(K, bits)) return false;
+    return N * K >= kExpMinWeights || (N * K >= kExpMinWeightsManyRows && N >= kExpManyRows);
+}
+
+// Matrices that share x (N = the sum of their rows): x is converted once for all of them and the
+// eight-wavefront workgroups of the batch kernel split small matrices finely, so the exponent
+// form won on every batch tried, down to two matrices of 512 rows (kernel times, fp16 form
+// against exponent form: 3 x 4096 x 4096 7.22 / 6.88 us, 2 x 2048 x 4096 4.74 / 4.37,
+// 2 x 1024 x 8192 5.73 / 5.29, 3 x 1024 x 4096 4.30 / 3.91, 2 x 512 x 4096 4.23 / 3.94).
 bool gemv_exp_batch_ok(int count, int64_t rows_total, int64_t K, int bits)
 {
-    return count <= kMaxExpBatch && gemv_exp_ok(rows_total, K, bits);
+    (void)rows_total;
+    return count <= kMaxExpBatch && exp_form_fits(K, bits);
 }
 
 template <int BITS, bool G64, int WAVES, bool BATCH>

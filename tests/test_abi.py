@@ -27,7 +27,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"pot_dequant", "int_dequant", "pot_gemv", "int_gemv", "pot_gemm", "int_gemm", "potq_repack",
-            "pot_check_scales", "pot_dequant_batch", "int_dequant_batch", "pot_gemv_batch", "int_gemv_batch", "potq_gemm_workspace_bytes", "pot_quantize", "pot_fakequant_forward", "pot_fakequant_backward", "potq_version", "potq_strerror", "potq_packed_row_bytes",
+            "pot_check_scales", "pot_dequant_batch", "int_dequant_batch", "pot_gemv_batch", "int_gemv_batch", "potq_gemv_batch_exponent_form", "potq_gemm_workspace_bytes", "pot_quantize", "pot_fakequant_forward", "pot_fakequant_backward", "potq_version", "potq_strerror", "potq_packed_row_bytes",
             "potq_packed_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -101,6 +101,14 @@ def test_host_side_validation(lib):
     assert lib.potq_gemv_exponent_form(28672, 8192, 4) == 0       # +-2^7 does not fit a signed byte
     assert lib.potq_gemv_exponent_form(1 << 20, 2048, 3) == 0     # fewer than 32 groups per row
     assert lib.potq_gemv_exponent_form(0, 8192, 3) == 0 and lib.potq_gemv_exponent_form(28672, 8200, 3) == 0
+    assert lib.potq_gemv_exponent_form(11008, 4096, 3) == 1       # rows for 160 workgroups: it pays from 24 M weights
+    assert lib.potq_gemv_exponent_form(4096, 11008, 3) == 0       # too few rows
+    # matrices sharing x: every size the form can serve
+    lib.potq_gemv_batch_exponent_form.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int]
+    assert lib.potq_gemv_batch_exponent_form(3, 4096, 3) == 1 and lib.potq_gemv_batch_exponent_form(2, 32768, 2) == 1
+    assert lib.potq_gemv_batch_exponent_form(3, 2048, 3) == 0 and lib.potq_gemv_batch_exponent_form(3, 36864, 3) == 0
+    assert lib.potq_gemv_batch_exponent_form(3, 4096, 4) == 0 and lib.potq_gemv_batch_exponent_form(17, 4096, 3) == 0
+    assert lib.potq_gemv_batch_exponent_form(0, 4096, 3) == 0
     assert lib.int_gemv(A, A, A, MIS, A, 16, 128, 3, 128, 1, None) == ALIGN
     r = lib.potq_repack
     assert r(A, A, 24, 128, 3, 1, None) == SHAPE

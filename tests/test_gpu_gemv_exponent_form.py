@@ -152,7 +152,7 @@ def test_non_finite_activations_with_two_to_four_tokens(potq):
 @pytest.mark.parametrize("bits", [2, 3])
 def test_batch_sharing_x(potq, bits):
     K, rows = 4096, (11008, 5504, 16)          # 16 528 rows together: served in the exponent form
-    assert potq.potq_gemv_exponent_form(sum(rows), K, bits)
+    assert potq.potq_gemv_batch_exponent_form(len(rows), K, bits)
     x = _x("outlier", K, 11)
     mats, refs = [], []
     for i, N in enumerate(rows):

@@ -67,7 +67,7 @@ def _check_rows(Y, rows, canonical, S, Z, X, K, bits, group, tag):
 @pytest.mark.parametrize("is_int", [False, True])
 @pytest.mark.parametrize("group", [64, 128])
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("K", [384, 1024, 2048, 4096, 8320])
+@pytest.mark.parametrize("K", [384, 1024, 2048, 4096, 8320, 36864])
 def test_gemv_and_batch_every_row_length_class(potq, K, bits, group, is_int):
     x = workloads.activations(7000 + K, 1, K)
     rows = [48, 16, 80]
@@ -83,7 +83,10 @@ def test_gemv_and_batch_every_row_length_class(potq, K, bits, group, is_int):
         want = oracle.gemm(packed, S, Z, x, K, bits, group)[0]
         e, nw, nfloor = rel_err(host_bits(y), want, K)
         assert e <= REL_TOL, (e, nw, nfloor)
-    assert np.array_equal(host_bits(single), host_bits(ys[0]))      # same arithmetic in the same order
+    # 2- and 3-bit PoT batches with 4096 <= K <= 32768 run in the exponent form, the small single
+    # matrix in the fp16 form; everywhere else both launches do the same arithmetic in the same order
+    if is_int or bits == 4 or K < 4096 or K > 32768:
+        assert np.array_equal(host_bits(single), host_bits(ys[0]))
 
 
 # Two to four tokens through the GEMV kernel (one activation vector per result column).

@@ -438,5 +438,8 @@ def test_gemv_rows_beyond_64_kib_of_lds(potq, K, is_int):
                                  dev(x[0]), K, bits)
     else:
         ys = potq.pot_gemv_batch([(tiled, dev(S)), (tiled, dev(S))], dev(x[0]), K, bits)
-    for y in ys:                              # the multi-matrix launch shares the kernel body
-        assert np.array_equal(host_bits(y), got)
+    for y in ys:
+        e, nw, nfloor = rel_err(host_bits(y), want, K)
+        assert e <= REL_TOL, (K, is_int, e, nw, nfloor)
+        if is_int or K > 32768:               # the multi-matrix launch shares the kernel body (PoT batches with
+            assert np.array_equal(host_bits(y), got)   # rows up to 32768 run in the exponent form instead)
