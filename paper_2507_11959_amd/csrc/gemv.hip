@@ -428,7 +428,8 @@ constexpr int kFewChunk = 4 * kFewSplit;              // scale groups per round
 constexpr int kFewDepth = 1;                          // rounds of codes requested ahead (two or three measured no better)
 
 template <int BITS, bool IS_INT, bool G64, int kFewWaves>
-__global__ __launch_bounds__(kFewWaves * kWave) void gemm_fewtok_kernel(
+__global__ __launch_bounds__(kFewWaves * kWave)
+__attribute__((amdgpu_waves_per_eu(kFewWaves == 16 ? 4 : 1, kFewWaves == 16 ? 4 : 8))) void gemm_fewtok_kernel(
     const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
     const uint16_t *__restrict__ X, uint16_t *__restrict__ Y, int M, int64_t N, int K)
 {
