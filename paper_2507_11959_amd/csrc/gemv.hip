@@ -498,8 +498,10 @@ __attribute__((amdgpu_waves_per_eu(kFewWaves == 16 ? 4 : 1, kFewWaves == 16 ? 4 
 #pragma unroll
         for (int i = 0; i < kFewPieces; ++i) {
             const int g = rnd * kFewChunk + xgrp[i];
-            const u32x4 v = *(const u32x4 *)(xsrc[i] + (int64_t)min(g, G - 1) * kTileCols);
-            xr[i] = (xtok[i] && g < G) ? v : u32x4{0u, 0u, 0u, 0u};   // tokens past M and groups past K count as zero
+            // tokens past M and groups past K count as zero, and are not requested
+            u32x4 v = u32x4{0u, 0u, 0u, 0u};
+            if (xtok[i] && g < G) v = *(const u32x4 *)(xsrc[i] + (int64_t)g * kTileCols);
+            xr[i] = v;
         }
     };
     // B operand of step j for lane (token r, k-slice t): group 4*part + t of the chunk
