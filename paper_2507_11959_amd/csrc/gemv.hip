@@ -524,7 +524,7 @@ __attribute__((amdgpu_waves_per_eu(kFewWaves == 16 ? 4 : 1, kFewWaves == 16 ? 4 
         __syncthreads();
         // X first: loads return in order, and the chunk (from L2) is wanted at the top of the next round,
         // before the codes (from HBM) are
-        fetch_x(round + 1);                             // past the end: clamped addresses, zeros, never used
+        fetch_x(round + 1);                             // past the end: nothing is requested
         Fetched nx;
         fetch(round + kFewDepth, nx);
         const Fetched &cur = q[0];
