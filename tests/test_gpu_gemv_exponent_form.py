@@ -165,6 +165,27 @@ def test_batch_sharing_x(potq, bits):
         assert e <= REL_TOL, (bits, e, nw, nfloor)
 
 
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("K", [4096, 5120, 16384])
+def test_small_batches_sharing_x(potq, K, bits, group):
+    """Matrices that share x take the exponent form at every size: the largest batch the entry
+    point accepts, of matrices of one to thirteen row tiles (fewer tiles than workgroups), and a
+    batch of two single-tile matrices."""
+    assert potq.potq_gemv_batch_exponent_form(16, K, bits)
+    x = _x("normal", K, 40 + bits)
+    for rows in ([16 * (1 + (5 * i) % 13) for i in range(16)], [16, 16]):
+        mats, refs = [], []
+        for i, N in enumerate(rows):
+            packed, S = workloads.pot_matrix(6, 60 + i + 20 * (group == 64), N, K, bits, group)
+            mats.append((potq.potq_repack(dev(packed), K, bits), dev(S)))
+            refs.append(oracle.gemm(packed, S, None, x[None, :], K, bits, group, nthreads=_threads())[0])
+        ys = potq.pot_gemv_batch(mats, dev(x), K, bits, group)
+        for i, (y, want) in enumerate(zip(ys, refs)):
+            e, nw, nfloor = rel_err(host_bits(y), want, K)
+            assert e <= REL_TOL, (K, bits, group, len(rows), i, e, nw, nfloor)
+
+
 def test_gemm_with_one_token_takes_the_same_path(potq):
     N, K, bits = 8192, 8192, 3
     packed, S = workloads.pot_matrix(6, 30, N, K, bits, 128)
