@@ -479,28 +479,24 @@ __attribute__((amdgpu_waves_per_eu(kFewWaves == 16 ? 4 : 1, kFewWaves == 16 ? 4 
     };
 
     // X pieces of this thread: piece p = tid + (threads) i is run (p % 4) + 4 (p/64 % 4) of group p/256
-    // for token (p/4) % 16 -- four consecutive lanes read 64 contiguous bytes of one token
-    const uint16_t *xsrc[kFewPieces];
-    int xslot[kFewPieces], xgrp[kFewPieces];
-    bool xtok[kFewPieces];
-#pragma unroll
-    for (int i = 0; i < kFewPieces; ++i) {
-        const int p = tid + kFewWaves * kWave * i;
-        const int jl = p & 3, c = (p >> 2) & 15, blk = p >> 6;
-        const int j = (blk & 3) * 4 + jl;
-        xgrp[i] = blk >> 2;
-        xtok[i] = c < M;
-        xsrc[i] = X + (int64_t)(xtok[i] ? c : 0) * K + 8 * j;
-        xslot[i] = (xgrp[i] * 16 + j) * 16 + ((c + 4 * jl) & 15);
-    }
+    // for token (p/4) % 16 -- four consecutive lanes read 64 contiguous bytes of one token.  The
+    // thread count is a multiple of 256, so token and run are the same for all pieces of a thread
+    // and piece i lies kFewWaves/4 groups after piece i - 1: one address, one slot, constant steps.
+    constexpr int kPieceGroups = kFewWaves / 4;         // groups between consecutive pieces of a thread
+    const int xrun = (wave & 3) * 4 + (tid & 3);        // run of 8 columns inside the group
+    const int xc = (tid >> 2) & 15;                     // token
+    const int xgrp0 = wave >> 2;                        // group of piece 0 inside the chunk
+    const bool xtok = xc < M;
+    const uint16_t *xsrc = X + (int64_t)(xtok ? xc : 0) * K + 8 * xrun;
+    const int xslot0 = (xgrp0 * 16 + xrun) * 16 + ((xc + 4 * (tid & 3)) & 15);
     u32x4 xr[kFewPieces];
     auto fetch_x = [&](int rnd) {
 #pragma unroll
         for (int i = 0; i < kFewPieces; ++i) {
-            const int g = rnd * kFewChunk + xgrp[i];
+            const int g = rnd * kFewChunk + xgrp0 + kPieceGroups * i;
             // tokens past M and groups past K count as zero, and are not requested
             u32x4 v = u32x4{0u, 0u, 0u, 0u};
-            if (xtok[i] && g < G) v = *(const u32x4 *)(xsrc[i] + (int64_t)g * kTileCols);
+            if (xtok && g < G) v = *(const u32x4 *)(xsrc + (int64_t)g * kTileCols);
             xr[i] = v;
         }
     };
@@ -520,7 +516,7 @@ __attribute__((amdgpu_waves_per_eu(kFewWaves == 16 ? 4 : 1, kFewWaves == 16 ? 4 
     for (int round = 0; round < rounds; ++round) {
         if (round) __syncthreads();                     // the previous chunk has been consumed
 #pragma unroll
-        for (int i = 0; i < kFewPieces; ++i) smem[xslot[i]] = xr[i];
+        for (int i = 0; i < kFewPieces; ++i) smem[xslot0 + kPieceGroups * 256 * i] = xr[i];
         __syncthreads();
         // X first: loads return in order, and the chunk (from L2) is wanted at the top of the next round,
         // before the codes (from HBM) are
@@ -584,13 +580,18 @@ static void launch_gemm_fewtok_cfg(const void *codes, const void *scales, const 
                        (int)K);
 }
 
-// Tall matrices take 16 wavefronts per workgroup (four row tiles share every X chunk: 13.3 us
-// against 15.8 us on 13824 x 5120), the others 8 (more workgroups: 9.2 us against 12.2 us on 5120 x 5120).
+// Workgroups of 16 wavefronts (four row tiles share every X chunk, one workgroup per compute unit)
+// or of 8 (two row tiles, two workgroups per compute unit): either way the chip takes 1024 row
+// tiles at a time.  Sixteen are faster while the last such round is more than half full (11008 x
+// 4096: 8.8 against 11.0 us, 13824 x 5120: 11.9 / 14.5, 28672 x 8192: 31.0 / 35.0); when it is not,
+// they leave half of the compute units idle in it and eight win (8192 x 8192: 11.6 against 13.9 us,
+// 5120 x 5120: 8.1 / 10.8, 17920 x 6656: 25.0 / 27.0, 24576 x 4096: 15.8 / 17.4).
 template <int BITS, bool IS_INT>
 static void launch_gemm_fewtok(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                                int64_t M, int64_t N, int64_t K, int group, hipStream_t stream)
 {
-    const bool tall = N / kTileRows >= 768;
+    const int64_t in_last_round = (N / kTileRows) % 1024;
+    const bool tall = in_last_round == 0 || in_last_round > 512;
     if (group == 64) {
         if (tall) launch_gemm_fewtok_cfg<BITS, IS_INT, true, 16>(codes, scales, zeros, X, Y, M, N, K, stream);
         else launch_gemm_fewtok_cfg<BITS, IS_INT, true, 8>(codes, scales, zeros, X, Y, M, N, K, stream);
