@@ -586,12 +586,17 @@ static void launch_gemm_fewtok_cfg(const void *codes, const void *scales, const 
 // 4096: 8.8 against 11.0 us, 13824 x 5120: 11.9 / 14.5, 28672 x 8192: 31.0 / 35.0); when it is not,
 // they leave half of the compute units idle in it and eight win (8192 x 8192: 11.6 against 13.9 us,
 // 5120 x 5120: 8.1 / 10.8, 17920 x 6656: 25.0 / 27.0, 24576 x 4096: 15.8 / 17.4).
+static bool fewtok_sixteen_wavefronts(int64_t N)
+{
+    const int64_t in_last_round = (N / kTileRows) % 1024;
+    return in_last_round == 0 || in_last_round > 512;
+}
+
 template <int BITS, bool IS_INT>
 static void launch_gemm_fewtok(const void *codes, const void *scales, const void *zeros, const void *X, void *Y,
                                int64_t M, int64_t N, int64_t K, int group, hipStream_t stream)
 {
-    const int64_t in_last_round = (N / kTileRows) % 1024;
-    const bool tall = in_last_round == 0 || in_last_round > 512;
+    const bool tall = fewtok_sixteen_wavefronts(N);
     if (group == 64) {
         if (tall) launch_gemm_fewtok_cfg<BITS, IS_INT, true, 16>(codes, scales, zeros, X, Y, M, N, K, stream);
         else launch_gemm_fewtok_cfg<BITS, IS_INT, true, 8>(codes, scales, zeros, X, Y, M, N, K, stream);
@@ -632,14 +637,15 @@ static size_t gemv_multi_lds_bytes(int64_t K, int mt)
 }
 
 // Whether run_gemv_multi serves this shape: 2..4 tokens, group 128, rows long enough for eight
-// wavefronts per tile, the padded vectors within 64 KB of LDS, and not four vectors on a tall
-// matrix (13824 x 5120: 13.7 us against 12.3 us for the few-token kernel; elsewhere the GEMV
-// kernel measured 1.1-1.45x faster than the few-token kernel at two to four tokens).
+// wavefronts per tile, the padded vectors within 64 KB of LDS, and not three or four vectors
+// where the few-token kernel runs its sixteen-wavefront workgroups (13824 x 5120 at four tokens:
+// 13.1 us against 11.4 us for the few-token kernel, 11008 x 4096: 9.8 against 8.8; elsewhere
+// the GEMV kernel measured 1.1-1.8x faster than the few-token kernel at two to four tokens).
 bool gemv_multi_ok(int64_t M, int64_t N, int64_t K, int group)
 {
     const int64_t G = K / kTileCols;
     if (M < 2 || M > 4 || group != 128 || kGemvWaves != 8 || G < 32) return false;
-    if (M > 2 && N / kTileRows >= 768) return false;
+    if (M > 2 && fewtok_sixteen_wavefronts(N)) return false;
     return gemv_multi_lds_bytes(K, M <= 2 ? 2 : 4) <= 64 * 1024;
 }
 
