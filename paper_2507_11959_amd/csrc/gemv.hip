@@ -75,7 +75,8 @@ constexpr int kGemvWaves = 8;
 // lane group t takes groups 4p + t, 4p + t + 4S, ...  Long rows want S = 8 (all
 // of K in flight at once), tall matrices want S = 1 or 2 (long-lived wavefronts,
 // no cross-wavefront sums).  The codes of the next round are requested before
-// the current one is expanded, and the first request goes out before x is staged.
+// the current one is expanded; the first request goes out right after the request for x and
+// before x is written to LDS.
 // MT > 1: the same kernel for MT activation vectors at once (a GEMM with two to four tokens: rows
 // m < tokens of x, K apart; results y[m * ystride + n]).  Vector m is the B operand of column m, so the
 // matrix is decoded once and every vector costs only LDS space: column m of the MFMA result is its y.

@@ -198,7 +198,8 @@ __device__ __forceinline__ void stage_digits(const u32x4 xv, u32x4 *__restrict__
 // of a slot split the scale groups of its tile (wavefront p, lane group t: groups 4p + t,
 // 4p + t + 32, ...).  The codes of the next step -- the next round of the tile or the first round
 // of the next tile -- are requested before the current ones are expanded (requests two or three
-// steps ahead measured slower), and the very first request goes out before x is staged.
+// steps ahead measured slower); the very first request goes out right after the request for x,
+// before x is converted.
 template <int BITS, bool G64, int WAVES>
 __device__ __forceinline__ void gemv_exp_body(const u32x4 *__restrict__ codes, const uint16_t *__restrict__ scales,
                                               const u32x4 *__restrict__ x, uint16_t *__restrict__ y, int K,
